@@ -1,0 +1,104 @@
+"""CPU oracle (scalar fp64 C) for the batched RNNLM step.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+package; the GPU library and its Python binding never do.  The arithmetic lives in
+rnnlm_oracle.c (see its header for what is computed and from which passages); this file
+compiles it with gcc and marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rnnlm_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile rnnlm_oracle.c -> liboracle.so (gcc -O2, OpenMP over rows, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        P = ctypes.c_void_p
+        I = ctypes.c_int
+        lib.oracle_dedup.argtypes = [P, I, P, P]
+        lib.oracle_dedup.restype = I
+        lib.oracle_step.argtypes = [I, I, I, I, I, P, P, P, P, P, P, P, P, P, P, P, P, I]
+        lib.oracle_step.restype = I
+        lib.oracle_max_threads.restype = I
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def dedup(keys: np.ndarray):
+    """keys u64[N] -> (n_unique, rep i32[n_unique], inverse i32[N]), first-appearance order."""
+    keys = _c(keys, np.uint64)
+    N = keys.shape[0]
+    rep = np.zeros(max(N, 1), dtype=np.int32)
+    inverse = np.zeros(max(N, 1), dtype=np.int32)
+    U = _load().oracle_dedup(_ptr(keys), N, _ptr(rep), _ptr(inverse))
+    return U, rep[:U].copy(), inverse[:N].copy()
+
+
+def step(model: dict, prev, h_in, query, row_of_query=None, want_full: bool = False,
+         num_threads: int = 0) -> dict:
+    """One step.  model: dict with float32 U[V,H], W[H,H], O[H,V], bias[V] or None.
+    Returns float64 h_out[B,H], lse[B], logprob[N,K] (and full_logp[B,V] if want_full)."""
+    U = _c(model["U"], np.float32)
+    W = _c(model["W"], np.float32)
+    O = _c(model["O"], np.float32)
+    bias = model.get("bias")
+    bias = None if bias is None else _c(bias, np.float32)
+    V, H = U.shape
+    assert W.shape == (H, H) and O.shape == (H, V)
+    prev = _c(prev, np.int32)
+    h_in = _c(h_in, np.float32)
+    query = _c(query, np.int32)
+    B = prev.shape[0]
+    N, K = query.shape
+    assert h_in.shape == (B, H)
+    if row_of_query is not None:
+        row_of_query = _c(row_of_query, np.int32)
+        assert row_of_query.shape == (N,)
+    else:
+        assert N == B
+    h_out = np.zeros((B, H), dtype=np.float64)
+    lse = np.zeros(B, dtype=np.float64)
+    logprob = np.zeros((N, K), dtype=np.float64)
+    full = np.zeros((B, V), dtype=np.float64) if want_full else None
+    rc = _load().oracle_step(V, H, B, K, N, _ptr(U), _ptr(W), _ptr(O), _ptr(bias),
+                             _ptr(prev), _ptr(h_in), _ptr(query), _ptr(row_of_query),
+                             _ptr(h_out), _ptr(lse), _ptr(logprob), _ptr(full), num_threads)
+    if rc != 0:
+        raise ValueError("oracle_step: index out of range" if rc == -1 else "oracle_step: out of memory")
+    out = {"h_out": h_out, "lse": lse, "logprob": logprob}
+    if want_full:
+        out["full_logp"] = full
+    return out
