@@ -1,0 +1,174 @@
+/*
+ * librnnlm -- batched RNNLM scoring step for network search, on one MI355X (gfx950).
+ *
+ * The search hands over, for every active hypothesis, a 64-bit history id, the previous
+ * word, the previous hidden vector and the words it wants scored.  The library groups
+ * identical histories, computes each distinct history once, and returns only the
+ * log-probabilities that were asked for.  (The paper's RnnlmProb(w, c) -> (p, c') with a
+ * cache of already computed contexts -- Section 4, Table 1 -- as one batched device step;
+ * the full-vocabulary normalisation is the cost Section 2.1 describes.)
+ *
+ * Conventions
+ *   - Plain C ABI.  Every function returns an rnnlm_status (0 = OK, < 0 = error) except
+ *     where stated; nothing throws or aborts.
+ *   - rnnlm_load takes HOST pointers and copies; the caller keeps its buffers.
+ *   - rnnlm_dedup / rnnlm_step / rnnlm_step_dedup take DEVICE pointers owned by the caller
+ *     and are asynchronous on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  No call here synchronises, allocates or frees device memory
+ *     except rnnlm_load, rnnlm_free and rnnlm_last_error.
+ *   - float / int32 / uint64 arrays are dense, row-major, naturally aligned; `h_in` and
+ *     `h_out` rows must start on 16-byte boundaries when H is a multiple of 4 (any
+ *     allocator's base alignment gives this).
+ *   - A model may be used from one stream at a time (its scratch buffers are shared).
+ *   - Host-checkable mistakes (NULL, negative sizes, B > max_B, short workspace) return
+ *     before anything is launched.  Mistakes only visible on the device (a word id outside
+ *     [0,V), a row index outside [0,B)) never cause an out-of-bounds access: the affected
+ *     outputs become NaN and a sticky flag is raised, read by rnnlm_last_error.
+ */
+#ifndef RNNLM_H_
+#define RNNLM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rnnlm_model rnnlm_model;       /* opaque, owned by the library */
+
+enum rnnlm_dtype { RNNLM_F32 = 0, RNNLM_BF16 = 1 };
+
+enum rnnlm_status {
+    RNNLM_OK = 0,
+    RNNLM_EINVAL = -1,        /* NULL pointer, bad size, unknown dtype or option */
+    RNNLM_ENOMEM = -2,        /* device or host allocation failed */
+    RNNLM_EDEVICE = -3,       /* a HIP call failed */
+    RNNLM_ERANGE = -4,        /* B or N beyond what the model was loaded for */
+    RNNLM_EWORKSPACE = -5     /* workspace too small or misaligned */
+};
+
+/* Bits of the sticky device flag returned by rnnlm_last_error. */
+enum rnnlm_device_flag {
+    RNNLM_FLAG_BAD_PREV_WORD = 1,     /* prev_word outside [0,V): that row's outputs are NaN */
+    RNNLM_FLAG_BAD_QUERY_WORD = 2,    /* query_word outside [0,V): that logprob is NaN */
+    RNNLM_FLAG_BAD_ROW = 4            /* row_of_query outside [0,B): that query's logprobs are NaN */
+};
+
+/* Tunables for rnnlm_set_option. */
+enum rnnlm_option {
+    /* How the log-sum-exp over the vocabulary is taken (same mathematical result):
+     * 0 = automatic (default): a fixed offset derived at load time from a bound on every
+     *     logit when that bound is tight enough for fp32, else a running maximum;
+     * 1 = always the running maximum;  2 = always the fixed offset (EINVAL if unusable). */
+    RNNLM_OPT_LSE_MODE = 1,
+    /* Which output-projection kernel: 0 = automatic (default), 1 = the plain any-shape
+     * kernel, 2 = the LDS-staged kernel with the hidden block held in registers
+     * (EINVAL if the model's shape does not allow it). */
+    RNNLM_OPT_OUTPROJ_KERNEL = 2
+};
+
+/* Human-readable text for a status code; never NULL; static storage. */
+const char *rnnlm_strerror(int status);
+
+/*
+ * Load a model: V words, H hidden units (the recurrent LM of Section 2).
+ *   dtype  RNNLM_F32: U, W, O are float.  RNNLM_BF16: they are uint16 bfloat16 bit
+ *          patterns; products are accumulated in fp32 on the matrix cores.
+ *   U      [V][H]  row w = input embedding of word w.
+ *   W      [H][H]  W[j][i] multiplies h_in[i] in the pre-activation of unit j.
+ *   O      [H][V]  output weights, z[v] = bias[v] + sum_j O[j][v] h'[j].
+ *   bias   [V] float, or NULL for zero.
+ *   max_B  largest number of rows (and of raw queries) any later call will pass.
+ * All five are HOST pointers; the library uploads them and re-lays O out as [V][H].
+ * *out receives the handle.  Synchronous.
+ */
+int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void *O,
+               const float *bias_or_null, int max_B, rnnlm_model **out);
+
+/* Release a model and its device memory.  NULL is a no-op.  Synchronises the device. */
+int rnnlm_free(rnnlm_model *model);
+
+/* Set a tunable (see rnnlm_option).  Host-side only; affects later calls. */
+int rnnlm_set_option(rnnlm_model *model, int option, int value);
+
+/* Wait for `hip_stream`, then return and clear the sticky rnnlm_device_flag bits in
+ * *flags.  Returns a status. */
+int rnnlm_last_error(rnnlm_model *model, void *hip_stream, int *flags);
+
+/* Bytes of device workspace rnnlm_dedup / rnnlm_step_dedup need for N raw queries
+ * (returns 0 for N <= 0).  The workspace must be 16-byte aligned. */
+size_t rnnlm_dedup_workspace_bytes(int N);
+
+/*
+ * Group identical history ids (the cache lookup of Table 1, steps 1-3, for a whole batch:
+ * a history seen before is not computed again; new ones are numbered in order of first
+ * appearance, step 10).
+ *   history_ids  dev u64[N]   any 64-bit value is an ordinary key (Section 3.2 packs a
+ *                             context index and a small-LM index into one number).
+ *   rep          dev i32[N]   out: rep[u] = smallest n holding the u-th distinct id;
+ *                             ascending; only the first *n_unique entries are written.
+ *   inverse      dev i32[N]   out: inverse[n] = u such that history_ids[rep[u]] == history_ids[n].
+ *   n_unique     dev i32[1]   out: number of distinct ids.
+ * The result is unique, hence bit-exact and run-to-run deterministic.  N = 0 writes
+ * *n_unique = 0.  workspace: dev, rnnlm_dedup_workspace_bytes(N) bytes, contents undefined
+ * before and after.
+ */
+int rnnlm_dedup(const uint64_t *history_ids, int N, int32_t *rep, int32_t *inverse,
+                int32_t *n_unique, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Score one step for B distinct histories and N raw queries (ComputeRnnlm of Table 1,
+ * step 6, batched):
+ *   h_out[b][j]   = sigmoid(U[prev_word[b]][j] + sum_i W[j][i] h_in[b][i])
+ *   logprob[n][k] = z_r[query_word[n][k]] - log sum_v exp z_r[v],   r = row_of_query[n],
+ *                   z_r[v] = bias[v] + sum_j O[j][v] h_out[r][j]
+ *   prev_word     dev i32[B]
+ *   h_in          dev f32[B][H]   any finite values; all-zero rows are the utterance start
+ *   query_word    dev i32[N][K]
+ *   row_of_query  dev i32[N] with values in [0,B), or NULL meaning N == B and row n
+ *   h_out         dev f32[B][H]   out; must not overlap h_in
+ *   logprob       dev f32[N][K]   out
+ * The B x V logits never leave the chip; only N x K floats are written besides h_out.
+ * B = 0 or N = 0 or K = 0 is a valid no-op for the corresponding outputs.
+ */
+int rnnlm_step(const rnnlm_model *model, int B, int K,
+               const int32_t *prev_word, const float *h_in,
+               const int32_t *query_word, const int32_t *row_of_query_or_null, int N,
+               float *h_out, float *logprob, void *hip_stream);
+
+/*
+ * The whole path in one call, with no host round trip between grouping and scoring
+ * (RnnlmProb of Table 1 for N (history, words) lookups at once): rnnlm_dedup on
+ * history_ids, then rnnlm_step on the distinct histories only, each taken from its first
+ * occurrence, with every raw query answered from its group's row.
+ *   history_ids   dev u64[N]
+ *   prev_word     dev i32[N]      per RAW query (equal ids must carry equal histories)
+ *   h_in          dev f32[N][H]   per RAW query
+ *   query_word    dev i32[N][K]
+ *   rep, inverse, n_unique        out, as rnnlm_dedup
+ *   h_out         dev f32[N][H]   out: row u < *n_unique = updated hidden vector of the
+ *                                 u-th distinct history; rows beyond are left untouched
+ *   logprob       dev f32[N][K]   out
+ * Requires N <= max_B.
+ */
+int rnnlm_step_dedup(const rnnlm_model *model, int N, int K,
+                     const uint64_t *history_ids, const int32_t *prev_word, const float *h_in,
+                     const int32_t *query_word,
+                     int32_t *rep, int32_t *inverse, int32_t *n_unique,
+                     float *h_out, float *logprob,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Measurement aid: run only the output-projection + log-sum-exp kernel on the hidden
+ * block left in the model by the latest rnnlm_step/rnnlm_step_dedup (B rows), `repeats`
+ * times back to back on `hip_stream`, bracketed by HIP events on that stream, and return
+ * the mean time of one launch in milliseconds in *ms_per_launch.  Synchronises the stream.
+ */
+int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream,
+                       float *ms_per_launch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNNLM_H_ */

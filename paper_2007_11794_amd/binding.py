@@ -1,0 +1,209 @@
+"""ctypes binding of librnnlm.so: argument marshalling only.
+
+Every function mirrors the C entry point of the same name (include/rnnlm.h).  Device
+buffers are torch tensors (their data_ptr() is passed through); the stream is torch's
+current stream unless one is given.  If the library has not been built this module raises
+at import of the symbol table -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+RNNLM_F32, RNNLM_BF16 = 0, 1
+FLAG_BAD_PREV_WORD, FLAG_BAD_QUERY_WORD, FLAG_BAD_ROW = 1, 2, 4
+OPT_LSE_MODE, OPT_OUTPROJ_KERNEL = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "librnnlm.so")
+_lib = None
+
+EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rnnlm_last_error",
+           "rnnlm_dedup_workspace_bytes", "rnnlm_dedup", "rnnlm_step", "rnnlm_step_dedup",
+           "rnnlm_time_outproj"]
+
+
+class RnnlmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, rnnlm_strerror(status), status))
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """Load librnnlm.so (built in-tree by paper_2007_11794_amd.build); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("librnnlm.so is not built: run `python -m paper_2007_11794_amd.build` "
+                              "(or __graft_entry__.build()); there is no fallback implementation")
+        L = ctypes.CDLL(_LIB_PATH)
+        P, I, Z = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.rnnlm_strerror.argtypes = [I]
+        L.rnnlm_strerror.restype = ctypes.c_char_p
+        L.rnnlm_load.argtypes = [I, I, I, P, P, P, P, I, ctypes.POINTER(P)]
+        L.rnnlm_load.restype = I
+        L.rnnlm_free.argtypes = [P]
+        L.rnnlm_free.restype = I
+        L.rnnlm_set_option.argtypes = [P, I, I]
+        L.rnnlm_set_option.restype = I
+        L.rnnlm_last_error.argtypes = [P, P, ctypes.POINTER(I)]
+        L.rnnlm_last_error.restype = I
+        L.rnnlm_dedup_workspace_bytes.argtypes = [I]
+        L.rnnlm_dedup_workspace_bytes.restype = Z
+        L.rnnlm_dedup.argtypes = [P, I, P, P, P, P, Z, P]
+        L.rnnlm_dedup.restype = I
+        L.rnnlm_step.argtypes = [P, I, I, P, P, P, P, I, P, P, P]
+        L.rnnlm_step.restype = I
+        L.rnnlm_step_dedup.argtypes = [P, I, I, P, P, P, P, P, P, P, P, P, P, Z, P]
+        L.rnnlm_step_dedup.restype = I
+        L.rnnlm_time_outproj.argtypes = [P, I, I, P, ctypes.POINTER(ctypes.c_float)]
+        L.rnnlm_time_outproj.restype = I
+        _lib = L
+    return _lib
+
+
+def rnnlm_strerror(status: int) -> str:
+    return lib().rnnlm_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise RnnlmError(status, where)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dev(t, dtype, name):
+    """Device pointer of a contiguous CUDA tensor of the given torch dtype (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError("%s must be a contiguous device tensor of dtype %s" % (name, dtype))
+    return t.data_ptr() or None
+
+
+def rnnlm_dedup_workspace_bytes(N: int) -> int:
+    return int(lib().rnnlm_dedup_workspace_bytes(int(N)))
+
+
+class RnnlmModel:
+    """Handle returned by rnnlm_load; frees the device copy when closed or collected."""
+
+    def __init__(self, handle: int, V: int, H: int, dtype: int, max_B: int):
+        self._h = handle
+        self.V, self.H, self.dtype, self.max_B = V, H, dtype, max_B
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("model already freed")
+        return self._h
+
+    def set_option(self, option: int, value: int):
+        _check(lib().rnnlm_set_option(self.handle, int(option), int(value)), "rnnlm_set_option")
+
+    def last_error(self, stream=None) -> int:
+        f = ctypes.c_int(0)
+        _check(lib().rnnlm_last_error(self.handle, _stream(stream), ctypes.byref(f)), "rnnlm_last_error")
+        return f.value
+
+    def time_outproj(self, B: int, repeats: int, stream=None) -> float:
+        ms = ctypes.c_float(0)
+        _check(lib().rnnlm_time_outproj(self.handle, int(B), int(repeats), _stream(stream),
+                                        ctypes.byref(ms)), "rnnlm_time_outproj")
+        return ms.value
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, None
+            _check(lib().rnnlm_free(h), "rnnlm_free")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def rnnlm_load(V: int, H: int, dtype: int, U: np.ndarray, W: np.ndarray, O: np.ndarray,
+               bias: Optional[np.ndarray], max_B: int) -> RnnlmModel:
+    """Host numpy arrays in: float32 for RNNLM_F32, uint16 bfloat16 bit patterns for RNNLM_BF16."""
+    want = np.float32 if dtype == RNNLM_F32 else np.uint16
+    arrs = []
+    for name, a, shape in (("U", U, (V, H)), ("W", W, (H, H)), ("O", O, (H, V))):
+        a = np.ascontiguousarray(a)
+        if a.dtype != want or a.shape != shape:
+            raise TypeError("%s must be %s of shape %s" % (name, want.__name__, shape))
+        arrs.append(a)
+    b = None
+    if bias is not None:
+        b = np.ascontiguousarray(bias, dtype=np.float32)
+        if b.shape != (V,):
+            raise TypeError("bias must have shape (V,)")
+    out = ctypes.c_void_p()
+    st = lib().rnnlm_load(V, H, dtype, arrs[0].ctypes.data, arrs[1].ctypes.data, arrs[2].ctypes.data,
+                          b.ctypes.data if b is not None else None, int(max_B), ctypes.byref(out))
+    _check(st, "rnnlm_load")
+    return RnnlmModel(out.value, V, H, dtype, int(max_B))
+
+
+def rnnlm_dedup(history_ids, rep, inverse, n_unique, workspace, stream=None):
+    """history_ids: int64 device tensor holding the u64 bit patterns [N]; rep, inverse int32 [N];
+    n_unique int32 [1]; workspace uint8 device tensor of rnnlm_dedup_workspace_bytes(N)."""
+    import torch
+    N = int(history_ids.shape[0])
+    _check(lib().rnnlm_dedup(_dev(history_ids, torch.int64, "history_ids"), N,
+                             _dev(rep, torch.int32, "rep"), _dev(inverse, torch.int32, "inverse"),
+                             _dev(n_unique, torch.int32, "n_unique"),
+                             _dev(workspace, torch.uint8, "workspace"),
+                             0 if workspace is None else workspace.numel(), _stream(stream)), "rnnlm_dedup")
+
+
+def rnnlm_step(model: RnnlmModel, prev_word, h_in, query_word, h_out, logprob,
+               row_of_query=None, stream=None):
+    import torch
+    B = int(prev_word.shape[0])
+    N = int(query_word.shape[0])
+    K = int(query_word.shape[1]) if query_word.dim() == 2 else 0
+    if h_in.shape != (B, model.H) or h_out.shape != (B, model.H) or logprob.shape != (N, K):
+        raise TypeError("shape mismatch")
+    if row_of_query is not None and row_of_query.shape != (N,):
+        raise TypeError("row_of_query must have shape (N,)")
+    _check(lib().rnnlm_step(model.handle, B, K, _dev(prev_word, torch.int32, "prev_word"),
+                            _dev(h_in, torch.float32, "h_in"), _dev(query_word, torch.int32, "query_word"),
+                            _dev(row_of_query, torch.int32, "row_of_query"), N,
+                            _dev(h_out, torch.float32, "h_out"), _dev(logprob, torch.float32, "logprob"),
+                            _stream(stream)), "rnnlm_step")
+
+
+def rnnlm_step_dedup(model: RnnlmModel, history_ids, prev_word, h_in, query_word, rep, inverse, n_unique,
+                     h_out, logprob, workspace, stream=None):
+    import torch
+    N = int(history_ids.shape[0])
+    K = int(query_word.shape[1]) if query_word.dim() == 2 else 0
+    if (prev_word.shape != (N,) or h_in.shape != (N, model.H) or h_out.shape != (N, model.H)
+            or query_word.shape[0] != N or logprob.shape != (N, K)
+            or rep.shape != (N,) or inverse.shape != (N,)):
+        raise TypeError("shape mismatch")
+    _check(lib().rnnlm_step_dedup(model.handle, N, K, _dev(history_ids, torch.int64, "history_ids"),
+                                  _dev(prev_word, torch.int32, "prev_word"), _dev(h_in, torch.float32, "h_in"),
+                                  _dev(query_word, torch.int32, "query_word"), _dev(rep, torch.int32, "rep"),
+                                  _dev(inverse, torch.int32, "inverse"), _dev(n_unique, torch.int32, "n_unique"),
+                                  _dev(h_out, torch.float32, "h_out"), _dev(logprob, torch.float32, "logprob"),
+                                  _dev(workspace, torch.uint8, "workspace"),
+                                  0 if workspace is None else workspace.numel(), _stream(stream)),
+           "rnnlm_step_dedup")

@@ -1,0 +1,301 @@
+// C ABI of librnnlm: argument checks, model set-up, and the order of kernel launches.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "rnnlm_internal.h"
+
+using namespace rnnlm;
+
+namespace {
+
+inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) {                        \
+            status = (e_ == hipErrorOutOfMemory) ? RNNLM_ENOMEM : RNNLM_EDEVICE; \
+            goto fail;                                 \
+        }                                              \
+    } while (0)
+
+size_t elem_size(int dtype) { return dtype == RNNLM_BF16 ? 2 : 4; }
+
+bool use_fixed_offset(const rnnlm_model *m) {
+    if (m->lse_mode == 1) return false;
+    if (m->lse_mode == 2) return true;
+    return m->fixed_ok != 0;
+}
+
+void free_dev(rnnlm_model *m) {
+    ModelDev &d = m->dev;
+    (void)hipFree(const_cast<void *>(d.U));
+    (void)hipFree(const_cast<void *>(d.W));
+    (void)hipFree(const_cast<void *>(d.Ot));
+    (void)hipFree(const_cast<float *>(d.half_rowsum_W));
+    (void)hipFree(const_cast<float *>(d.bias));
+    (void)hipFree(const_cast<float *>(d.half_colsum_O));
+    (void)hipFree(const_cast<float *>(d.cvec));
+    (void)hipFree(const_cast<float *>(d.cvec_fixed));
+    (void)hipFree(d.d);
+    (void)hipFree(d.part);
+    (void)hipFree(d.flag);
+    if (m->ev0) (void)hipEventDestroy(m->ev0);
+    if (m->ev1) (void)hipEventDestroy(m->ev1);
+}
+
+double widen_host(const void *p, size_t i, int dtype) {
+    if (dtype == RNNLM_BF16) {
+        uint32_t u = (uint32_t)static_cast<const uint16_t *>(p)[i] << 16;
+        float f;
+        memcpy(&f, &u, 4);
+        return (double)f;
+    }
+    return (double)static_cast<const float *>(p)[i];
+}
+
+int check_step_args(const rnnlm_model *model, int B, int K, int N) {
+    if (!model) return RNNLM_EINVAL;
+    if (B < 0 || K < 0 || N < 0) return RNNLM_EINVAL;
+    if (B > model->max_B || N > model->max_B) return RNNLM_ERANGE;
+    return RNNLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rnnlm_strerror(int status) {
+    switch (status) {
+        case RNNLM_OK: return "ok";
+        case RNNLM_EINVAL: return "invalid argument";
+        case RNNLM_ENOMEM: return "out of memory";
+        case RNNLM_EDEVICE: return "HIP call failed";
+        case RNNLM_ERANGE: return "batch larger than the model was loaded for";
+        case RNNLM_EWORKSPACE: return "workspace too small or misaligned";
+        default: return "unknown status";
+    }
+}
+
+int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void *O,
+               const float *bias_or_null, int max_B, rnnlm_model **out) {
+    if (!out) return RNNLM_EINVAL;
+    *out = nullptr;
+    if (!U || !W || !O) return RNNLM_EINVAL;
+    if (V <= 0 || H <= 0 || max_B <= 0) return RNNLM_EINVAL;
+    if (dtype != RNNLM_F32 && dtype != RNNLM_BF16) return RNNLM_EINVAL;
+    if ((long long)V > (1ll << 30) || H > (1 << 16) || max_B > (1 << 24)) return RNNLM_EINVAL;
+
+    rnnlm_model *m = new (std::nothrow) rnnlm_model();
+    if (!m) return RNNLM_ENOMEM;
+    memset(m, 0, sizeof(*m));
+    int status = RNNLM_OK;
+    const size_t es = elem_size(dtype);
+    // bf16 models pad to at least 128 so that every Hp <= 512 fits the staged kernel
+    const int Hp = (dtype == RNNLM_BF16 && H < 128) ? 128 : round_up(H, 64), Vp = round_up(V, 256);
+    const int max_Bp = round_up(max_B, 256);
+    ModelDev &d = m->dev;
+    d.V = V; d.H = H; d.Hp = Hp; d.Vp = Vp; d.dtype = dtype;
+    m->max_B = max_B; m->max_Bp = max_Bp;
+    void *O_stage = nullptr;
+    float *bias_stage = nullptr, *upper = nullptr, *lower = nullptr;
+    std::vector<float> hu, hl, hrs;
+    float max_upper = -INFINITY, min_lower = INFINITY;
+
+    void *p;
+    HIP_TRY(hipMalloc(&p, (size_t)V * Hp * es)); d.U = p;
+    HIP_TRY(hipMalloc(&p, (size_t)Hp * Hp * es)); d.W = p;
+    HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * es)); d.Ot = p;
+    HIP_TRY(hipMalloc(&p, (size_t)Hp * 4)); d.half_rowsum_W = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.bias = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.half_colsum_O = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec_fixed = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.d = p;
+    HIP_TRY(hipMalloc(&p, (size_t)max_Bp * kMaxSplits * sizeof(float2))); d.part = static_cast<float2 *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
+    HIP_TRY(hipMemset(d.d, 0, (size_t)max_Bp * Hp * es));
+    HIP_TRY(hipMemset(d.part, 0, (size_t)max_Bp * kMaxSplits * sizeof(float2)));
+    HIP_TRY(hipMemset(d.flag, 0, 4));
+    HIP_TRY(hipEventCreate(&m->ev0));
+    HIP_TRY(hipEventCreate(&m->ev1));
+
+    // U and W: zero-padded to Hp columns (and W to Hp rows)
+    HIP_TRY(hipMemset(const_cast<void *>(d.U), 0, (size_t)V * Hp * es));
+    HIP_TRY(hipMemset(const_cast<void *>(d.W), 0, (size_t)Hp * Hp * es));
+    HIP_TRY(hipMemcpy2D(const_cast<void *>(d.U), Hp * es, U, H * es, H * es, V, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy2D(const_cast<void *>(d.W), Hp * es, W, H * es, H * es, H, hipMemcpyHostToDevice));
+
+    // half row sums of W in fp64 on the host (H*H elements)
+    hrs.assign(Hp, 0.f);
+    for (int j = 0; j < H; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < H; ++i) s += widen_host(W, (size_t)j * H + i, dtype);
+        hrs[j] = (float)(0.5 * s);
+    }
+    HIP_TRY(hipMemcpy(const_cast<float *>(d.half_rowsum_W), hrs.data(), (size_t)Hp * 4, hipMemcpyHostToDevice));
+
+    // O: upload as given, transpose + pad on the device, column statistics
+    HIP_TRY(hipMalloc(&O_stage, (size_t)H * V * es));
+    HIP_TRY(hipMemcpy(O_stage, O, (size_t)H * V * es, hipMemcpyHostToDevice));
+    if (bias_or_null) {
+        HIP_TRY(hipMalloc(&p, (size_t)V * 4)); bias_stage = static_cast<float *>(p);
+        HIP_TRY(hipMemcpy(bias_stage, bias_or_null, (size_t)V * 4, hipMemcpyHostToDevice));
+    }
+    HIP_TRY(hipMalloc(&p, (size_t)V * 4)); upper = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)V * 4)); lower = static_cast<float *>(p);
+    HIP_TRY(launch_transpose_O(O_stage, const_cast<void *>(d.Ot), dtype, H, V, Hp, Vp, nullptr));
+    HIP_TRY(launch_col_stats(O_stage, bias_stage, dtype, H, V, const_cast<float *>(d.half_colsum_O), upper,
+                             lower, nullptr));
+    hu.resize(V); hl.resize(V);
+    HIP_TRY(hipMemcpy(hu.data(), upper, (size_t)V * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(hl.data(), lower, (size_t)V * 4, hipMemcpyDeviceToHost));
+    for (int v = 0; v < V; ++v) {
+        if (!(hu[v] <= max_upper)) max_upper = hu[v];      // NaN-propagating max
+        if (!(hl[v] >= min_lower)) min_lower = hl[v];
+    }
+    {
+        // Every base-2 logit lies in [lo2, hi2] (margin covers fp32 rounding of the sums).
+        const double hi2 = (double)max_upper * 1.4426950408889634, lo2 = (double)min_lower * 1.4426950408889634;
+        const double margin = 0.01 + 1e-5 * (fabs(hi2) + fabs(lo2));
+        d.m2_fixed = (float)(hi2 + margin);
+        // usable when even the smallest possible term 2^(lo2 - m2) is a normal fp32 number
+        m->fixed_ok = (isfinite(hi2) && isfinite(lo2) && (hi2 - lo2 + 2 * margin) < 100.0) ? 1 : 0;
+        if (!isfinite(d.m2_fixed)) d.m2_fixed = 0.f;
+    }
+    HIP_TRY(launch_fill_cvec(bias_stage, d.half_colsum_O, V, Vp, d.m2_fixed, const_cast<float *>(d.bias),
+                             const_cast<float *>(d.cvec), const_cast<float *>(d.cvec_fixed), nullptr));
+    HIP_TRY(hipDeviceSynchronize());
+    (void)hipFree(O_stage); (void)hipFree(bias_stage); (void)hipFree(upper); (void)hipFree(lower);
+    *out = m;
+    return RNNLM_OK;
+
+fail:
+    (void)hipFree(O_stage); (void)hipFree(bias_stage); (void)hipFree(upper); (void)hipFree(lower);
+    free_dev(m);
+    delete m;
+    (void)hipGetLastError();
+    return status;
+}
+
+int rnnlm_free(rnnlm_model *model) {
+    if (!model) return RNNLM_OK;
+    hipError_t e = hipDeviceSynchronize();
+    free_dev(model);
+    delete model;
+    return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
+}
+
+int rnnlm_set_option(rnnlm_model *model, int option, int value) {
+    if (!model) return RNNLM_EINVAL;
+    switch (option) {
+        case RNNLM_OPT_LSE_MODE:
+            if (value < 0 || value > 2) return RNNLM_EINVAL;
+            if (value == 2 && !model->fixed_ok) return RNNLM_EINVAL;
+            model->lse_mode = value;
+            return RNNLM_OK;
+        case RNNLM_OPT_OUTPROJ_KERNEL:
+            if (value < 0 || value > 2) return RNNLM_EINVAL;
+            if (value == 2 && !outproj_staged_supported(model->dev)) return RNNLM_EINVAL;
+            model->outproj_kernel = value;
+            return RNNLM_OK;
+        default:
+            return RNNLM_EINVAL;
+    }
+}
+
+int rnnlm_last_error(rnnlm_model *model, void *hip_stream, int *flags) {
+    if (!model || !flags) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int f = 0;
+    if (hipMemcpyAsync(&f, model->dev.flag, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (hipMemsetAsync(model->dev.flag, 0, 4, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return RNNLM_EDEVICE;
+    *flags = f;
+    return RNNLM_OK;
+}
+
+size_t rnnlm_dedup_workspace_bytes(int N) { return dedup_workspace_bytes(N); }
+
+int rnnlm_dedup(const uint64_t *history_ids, int N, int32_t *rep, int32_t *inverse, int32_t *n_unique,
+                void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (N < 0 || !n_unique) return RNNLM_EINVAL;
+    if (N > 0 && (!history_ids || !rep || !inverse)) return RNNLM_EINVAL;
+    if (N > (1 << 28)) return RNNLM_ERANGE;
+    if (N > 0) {
+        if (!workspace || workspace_bytes < dedup_workspace_bytes(N)) return RNNLM_EWORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 15) return RNNLM_EWORKSPACE;
+    }
+    hipError_t e = launch_dedup(history_ids, N, rep, inverse, n_unique, workspace,
+                                static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
+}
+
+int rnnlm_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word, const float *h_in,
+               const int32_t *query_word, const int32_t *row_of_query_or_null, int N, float *h_out,
+               float *logprob, void *hip_stream) {
+    int rc = check_step_args(model, B, K, N);
+    if (rc != RNNLM_OK) return rc;
+    if (B > 0 && (!prev_word || !h_in || !h_out)) return RNNLM_EINVAL;
+    if (N > 0 && K > 0 && (!query_word || !logprob)) return RNNLM_EINVAL;
+    if (!row_of_query_or_null && N != B) return RNNLM_EINVAL;
+    if (B > 0 && h_out == h_in) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const ModelDev &d = model->dev;
+    SplitInfo splits = {1, 0};
+    if (launch_recur(d, B, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_outproj(d, B, nullptr, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (launch_query(d, B, nullptr, N, K, splits, query_word, row_of_query_or_null, h_out, logprob, s) !=
+        hipSuccess)
+        return RNNLM_EDEVICE;
+    return RNNLM_OK;
+}
+
+int rnnlm_step_dedup(const rnnlm_model *model, int N, int K, const uint64_t *history_ids,
+                     const int32_t *prev_word, const float *h_in, const int32_t *query_word, int32_t *rep,
+                     int32_t *inverse, int32_t *n_unique, float *h_out, float *logprob, void *workspace,
+                     size_t workspace_bytes, void *hip_stream) {
+    int rc = check_step_args(model, N, K, N);
+    if (rc != RNNLM_OK) return rc;
+    if (!n_unique) return RNNLM_EINVAL;
+    if (N > 0 && (!history_ids || !prev_word || !h_in || !rep || !inverse || !h_out)) return RNNLM_EINVAL;
+    if (N > 0 && K > 0 && (!query_word || !logprob)) return RNNLM_EINVAL;
+    if (N > 0 && h_out == h_in) return RNNLM_EINVAL;
+    rc = rnnlm_dedup(history_ids, N, rep, inverse, n_unique, workspace, workspace_bytes, hip_stream);
+    if (rc != RNNLM_OK || N == 0) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const ModelDev &d = model->dev;
+    SplitInfo splits = {1, 0};
+    // Grids cover N rows; the kernels read the true number of rows from *n_unique.
+    if (launch_recur(d, N, n_unique, rep, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_outproj(d, N, n_unique, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (launch_query(d, N, n_unique, N, K, splits, query_word, inverse, h_out, logprob, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    return RNNLM_OK;
+}
+
+int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream, float *ms_per_launch) {
+    if (!model || !ms_per_launch || repeats <= 0 || B <= 0) return RNNLM_EINVAL;
+    if (B > model->max_B) return RNNLM_ERANGE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    SplitInfo splits = {1, 0};
+    const bool fixed = use_fixed_offset(model);
+    if (hipEventRecord(model->ev0, s) != hipSuccess) return RNNLM_EDEVICE;
+    for (int i = 0; i < repeats; ++i)
+        if (launch_outproj(model->dev, B, nullptr, fixed, model->outproj_kernel, &splits, s) != hipSuccess)
+            return RNNLM_EDEVICE;
+    if (hipEventRecord(model->ev1, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (hipEventSynchronize(model->ev1) != hipSuccess) return RNNLM_EDEVICE;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, model->ev0, model->ev1) != hipSuccess) return RNNLM_EDEVICE;
+    *ms_per_launch = ms / (float)repeats;
+    return RNNLM_OK;
+}
+
+}  // extern "C"

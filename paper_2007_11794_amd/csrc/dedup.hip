@@ -1,0 +1,243 @@
+// Grouping of identical 64-bit history ids on the device.
+//
+// The batched form of the cache lookup in Table 1 of the paper (steps 1-3 and 14): a
+// history that was seen before is not computed again.  New histories are numbered in the
+// order of first appearance (Table 1 step 10 numbers entries sequentially), which makes
+// the result unique: rep[] ascending, inverse[] fixed.  Insertion order into the hash
+// table is racy, so the order never comes from it: every slot keeps the MINIMUM raw
+// index that hit it, a query is "first" iff it equals that minimum, and an exclusive
+// prefix sum over the "first" flags gives the group numbers.
+//
+// Two implementations with identical results:
+//   small  (N <= kSmallN): one workgroup, table and flags in LDS, one launch;
+//   large  : table in the caller's workspace, four launches.
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+constexpr uint64_t kEmpty = 0xFFFFFFFFFFFFFFFFull;   // marks a free slot; the key with this
+                                                     // value lives in a slot of its own
+constexpr int kSmallN = 4096;
+constexpr int kSmallCap = 8192;                      // LDS slots of the small path
+constexpr int kSmallThreads = 1024;
+
+__device__ __forceinline__ uint32_t mix64(uint64_t k) {
+    // splitmix64 finaliser
+    k ^= k >> 30; k *= 0xBF58476D1CE4E5B9ull;
+    k ^= k >> 27; k *= 0x94D049BB133111EBull;
+    k ^= k >> 31;
+    return (uint32_t)k;
+}
+
+__host__ __device__ inline int table_capacity(int N) {
+    int cap = 64;
+    while (cap < 2 * N) cap <<= 1;
+    return cap;
+}
+
+// Find or claim the slot of `key` in an open-addressing table of `cap` slots (+1 extra slot
+// at index cap for the key that equals the free marker).
+template <typename KeyPtr>
+__device__ __forceinline__ int find_or_insert(KeyPtr tkeys, int cap, uint64_t key) {
+    if (key == kEmpty) return cap;
+    uint32_t h = mix64(key) & (uint32_t)(cap - 1);
+    // The table holds at most N <= cap/2 keys, so a free slot is always met.
+    for (int probe = 0; probe < cap; ++probe) {
+        unsigned long long old = atomicCAS(reinterpret_cast<unsigned long long *>(&tkeys[h]),
+                                           (unsigned long long)kEmpty, (unsigned long long)key);
+        if (old == kEmpty || old == key) return (int)h;
+        h = (h + 1) & (uint32_t)(cap - 1);
+    }
+    return -1;   // unreachable for N <= cap/2
+}
+
+// Block-wide exclusive prefix sum of one int per thread; returns the exclusive prefix and,
+// through `total`, the block sum.  `wsum` is LDS scratch of blockDim.x/64 + 1 ints.
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int &total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        int w = (lane < nwaves) ? wsum[lane] : 0;
+        int wi = w;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            int t = __shfl_up(wi, off, 64);
+            if (lane >= off) wi += t;
+        }
+        if (lane < nwaves) wsum[lane] = wi - w;       // exclusive prefix of the wave sums
+        if (lane == nwaves - 1) wsum[nwaves] = wi;    // block total
+    }
+    __syncthreads();
+    int excl = wsum[wave] + incl - v;
+    total = wsum[nwaves];
+    __syncthreads();                                  // wsum may be reused by the caller
+    return excl;
+}
+
+// ------------------------------------------------------------------------------ small path
+__global__ __launch_bounds__(kSmallThreads) void dedup_small_kernel(
+    const uint64_t *__restrict__ keys, int N, int32_t *__restrict__ rep,
+    int32_t *__restrict__ inverse, int32_t *__restrict__ n_unique) {
+    __shared__ uint64_t tkeys[kSmallCap + 1];
+    __shared__ int tfirst[kSmallCap + 1];    // min raw index per slot, later the group number
+    __shared__ int wsum[kSmallThreads / 64 + 1];
+    constexpr int kPer = kSmallN / kSmallThreads;      // queries per thread
+
+    for (int i = threadIdx.x; i <= kSmallCap; i += kSmallThreads) {
+        tkeys[i] = kEmpty;
+        tfirst[i] = 0x7FFFFFFF;
+    }
+    __syncthreads();
+
+    // Thread t owns the contiguous queries t*kPer .. t*kPer+kPer-1, so that the scan below
+    // runs over raw-index order.
+    int slot[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        int n = threadIdx.x * kPer + i;
+        slot[i] = -1;
+        if (n < N) {
+            slot[i] = find_or_insert(tkeys, kSmallCap, keys[n]);
+            atomicMin(&tfirst[slot[i]], n);
+        }
+    }
+    __syncthreads();
+
+    int is_first[kPer];
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        int n = threadIdx.x * kPer + i;
+        is_first[i] = (n < N && tfirst[slot[i]] == n) ? 1 : 0;
+        mine += is_first[i];
+    }
+    int total;
+    int u = block_exclusive_scan(mine, wsum, total);   // barriers inside: all tfirst reads done
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        if (is_first[i]) {
+            int n = threadIdx.x * kPer + i;
+            rep[u] = n;
+            tfirst[slot[i]] = u;                       // the slot now carries its group number
+            ++u;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        int n = threadIdx.x * kPer + i;
+        if (n < N) inverse[n] = tfirst[slot[i]];
+    }
+    if (threadIdx.x == 0) *n_unique = total;
+}
+
+// ------------------------------------------------------------------------------ large path
+struct LargeWs {
+    uint64_t *tkeys;   // [cap+1]
+    int *tfirst;       // [cap+1]
+    int *tgroup;       // [cap+1]
+    int *slot;         // [N]
+};
+
+__host__ inline LargeWs carve(void *ws, int N) {
+    int cap = table_capacity(N);
+    char *p = static_cast<char *>(ws);
+    LargeWs w;
+    w.tkeys = reinterpret_cast<uint64_t *>(p); p += (size_t)(cap + 2) * 8;
+    w.tfirst = reinterpret_cast<int *>(p);     p += (size_t)(cap + 2) * 4;
+    w.tgroup = reinterpret_cast<int *>(p);     p += (size_t)(cap + 2) * 4;
+    w.slot = reinterpret_cast<int *>(p);
+    return w;
+}
+
+__global__ void dedup_init_kernel(uint64_t *tkeys, int *tfirst, int cap) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= cap) {
+        tkeys[i] = kEmpty;
+        tfirst[i] = 0x7FFFFFFF;
+    }
+}
+
+__global__ void dedup_insert_kernel(const uint64_t *__restrict__ keys, int N, uint64_t *tkeys,
+                                    int *tfirst, int *slot, int cap) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    int s = find_or_insert(tkeys, cap, keys[n]);
+    slot[n] = s;
+    atomicMin(&tfirst[s], n);
+}
+
+// One workgroup walks the queries in raw order, 1024 at a time, carrying the running count.
+__global__ __launch_bounds__(1024) void dedup_rank_kernel(int N, const int *__restrict__ slot,
+                                                          const int *__restrict__ tfirst,
+                                                          int *tgroup, int32_t *rep,
+                                                          int32_t *n_unique) {
+    __shared__ int wsum[1024 / 64 + 1];
+    int carry = 0;
+    for (int base = 0; base < N; base += 1024) {
+        int n = base + threadIdx.x;
+        int s = (n < N) ? slot[n] : 0;
+        int first = (n < N && tfirst[s] == n) ? 1 : 0;
+        int total;
+        int u = carry + block_exclusive_scan(first, wsum, total);
+        if (first) {
+            rep[u] = n;
+            tgroup[s] = u;
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) *n_unique = carry;
+}
+
+__global__ void dedup_inverse_kernel(int N, const int *__restrict__ slot,
+                                     const int *__restrict__ tgroup, int32_t *inverse) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n < N) inverse[n] = tgroup[slot[n]];
+}
+
+__global__ void dedup_empty_kernel(int32_t *n_unique) { *n_unique = 0; }
+
+}  // namespace
+
+size_t dedup_workspace_bytes(int N) {
+    if (N <= 0) return 0;
+    int cap = table_capacity(N);
+    size_t bytes = (size_t)(cap + 2) * 16 + (size_t)N * 4;
+    return (bytes + 255) & ~(size_t)255;
+}
+
+hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inverse,
+                        int32_t *n_unique, void *workspace, hipStream_t stream) {
+    if (N <= 0) {
+        hipLaunchKernelGGL(dedup_empty_kernel, dim3(1), dim3(1), 0, stream, n_unique);
+        return hipGetLastError();
+    }
+    if (N <= kSmallN) {
+        hipLaunchKernelGGL(dedup_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, keys, N, rep,
+                           inverse, n_unique);
+        return hipGetLastError();
+    }
+    const int cap = table_capacity(N);
+    LargeWs w = carve(workspace, N);
+    hipLaunchKernelGGL(dedup_init_kernel, dim3((cap + 1 + 255) / 256), dim3(256), 0, stream, w.tkeys,
+                       w.tfirst, cap);
+    hipLaunchKernelGGL(dedup_insert_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, keys, N,
+                       w.tkeys, w.tfirst, w.slot, cap);
+    hipLaunchKernelGGL(dedup_rank_kernel, dim3(1), dim3(1024), 0, stream, N, w.slot, w.tfirst, w.tgroup,
+                       rep, n_unique);
+    hipLaunchKernelGGL(dedup_inverse_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, N, w.slot,
+                       w.tgroup, inverse);
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm

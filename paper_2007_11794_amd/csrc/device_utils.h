@@ -1,0 +1,85 @@
+// Small device helpers: bf16 <-> fp32, 8-element loads, wave reductions, MFMA types.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rnnlm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+// Round to nearest even; NaN stays NaN, infinities stay infinite.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Eight consecutive weights starting at element index `at` (a multiple of 8) as floats.
+__device__ __forceinline__ void load8_weights(const uint16_t *p, size_t at, float (&out)[8]) {
+    u32x4 v = *reinterpret_cast<const u32x4 *>(p + at);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(v[i] << 16);
+        out[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ void load8_weights(const float *p, size_t at, float (&out)[8]) {
+    f32x4 a = *reinterpret_cast<const f32x4 *>(p + at);
+    f32x4 b = *reinterpret_cast<const f32x4 *>(p + at + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { out[i] = a[i]; out[4 + i] = b[i]; }
+}
+
+// Eight consecutive floats row[k0 .. k0+7] of a caller-owned row of length H (not padded);
+// elements at or beyond H read as `fill`.  Vector loads when the row allows them.
+__device__ __forceinline__ void load8_row(const float *row, int k0, int H, bool vec_ok, float fill,
+                                          float (&out)[8]) {
+    if (vec_ok && k0 + 8 <= H) {
+        f32x4 a = *reinterpret_cast<const f32x4 *>(row + k0);
+        f32x4 b = *reinterpret_cast<const f32x4 *>(row + k0 + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { out[i] = a[i]; out[4 + i] = b[i]; }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) out[i] = (k0 + i < H) ? row[k0 + i] : fill;
+    }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// 2^x with the hardware instruction (x = -inf gives 0).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Merge two (max, sum) pairs of a base-2 log-sum-exp: value = 2^m * s.
+__device__ __forceinline__ void lse2_merge(float &m, float &s, float m2, float s2) {
+    float mm = fmaxf(m, m2);
+    if (mm == -INFINITY) { m = mm; s = 0.f; return; }
+    s = s * fast_exp2(m - mm) + s2 * fast_exp2(m2 - mm);
+    m = mm;
+}
+
+__device__ __forceinline__ float quiet_nan() { return __uint_as_float(0x7FC00000u); }
+
+}  // namespace rnnlm

@@ -1,0 +1,232 @@
+// Output projection fused with the log-sum-exp over the vocabulary:
+//     z[b][v] = bias[v] + sum_j O[j][v] h'[b][j],      lse[b] = log sum_v exp z[b][v]
+// (normalising over all words of the vocabulary is the cost Section 2.1 of the paper
+// names).  The B x V logits exist only in registers; what reaches memory is, per row and
+// per vocabulary split, one (max, sum) pair of the base-2 log-sum-exp.
+//
+// With h' = 1/2 + d the logit is  z = (bias + 1/2 colsum(O)) + sum_j O[j][v] d[j]; the
+// bracket is the per-word constant cvec[v] the accumulators start from (-inf for the padded
+// words beyond V, which then add 2^-inf = 0).  Two ways to take the sum:
+//   running maximum  per lane (m, s): always valid;
+//   fixed offset     since |d| <= 1/2 every base-2 logit is <= m2_fixed, a bound computed
+//                    at load time; s = sum 2^(x - m2_fixed) needs no maximum and no
+//                    rescaling.  Used when the bound is tight enough for fp32.
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+// Accumulate sixteen base-2 logits of one row into (m, s).
+template <bool FIXED>
+__device__ __forceinline__ void lse2_accumulate16(const float (&x)[16], float &m, float &s) {
+    if (FIXED) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += fast_exp2(x[i]);       // x already has the offset removed
+    } else {
+        float mx = x[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+        float mn = fmaxf(m, mx);
+        if (mn != -INFINITY) {
+            float t = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t += fast_exp2(x[i] - mn);
+            s = s * fast_exp2(m - mn) + t;
+            m = mn;
+        }
+    }
+}
+
+// ------------------------------------------------------------------- plain bf16 MFMA kernel
+// Any Hp (multiple of 16), any Vp (multiple of 32).  One wave owns 32 rows and walks the
+// 32-word blocks of its vocabulary split; operands come straight from global memory (L1/L2).
+// MFMA roles: A = 32 words x 16 k of Ot, B = 16 k x 32 rows of d, so that lane l holds
+// sixteen logits of ONE row (l % 32) and the sum over words needs no cross-lane traffic
+// until the very end (lanes l and l + 32 share a row).
+template <bool FIXED>
+__global__ __launch_bounds__(256) void outproj_plain_bf16_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, int blocks_per_split, int splits) {
+    const int B = B_dev ? *B_dev : rows;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, col = lane & 31, g = lane >> 5;
+    const int b0 = (blockIdx.y * 4 + wave) * 32;
+    if (b0 >= B) return;
+    const int Hp = m.Hp;
+    const bf16_t *Ot = static_cast<const bf16_t *>(m.Ot);
+    const bf16_t *drow = static_cast<const bf16_t *>(m.d) + (size_t)(b0 + col) * Hp;
+    const float *cvec = FIXED ? m.cvec_fixed : m.cvec;
+    const int split = blockIdx.x;
+    const int nblocks = m.Vp / 32;
+    const int blk_begin = split * blocks_per_split;
+    const int blk_end = min(nblocks, blk_begin + blocks_per_split);
+
+    float mrun = FIXED ? m.m2_fixed : -INFINITY, srun = 0.f;
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        const int v0 = blk * 32;
+        const bf16_t *orow = Ot + (size_t)(v0 + col) * Hp;
+        f32x16 acc;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f32x4 c = *reinterpret_cast<const f32x4 *>(cvec + v0 + 8 * q + 4 * g);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[4 * q + i] = c[i];
+        }
+        for (int k0 = 8 * g; k0 < Hp; k0 += 16) {
+            bf16x8 of = *reinterpret_cast<const bf16x8 *>(orow + k0);
+            bf16x8 df = *reinterpret_cast<const bf16x8 *>(drow + k0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(of, df, acc, 0, 0, 0);
+        }
+        float x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = acc[i] * kLog2e;
+        lse2_accumulate16<FIXED>(x, mrun, srun);
+    }
+    // lanes l and l+32 hold the two halves of a row
+    float m2 = __shfl_xor(mrun, 32, 64), s2 = __shfl_xor(srun, 32, 64);
+    if (FIXED) srun += s2;
+    else lse2_merge(mrun, srun, m2, s2);
+    if (g == 0 && b0 + col < B) m.part[(size_t)(b0 + col) * kMaxSplits + split] = make_float2(mrun, srun);
+}
+
+// ------------------------------------------------------------------- plain fp32 ALU kernel
+// A 64 (rows) x 64 (words) tile per workgroup of 256 threads, 4 x 4 logits per thread, K in
+// chunks of 16 through LDS (stored k-major so a thread reads its four rows / four words as
+// one 16-byte LDS access).
+constexpr int kFM = 64, kFN = 64, kFK = 16;
+
+template <bool FIXED>
+__global__ __launch_bounds__(256) void outproj_plain_f32_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, int blocks_per_split, int splits) {
+    const int B = B_dev ? *B_dev : rows;
+    const int b0 = blockIdx.y * kFM;
+    if (b0 >= B) return;
+    const int Hp = m.Hp;
+    const float *Ot = static_cast<const float *>(m.Ot);
+    const float *d = static_cast<const float *>(m.d);
+    const float *cvec = FIXED ? m.cvec_fixed : m.cvec;
+    const int split = blockIdx.x;
+    const int nblocks = m.Vp / kFN;
+    const int blk_begin = split * blocks_per_split;
+    const int blk_end = min(nblocks, blk_begin + blocks_per_split);
+
+    __shared__ float As[kFK][kFM + 4];
+    __shared__ float Bs[kFK][kFN + 4];
+    __shared__ float2 red[kFM][16];
+    const int t = threadIdx.x, tx = t & 15, ty = t >> 4;     // tx: word group, ty: row group
+    const int lr = t >> 2, lk = (t & 3) * 4;                  // loader: row/word lr, k offset lk
+
+    float mrun[4], srun[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { mrun[r] = FIXED ? m.m2_fixed : -INFINITY; srun[r] = 0.f; }
+
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        const int v0 = blk * kFN;
+        float acc[4][4];
+        f32x4 cv = *reinterpret_cast<const f32x4 *>(cvec + v0 + tx * 4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[r][c] = cv[c];
+        for (int k0 = 0; k0 < Hp; k0 += kFK) {
+            // rows of d beyond B are stale scratch; rows are independent, so whatever they
+            // hold only reaches partials that are never written
+            f32x4 av = *reinterpret_cast<const f32x4 *>(d + (size_t)(b0 + lr) * Hp + k0 + lk);
+            f32x4 bv = *reinterpret_cast<const f32x4 *>(Ot + (size_t)(v0 + lr) * Hp + k0 + lk);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { As[lk + i][lr] = av[i]; Bs[lk + i][lr] = bv[i]; }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kFK; ++k) {
+                f32x4 a = *reinterpret_cast<const f32x4 *>(&As[k][ty * 4]);
+                f32x4 b = *reinterpret_cast<const f32x4 *>(&Bs[k][tx * 4]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[r][c] = fmaf(a[r], b[c], acc[r][c]);
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float x[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x[c] = acc[r][c] * kLog2e;
+            if (FIXED) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) srun[r] += fast_exp2(x[c]);
+            } else {
+                float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+                float mn = fmaxf(mrun[r], mx);
+                if (mn != -INFINITY) {
+                    float tsum = 0.f;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) tsum += fast_exp2(x[c] - mn);
+                    srun[r] = srun[r] * fast_exp2(mrun[r] - mn) + tsum;
+                    mrun[r] = mn;
+                }
+            }
+        }
+    }
+    // combine the 16 word groups of every row, in a fixed order
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[ty * 4 + r][tx] = make_float2(mrun[r], srun[r]);
+    __syncthreads();
+    if (t < kFM) {
+        float mm = red[t][0].x, ss = red[t][0].y;
+        for (int i = 1; i < 16; ++i) {
+            if (FIXED) ss += red[t][i].y;
+            else lse2_merge(mm, ss, red[t][i].x, red[t][i].y);
+        }
+        if (b0 + t < B) m.part[(size_t)(b0 + t) * kMaxSplits + split] = make_float2(mm, ss);
+    }
+}
+
+int choose_splits(int row_blocks, int col_blocks, int target_groups) {
+    int s = (target_groups + row_blocks - 1) / row_blocks;
+    if (s > kMaxSplits) s = kMaxSplits;
+    if (s > col_blocks) s = col_blocks;
+    if (s < 1) s = 1;
+    return s;
+}
+
+}  // namespace
+
+// defined in outproj_staged.hip
+hipError_t launch_outproj_staged(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                                 SplitInfo *splits, hipStream_t stream);
+
+hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                          int kernel_choice, SplitInfo *splits, hipStream_t stream) {
+    splits->fixed_splits = 1;
+    splits->staged_wg_per_xcd = 0;
+    if (rows <= 0) return hipSuccess;
+    if (m.dtype == RNNLM_BF16) {
+        const bool staged = kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128);
+        if (staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
+        const int row_groups = (rows + 127) / 128, col_blocks = m.Vp / 32;
+        int S = choose_splits(row_groups, col_blocks, 1024);
+        int per = (col_blocks + S - 1) / S;
+        S = (col_blocks + per - 1) / per;
+        dim3 grid(S, row_groups);
+        if (fixed_offset)
+            hipLaunchKernelGGL(outproj_plain_bf16_kernel<true>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
+        else
+            hipLaunchKernelGGL(outproj_plain_bf16_kernel<false>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
+        splits->fixed_splits = S;
+    } else {
+        const int row_groups = (rows + kFM - 1) / kFM, col_blocks = m.Vp / kFN;
+        int S = choose_splits(row_groups, col_blocks, 1024);
+        int per = (col_blocks + S - 1) / S;
+        S = (col_blocks + per - 1) / per;
+        dim3 grid(S, row_groups);
+        if (fixed_offset)
+            hipLaunchKernelGGL(outproj_plain_f32_kernel<true>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
+        else
+            hipLaunchKernelGGL(outproj_plain_f32_kernel<false>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
+        splits->fixed_splits = S;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm

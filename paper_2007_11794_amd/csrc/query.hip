@@ -1,0 +1,80 @@
+// Query gather: only the log-probabilities the search asked for leave the device
+// (the paper's aim of exchanging as little as possible, Section 3.2; the returned value is
+// the p of Table 1 step 6):
+//     logprob[n][k] = z[r][q] - lse[r],  r = row_of_query[n],  q = query_word[n][k],
+// with z[r][q] = bias[q] + sum_j O[j][q] h'[r][j] recomputed as one H-long dot product per
+// queried word from the fp32 h' and the [V][H] copy of O (one contiguous row per word), and
+// lse[r] assembled from the per-split (max, sum) partials of the output projection in a
+// fixed order.
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+template <typename T>
+__global__ __launch_bounds__(256) void query_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K, SplitInfo si,
+    const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
+    const float *__restrict__ h_out, float *__restrict__ logprob) {
+    const int B = B_dev ? *B_dev : rows;
+    const int n = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int H = m.H, Hp = m.Hp;
+    const int r = row_of_query ? row_of_query[n] : n;
+    float *out = logprob + (size_t)n * K;
+    if (r < 0 || r >= B) {
+        if (threadIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_ROW);
+        for (int k = threadIdx.x; k < K; k += 256) out[k] = quiet_nan();
+        return;
+    }
+    // lse of row r, in base 2: every wave assembles it, lane l taking splits l, l+64, ...
+    const int splits = si.fixed_splits > 0 ? si.fixed_splits : staged_plan(B, si.staged_wg_per_xcd).S;
+    float pm = -INFINITY, ps = 0.f;
+    for (int s = lane; s < splits; s += 64) {
+        float2 p = m.part[(size_t)r * kMaxSplits + s];
+        lse2_merge(pm, ps, p.x, p.y);
+    }
+    float mm = wave_max(pm);
+    float ss = wave_sum(mm == -INFINITY ? 0.f : ps * fast_exp2(pm - mm));
+    const float lse = (mm + fast_log2(ss)) * kLn2;
+
+    const T *Ot = static_cast<const T *>(m.Ot);
+    const float *hrow = h_out + (size_t)r * H;
+    const bool vec_ok = (H % 4) == 0;
+    for (int k = wave; k < K; k += 4) {
+        const int q = query_word[(size_t)n * K + k];
+        if (q < 0 || q >= m.V) {
+            if (lane == 0) { atomicOr(m.flag, RNNLM_FLAG_BAD_QUERY_WORD); out[k] = quiet_nan(); }
+            continue;
+        }
+        float acc = 0.f;
+        for (int j0 = lane * 8; j0 < Hp; j0 += 512) {
+            float w8[8], h8[8];
+            load8_weights(Ot, (size_t)q * Hp + j0, w8);
+            load8_row(hrow, j0, H, vec_ok, 0.f, h8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc = fmaf(w8[i], h8[i], acc);
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) out[k] = (acc + m.bias[q]) - lse;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, int K, SplitInfo splits,
+                        const int32_t *query_word, const int32_t *row_of_query,
+                        const float *h_out, float *logprob, hipStream_t stream) {
+    if (N <= 0 || K <= 0) return hipSuccess;
+    if (m.dtype == RNNLM_BF16)
+        hipLaunchKernelGGL(query_kernel<bf16_t>, dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
+                           query_word, row_of_query, h_out, logprob);
+    else
+        hipLaunchKernelGGL(query_kernel<float>, dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
+                           query_word, row_of_query, h_out, logprob);
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm

@@ -1,0 +1,186 @@
+// Hidden update  h'[b][j] = sigmoid(U[prev[b]][j] + sum_i W[j][i] h_in[b][i])
+// (the context update inside ComputeRnnlm, Table 1 step 6; Section 4.1: the context is the
+// previous hidden layer plus the previous word).
+//
+// The activation enters the product centred: h_in = 1/2 + d, so
+//     W h_in = 1/2 rowsum(W) + W d,
+// with the first term precomputed at load time in fp64.  |d| <= 1/2 carries three times
+// less rounding error than h_in when it is cut to bf16 for the matrix cores, and the bf16
+// path additionally splits d = d_hi + d_lo (two MFMA passes; this product is under one
+// percent of the step's flops) so that the hidden vector is accurate to fp32 level.
+//
+// Besides h_out (fp32, caller's buffer) the kernel leaves d' = h' - 1/2 in the model's
+// scratch block, in the weights' type, as the operand of the output projection.
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+__device__ __forceinline__ float sigmoid_f32(float a) {
+    // 1/(1+2^(-a log2 e)); the hardware exp2/rcp are accurate to about 1 ulp
+    return __frcp_rn(1.0f + fast_exp2(-a * kLog2e));
+}
+
+// ----------------------------------------------------------------------------- bf16 / MFMA
+// One wave computes a 32 (units j) x 32 (rows b) block: D[j][b] = sum_i W[j][i] d[b][i].
+// MFMA 32x32x16 operand layout (lane l, g = l / 32):
+//   A: 8 consecutive k of row (l % 32), starting at 8 g;   B: same for column (l % 32);
+//   D: acc[i] is row 8 (i / 4) + 4 g + i % 4, column l % 32.
+__global__ __launch_bounds__(64) void recur_bf16_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
+    float *__restrict__ h_out) {
+    const int B = B_dev ? *B_dev : rows;
+    const int b0 = blockIdx.y * 32;
+    if (b0 >= B) return;
+    const int j0 = blockIdx.x * 32;
+    const int lane = threadIdx.x, col = lane & 31, g = lane >> 5;
+    const int H = m.H, Hp = m.Hp;
+    const bf16_t *W = static_cast<const bf16_t *>(m.W);
+    const bf16_t *U = static_cast<const bf16_t *>(m.U);
+
+    const int b = b0 + col;
+    const bool row_ok = b < B;
+    const int src = row_ok ? (row_src ? row_src[b] : b) : 0;
+    const float *hrow = h_in + (size_t)src * H;
+    const bool vec_ok = (H % 4) == 0;
+    const bf16_t *wrow = W + (size_t)(j0 + col) * Hp;
+
+    f32x16 acc = {0};
+    for (int k0 = 8 * g; k0 < Hp; k0 += 16) {
+        bf16x8 wf = *reinterpret_cast<const bf16x8 *>(wrow + k0);
+        float h8[8];
+        if (row_ok) load8_row(hrow, k0, H, vec_ok, 0.5f, h8);
+        else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) h8[i] = 0.5f;
+        }
+        u32x4 hi, lo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float d0 = h8[2 * i] - 0.5f, d1 = h8[2 * i + 1] - 0.5f;
+            uint16_t h0 = f32_to_bf16(d0), h1 = f32_to_bf16(d1);
+            hi[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+            lo[i] = pack_bf16x2(d0 - bf16_to_f32(h0), d1 - bf16_to_f32(h1));
+        }
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, hi), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, lo), acc, 0, 0, 0);
+    }
+
+    if (!row_ok) return;
+    const int w = prev_word[src];
+    const bool w_ok = (w >= 0 && w < m.V);
+    if (!w_ok && g == 0 && blockIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
+    const bf16_t *urow = U + (size_t)(w_ok ? w : 0) * Hp;
+    bf16_t *drow = static_cast<bf16_t *>(m.d) + (size_t)b * Hp;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int j = j0 + 8 * q + 4 * g;              // four consecutive units
+        uint2 u4 = *reinterpret_cast<const uint2 *>(urow + j);
+        f32x4 rs = *reinterpret_cast<const f32x4 *>(m.half_rowsum_W + j);
+        float u[4] = {__uint_as_float(u4.x << 16), __uint_as_float(u4.x & 0xFFFF0000u),
+                      __uint_as_float(u4.y << 16), __uint_as_float(u4.y & 0xFFFF0000u)};
+        float hp[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float a = acc[4 * q + i] + rs[i] + u[i];
+            hp[i] = w_ok ? sigmoid_f32(a) : quiet_nan();
+        }
+        uint2 dpk;
+        dpk.x = pack_bf16x2(hp[0] - 0.5f, hp[1] - 0.5f);
+        dpk.y = pack_bf16x2(hp[2] - 0.5f, hp[3] - 0.5f);
+        *reinterpret_cast<uint2 *>(drow + j) = dpk;   // padded units get sigmoid(0) - 1/2 = 0
+        if (vec_ok && j + 4 <= H) {
+            *reinterpret_cast<f32x4 *>(h_out + (size_t)b * H + j) = f32x4{hp[0], hp[1], hp[2], hp[3]};
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (j + i < H) h_out[(size_t)b * H + j + i] = hp[i];
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- fp32 / ALU
+// A 16 (rows) x 64 (units) tile per workgroup of 256 threads; thread t owns unit t % 64 and
+// the four rows 4 (t / 64) .. +3.  K is walked in chunks of 32 through LDS.
+constexpr int kRB = 16, kRJ = 64, kRK = 32;
+
+__global__ __launch_bounds__(256) void recur_f32_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
+    float *__restrict__ h_out) {
+    const int B = B_dev ? *B_dev : rows;
+    const int b0 = blockIdx.y * kRB;
+    if (b0 >= B) return;
+    const int j0 = blockIdx.x * kRJ;
+    const int H = m.H, Hp = m.Hp;
+    const float *W = static_cast<const float *>(m.W);
+    const float *U = static_cast<const float *>(m.U);
+    __shared__ float ds[kRB][kRK];
+    __shared__ float ws[kRJ][kRK + 1];
+    const int t = threadIdx.x, tj = t & 63, tb = (t >> 6) * 4;
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < Hp; k0 += kRK) {
+        // d tile: 16 x 32 values, two per thread
+        for (int e = t; e < kRB * kRK; e += 256) {
+            int r = e / kRK, k = e % kRK;
+            int b = b0 + r;
+            float v = 0.f;
+            if (b < B && k0 + k < H) {
+                int src = row_src ? row_src[b] : b;
+                v = h_in[(size_t)src * H + k0 + k] - 0.5f;
+            }
+            ds[r][k] = v;
+        }
+        // W tile: 64 x 32 values, eight per thread (padded rows/columns of W are zero)
+        for (int e = t; e < kRJ * kRK; e += 256) {
+            int r = e / kRK, k = e % kRK;
+            ws[r][k] = W[(size_t)(j0 + r) * Hp + k0 + k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kRK; ++k) {
+            float wv = ws[tj][k];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = fmaf(wv, ds[tb + r][k], acc[r]);
+        }
+        __syncthreads();
+    }
+    const int j = j0 + tj;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int b = b0 + tb + r;
+        if (b >= B) continue;
+        const int src = row_src ? row_src[b] : b;
+        const int w = prev_word[src];
+        const bool w_ok = (w >= 0 && w < m.V);
+        if (!w_ok && j == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
+        float a = acc[r] + m.half_rowsum_W[j] + U[(size_t)(w_ok ? w : 0) * Hp + j];
+        float hp = w_ok ? sigmoid_f32(a) : quiet_nan();
+        static_cast<float *>(m.d)[(size_t)b * Hp + j] = hp - 0.5f;
+        if (j < H) h_out[(size_t)b * H + j] = hp;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int32_t *row_src,
+                        const int32_t *prev_word, const float *h_in, float *h_out,
+                        hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    if (m.dtype == RNNLM_BF16) {
+        dim3 grid(m.Hp / 32, (rows + 31) / 32);
+        hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(64), 0, stream, m, rows, B_dev, row_src,
+                           prev_word, h_in, h_out);
+    } else {
+        dim3 grid(m.Hp / kRJ, (rows + kRB - 1) / kRB);
+        hipLaunchKernelGGL(recur_f32_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
+                           prev_word, h_in, h_out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm

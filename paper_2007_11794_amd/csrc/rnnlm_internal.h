@@ -1,0 +1,115 @@
+// Internal declarations shared by the translation units of librnnlm (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rnnlm.h"
+
+namespace rnnlm {
+
+typedef uint16_t bf16_t;                       // bfloat16 bit pattern
+
+constexpr int kMaxSplits = 256;                // most vocabulary splits of the output projection
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Device-side view of a loaded model (all pointers are device pointers).
+struct ModelDev {
+    int V, H;
+    int Hp;            // H rounded up to a multiple of 64; padded weights are zero
+    int Vp;            // V rounded up to a multiple of 256; padded rows of Ot are zero
+    int dtype;
+    const void *U;     // [V][Hp]
+    const void *W;     // [Hp][Hp], W[j][i]
+    const void *Ot;    // [Vp][Hp], Ot[v][j] = O[j][v]
+    const float *half_rowsum_W;   // [Hp]  0.5 * sum_i W[j][i]
+    const float *bias;            // [V]
+    const float *half_colsum_O;   // [V]   0.5 * sum_j O[j][v]
+    // Additive constant of every logit, bias[v] + 0.5*colsum_O[v]; -inf for the padded
+    // words v >= V so they add nothing to the sum.
+    const float *cvec;            // [Vp]
+    const float *cvec_fixed;      // [Vp]  cvec - m2_fixed * ln 2
+    float m2_fixed;    // upper bound of every base-2 logit z*log2(e), valid because |h' - 0.5| <= 0.5
+    // scratch
+    void *d;           // [max_Bp][Hp]  h' - 0.5 in the weights' type
+    float2 *part;      // [max_Bp][kMaxSplits]  (max, sum) partials of the base-2 log-sum-exp
+    int *flag;         // sticky rnnlm_device_flag bits
+};
+
+}  // namespace rnnlm
+
+struct rnnlm_model {
+    rnnlm::ModelDev dev;
+    int max_B, max_Bp;
+    int fixed_ok;          // the fixed-offset log-sum-exp is usable for this model
+    int lse_mode;          // RNNLM_OPT_LSE_MODE
+    int outproj_kernel;    // RNNLM_OPT_OUTPROJ_KERNEL
+    hipEvent_t ev0, ev1;
+};
+
+namespace rnnlm {
+
+// ---- launchers (each enqueues on `stream` and returns the hipGetLastError of the launch)
+
+// Grouping of equal 64-bit keys.
+size_t dedup_workspace_bytes(int N);
+hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inverse,
+                        int32_t *n_unique, void *workspace, hipStream_t stream);
+
+// Hidden update.  rows = number of rows the grid must cover (>= the true B); the true B is
+// *B_dev when B_dev != nullptr, else rows.  row_src (nullable) maps row b to the raw row
+// that holds its prev word and h_in.
+hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int32_t *row_src,
+                        const int32_t *prev_word, const float *h_in, float *h_out,
+                        hipStream_t stream);
+
+// How many (max, sum) partials per row the output projection left in m.part: a fixed
+// number, or (staged kernel, whose split count follows the true number of rows that only
+// the device may know) the number staged_plan derives from B and the grid size.
+struct SplitInfo {
+    int fixed_splits;      // > 0: that many
+    int staged_wg_per_xcd; // used when fixed_splits == 0
+};
+
+constexpr int kStagedRows = 256;   // rows per workgroup of the staged kernel
+constexpr int kStagedWords = 64;   // words per LDS stage
+constexpr int kXcds = 8;           // workgroup id modulo 8 = the XCD (L2 domain) it runs on
+
+// Work split of the staged kernel for B rows on a grid of kXcds * wg_per_xcd workgroups:
+// RG row groups of 256 rows; the vocabulary is cut into S = kXcds * Sx splits; split s is
+// served by XCD s % kXcds, so the RG workgroups that stream the same weights share one L2.
+struct StagedPlan { int RG, Sx, S; };
+__host__ __device__ inline StagedPlan staged_plan(int B, int wg_per_xcd) {
+    StagedPlan p;
+    p.RG = (B + kStagedRows - 1) / kStagedRows;
+    if (p.RG < 1) p.RG = 1;
+    p.Sx = wg_per_xcd / p.RG;
+    if (p.Sx < 1) p.Sx = 1;
+    if (p.Sx > kMaxSplits / kXcds) p.Sx = kMaxSplits / kXcds;
+    p.S = kXcds * p.Sx;
+    return p;
+}
+
+// Output projection + log-sum-exp partials over the vocabulary, on the block m.d.
+hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                          int kernel_choice, SplitInfo *splits, hipStream_t stream);
+bool outproj_staged_supported(const ModelDev &m);
+
+// Query gather: logprob[n][k] = z[row(n)][query[n][k]] - lse[row(n)].
+hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, int K, SplitInfo splits,
+                        const int32_t *query_word, const int32_t *row_of_query,
+                        const float *h_out, float *logprob, hipStream_t stream);
+
+// Load-time helpers.
+hipError_t launch_transpose_O(const void *O_dev /*[H][V]*/, void *Ot /*[Vp][Hp]*/, int dtype,
+                              int H, int V, int Hp, int Vp, hipStream_t stream);
+hipError_t launch_col_stats(const void *O_dev, const float *bias_or_null, int dtype, int H, int V,
+                            float *half_colsum /*[V]*/, float *upper /*[V]*/, float *lower /*[V]*/,
+                            hipStream_t stream);
+hipError_t launch_fill_cvec(const float *bias_or_null, const float *half_colsum, int V, int Vp,
+                            float m2_fixed, float *bias_out, float *cvec, float *cvec_fixed,
+                            hipStream_t stream);
+
+}  // namespace rnnlm

@@ -1,0 +1,79 @@
+"""The C-ABI library without a GPU: it loads, exports what include/rnnlm.h declares, and
+rejects host-checkable mistakes before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2007_11794_amd as rn
+from paper_2007_11794_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rnnlm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rnnlm_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = rn.lib()
+    names = declared_functions()
+    assert "rnnlm_load" in names and "rnnlm_dedup" in names and "rnnlm_step" in names
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_strerror_texts():
+    assert rn.rnnlm_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert rn.rnnlm_strerror(code) not in ("ok", "unknown status")
+    assert rn.rnnlm_strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes():
+    assert rn.rnnlm_dedup_workspace_bytes(0) == 0
+    assert rn.rnnlm_dedup_workspace_bytes(-3) == 0
+    small, big = rn.rnnlm_dedup_workspace_bytes(10), rn.rnnlm_dedup_workspace_bytes(100000)
+    assert 0 < small < big
+    assert big >= 100000 * (8 * 2 + 4)          # table of >= 2N slots of key+2 ints, plus N slot ids
+    assert big % 256 == 0
+
+
+def test_host_checked_errors_return_before_any_device_work():
+    L = rn.lib()
+    out = ctypes.c_void_p()
+    buf = (ctypes.c_float * 16)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    EINVAL, ERANGE, EWORKSPACE = -1, -4, -5
+    assert L.rnnlm_load(0, 4, 0, p, p, p, None, 1, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_load(4, 0, 0, p, p, p, None, 1, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_load(4, 4, 7, p, p, p, None, 1, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_load(4, 4, 0, None, p, p, None, 1, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_load(4, 4, 0, p, p, p, None, 0, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_load(4, 4, 0, p, p, p, None, 1, None) == EINVAL
+    assert out.value is None
+    assert L.rnnlm_free(None) == 0
+    assert L.rnnlm_set_option(None, 1, 0) == EINVAL
+    assert L.rnnlm_step(None, 1, 1, p, p, p, None, 1, p, p, None) == EINVAL
+    assert L.rnnlm_step_dedup(None, 1, 1, p, p, p, p, p, p, p, p, p, p, 1 << 20, None) == EINVAL
+    assert L.rnnlm_dedup(p, -1, p, p, p, p, 1 << 20, None) == EINVAL
+    assert L.rnnlm_dedup(None, 4, p, p, p, p, 1 << 20, None) == EINVAL
+    assert L.rnnlm_dedup(p, 4, p, p, None, p, 1 << 20, None) == EINVAL
+    assert L.rnnlm_dedup(p, 4, p, p, p, None, 1 << 20, None) == EWORKSPACE
+    assert L.rnnlm_dedup(p, 4, p, p, p, p, 8, None) == EWORKSPACE
+    assert L.rnnlm_dedup(p, 4, p, p, p, ctypes.c_void_p(p.value + 4), 1 << 20, None) == EWORKSPACE
+    assert L.rnnlm_dedup(p, (1 << 28) + 1, p, p, p, p, 1 << 20, None) == ERANGE
+    ms = ctypes.c_float()
+    assert L.rnnlm_time_outproj(None, 1, 1, None, ctypes.byref(ms)) == EINVAL
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(TypeError):
+        rn.rnnlm_dedup(torch.zeros(4, dtype=torch.int64), torch.zeros(4, dtype=torch.int32),
+                       torch.zeros(4, dtype=torch.int32), torch.zeros(1, dtype=torch.int32),
+                       torch.zeros(1024, dtype=torch.uint8), stream=0)

@@ -1,0 +1,359 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on the seeded workloads.
+
+Tolerances (written here, from the target statement): grouping indices bit-exact; fp32
+models |dlogprob| <= 1e-5 and |dh| <= 1e-5; bf16 models (fp32-accumulated bf16 MFMA)
+|dlogprob| <= 2e-3 and |dh| <= 1e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2007_11794_amd as rn
+from workloads import CONFIGS, DecodeTrace, make_model, make_step_inputs
+
+from harness import gpu_dedup, gpu_step, gpu_step_dedup, load_model
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (2e-3, 1e-3)}      # (logprob, h)
+
+
+def check(gpu_h, gpu_lp, ref, dtype, what=""):
+    tol_lp, tol_h = TOL[dtype]
+    dh = np.max(np.abs(gpu_h.astype(np.float64) - ref["h_out"])) if gpu_h.size else 0.0
+    dlp = np.max(np.abs(gpu_lp.astype(np.float64) - ref["logprob"])) if gpu_lp.size else 0.0
+    print("%s max|dh|=%.3g max|dlogprob|=%.3g" % (what, dh, dlp), flush=True)
+    assert np.all(np.isfinite(gpu_h)) and np.all(np.isfinite(gpu_lp))
+    assert dh <= tol_h, (what, dh)
+    assert dlp <= tol_lp, (what, dlp)
+    return dh, dlp
+
+
+# ------------------------------------------------------------------------ config 1: tiny, fp32
+def test_config1_tiny_full():
+    cfg = CONFIGS[1]
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    m = load_model(model, cfg.dtype, cfg.B)
+    for lse_mode in (0, 1):
+        m.set_option(rn.OPT_LSE_MODE, lse_mode)
+        h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+        check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), "f32", "cfg1 lse_mode=%d" % lse_mode)
+    assert m.last_error() == 0
+    m.close()
+
+
+# ------------------------------------------------------------------------ config 2: WSJ-sized, fp32, chained
+def test_config2_chained_steps_full():
+    cfg = CONFIGS[2]
+    model = make_model(cfg)
+    rng = np.random.default_rng(cfg.seed)
+    m = load_model(model, cfg.dtype, cfg.B)
+    x = make_step_inputs(cfg, rng)
+    h_gpu = h_ref = x["h_in"]
+    for step in range(cfg.steps):
+        if step:
+            x = make_step_inputs(cfg, rng)           # fresh prev/query draws every step
+        ref = oracle.step(model, x["prev"], h_ref, x["query"])
+        # (a) per-step error: both sides start from the oracle's state
+        h1, lp1 = gpu_step(m, x["prev"], h_ref, x["query"])
+        check(h1, lp1, ref, "f32", "cfg2 step %d (same state)" % step)
+        # (b) accumulated error: the GPU keeps feeding on its own h_out
+        h2, lp2 = gpu_step(m, x["prev"], h_gpu, x["query"])
+        check(h2, lp2, ref, "f32", "cfg2 step %d (own state)" % step)
+        h_gpu = h2
+        h_ref = ref["h_out"].astype(np.float32)
+    assert m.last_error() == 0
+    m.close()
+
+
+# ------------------------------------------------------------------------ bf16: reduced sizes, element by element
+@pytest.mark.parametrize("V,H,B,K", [
+    (5000, 512, 300, 8),      # several row groups and word tiles, ragged tails in both
+    (777, 256, 130, 5),       # staged kernel at Hp = 256
+    (1000, 100, 70, 3),       # the paper's hidden size: H not a multiple of anything useful
+    (300, 64, 33, 2),
+])
+@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("lse_mode", [1, 2])
+def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
+    cfg = CONFIGS[3].scaled(V=V, H=H, B=B, K=K)
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
+    m = load_model(model, "bf16", B)
+    m.set_option(rn.OPT_LSE_MODE, lse_mode)
+    m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
+    h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+    check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), "bf16",
+          "bf16 V=%d H=%d B=%d kernel=%d lse=%d" % (V, H, B, kernel, lse_mode))
+    assert m.last_error() == 0
+    m.close()
+
+
+@pytest.mark.parametrize("V,H,B,K", [(3000, 200, 150, 6), (1000, 64, 8, 4)])
+def test_f32_reduced_elementwise_both_lse_modes(V, H, B, K):
+    cfg = CONFIGS[2].scaled(V=V, H=H, B=B, K=K)
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
+    m = load_model(model, "f32", B)
+    for lse_mode in (1, 2):
+        m.set_option(rn.OPT_LSE_MODE, lse_mode)
+        h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+        check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), "f32", "f32 V=%d lse=%d" % (V, lse_mode))
+    m.close()
+
+
+# ------------------------------------------------------------------------ config 3: headline, full size, sampled rows
+def sampled_rows_check(cfg, model, x, h, lp, rows, what):
+    ref = oracle.step(model, x["prev"][rows], x["h_in"][rows], x["query"][rows])
+    return check(h[rows], lp[rows], ref, cfg.dtype, what)
+
+
+def test_config3_headline_full_size_sampled():
+    cfg = CONFIGS[3]
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    m = load_model(model, cfg.dtype, cfg.B)
+    rng = np.random.default_rng(7)
+    rows = np.sort(np.concatenate([[0, cfg.B - 1], rng.choice(np.arange(1, cfg.B - 1), 46, replace=False)]))
+    outs = {}
+    for kernel in (0, 1):                 # the launch configuration bench.py times, and the plain kernel
+        m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
+        h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+        sampled_rows_check(cfg, model, x, h, lp, rows, "cfg3 kernel=%d (48 sampled rows)" % kernel)
+        outs[kernel] = (h, lp)
+    # every row, not only the sampled ones: the two kernels agree with each other
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.max(np.abs(outs[0][1] - outs[1][1])) <= 1e-4
+    # properties that hold at any size: finite, log-probabilities negative
+    assert np.all(np.isfinite(outs[0][1])) and np.all(outs[0][1] < 0)
+    assert m.last_error() == 0
+    m.close()
+
+
+# ------------------------------------------------------------------------ config 5: stress, full size, sampled rows
+def test_config5_stress_full_size_sampled():
+    cfg = CONFIGS[5]
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    m = load_model(model, cfg.dtype, cfg.B)
+    h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+    rows = np.sort(np.concatenate([[0, cfg.B - 1], np.random.default_rng(9).choice(np.arange(1, cfg.B - 1), 14, replace=False)]))
+    sampled_rows_check(cfg, model, x, h, lp, rows, "cfg5 (16 sampled rows)")
+    assert np.all(np.isfinite(lp)) and np.all(lp < 0) and np.all(np.isfinite(h))
+    assert m.last_error() == 0
+    m.close()
+
+
+# ------------------------------------------------------------------------ config 4: decode trace
+def test_config4_reduced_trace_elementwise():
+    """A small trace, every step compared in full, the GPU feeding on its own h_out and the
+    oracle on its own; grouping indices bit-exact every step."""
+    cfg = CONFIGS[4].scaled(V=3000, H=128, N=600, K=4, steps=6)
+    model = make_model(cfg)
+    m = load_model(model, "bf16", cfg.N)
+    tr_g, tr_o = DecodeTrace(cfg), DecodeTrace(cfg)
+    xg, xo = tr_g.first(), tr_o.first()
+    for step in range(cfg.steps):
+        assert np.array_equal(xg["keys"], xo["keys"]) and np.array_equal(xg["query"], xo["query"])
+        out = gpu_step_dedup(m, xg["keys"], xg["prev"], xg["h_in"], xg["query"])
+        U, rep, inv = oracle.dedup(xo["keys"])
+        assert out["n_unique"] == U == tr_o.U0
+        assert np.array_equal(out["rep"], rep) and np.array_equal(out["inverse"], inv)
+        assert np.all(np.isnan(out["h_out_rest"]))          # rows beyond n_unique stay untouched
+        ref = oracle.step(model, xo["prev"][rep], xo["h_in"][rep], xo["query"], row_of_query=inv)
+        # own-state drift grows slowly; the per-step bar still has to hold along the trace
+        check(out["h_out"], out["logprob"], ref, "bf16", "cfg4-reduced step %d" % step)
+        # duplicates of one history get bit-identical answers when they ask the same word
+        xg = tr_g.next(xg, out["h_out"], out["inverse"])
+        xo = tr_o.next(xo, ref["h_out"], inv)
+    assert m.last_error() == 0
+    m.close()
+
+
+def test_config4_full_size_trace():
+    """N = 4096 raw queries, about 30 % distinct, 50 steps at V = 65536, H = 512.  Every step:
+    grouping bit-exact against the oracle; carried-over histories score bit-identically to
+    the step before.  Steps 0, 24, 49: sampled rows against the oracle."""
+    cfg = CONFIGS[4]
+    model = make_model(cfg)
+    m = load_model(model, cfg.dtype, cfg.N)
+    tr = DecodeTrace(cfg)
+    x = tr.first()
+    prev_by_key = {}
+    rng = np.random.default_rng(11)
+    for step in range(cfg.steps):
+        out = gpu_step_dedup(m, x["keys"], x["prev"], x["h_in"], x["query"])
+        U, rep, inv = oracle.dedup(x["keys"])
+        assert out["n_unique"] == U == tr.U0, step
+        assert np.array_equal(out["rep"], rep) and np.array_equal(out["inverse"], inv), step
+        assert np.all(np.isfinite(out["logprob"])) and np.all(out["logprob"] < 0), step
+        # cache reuse: the same history id seen in the previous step gives the same h_out bits
+        keys_u = x["keys"][rep]
+        hits = 0
+        for u, k in enumerate(keys_u.tolist()):
+            if k in prev_by_key:
+                assert np.array_equal(out["h_out"][u], prev_by_key[k]), (step, u)
+                hits += 1
+        if step:
+            assert hits == int(x["carried"].sum()) > 0
+        prev_by_key = {k: out["h_out"][u].copy() for u, k in enumerate(keys_u.tolist())}
+        if step in (0, 24, 49):
+            rows_u = np.sort(rng.choice(U, 12, replace=False))
+            raw = np.flatnonzero(np.isin(inv, rows_u))
+            remap = {int(u): i for i, u in enumerate(rows_u)}
+            roq = np.array([remap[int(inv[n])] for n in raw], np.int32)
+            ref = oracle.step(model, x["prev"][rep[rows_u]], x["h_in"][rep[rows_u]], x["query"][raw], row_of_query=roq)
+            check(out["h_out"][rows_u], out["logprob"][raw], ref, "bf16", "cfg4 step %d (12 sampled histories)" % step)
+        x = tr.next(x, out["h_out"], out["inverse"])
+    assert m.last_error() == 0
+    m.close()
+
+
+# ------------------------------------------------------------------------ grouping of equal ids
+@pytest.mark.parametrize("N,distinct", [(0, 1), (1, 1), (2, 1), (63, 7), (1024, 1024), (4096, 1229), (4096, 1),
+                                        (4097, 1300), (100000, 30000), (100000, 100000), (50000, 3)])
+def test_dedup_bit_exact(N, distinct):
+    rng = np.random.default_rng(N * 7 + distinct)
+    pool = rng.integers(0, 2 ** 64, size=distinct, dtype=np.uint64)
+    pool[0] = np.uint64(0xFFFFFFFFFFFFFFFF)              # the all-ones id is an ordinary id
+    if distinct > 2:
+        pool[1], pool[2] = np.uint64(0), np.uint64(1) << np.uint64(63)
+    keys = pool[rng.integers(0, distinct, size=N)] if N else np.zeros(0, np.uint64)
+    if N == distinct:
+        keys = pool[rng.permutation(N)]
+    U, rep, inv = gpu_dedup(keys)
+    Uo, repo, invo = oracle.dedup(keys) if N <= 5000 else None_or_numpy(keys)
+    assert U == Uo
+    assert np.array_equal(rep, repo) and np.array_equal(inv, invo)
+    for _ in range(5):                                    # run-to-run identical
+        U2, rep2, inv2 = gpu_dedup(keys)
+        assert U2 == U and np.array_equal(rep2, rep) and np.array_equal(inv2, inv)
+
+
+def None_or_numpy(keys):
+    """For sizes where the quadratic oracle is slow: the first-appearance reordering of
+    numpy.unique, which tests/test_oracle_pins.py shows equal to the oracle."""
+    uniq, first, inv = np.unique(keys, return_index=True, return_inverse=True)
+    order = np.argsort(first, kind="stable")
+    rank = np.empty_like(order)
+    rank[order] = np.arange(len(order))
+    return len(uniq), first[order].astype(np.int32), rank[inv].astype(np.int32)
+
+
+# ------------------------------------------------------------------------ edge cases
+def small_model(dtype="bf16", V=500, H=64, seed=3):
+    cfg = CONFIGS[3].scaled(V=V, H=H, B=16, K=4, dtype=dtype)
+    return cfg, make_model(cfg, seed=seed)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_zero_initial_hidden_and_single_row(dtype):
+    cfg, model = small_model(dtype)
+    m = load_model(model, dtype, 16)
+    prev = np.array([7], np.int32)
+    h0 = np.zeros((1, cfg.H), np.float32)                 # utterance start: zero hidden vector
+    q = np.array([[0, 499, 7, 7]], np.int32)              # repeated query words are allowed
+    h, lp = gpu_step(m, prev, h0, q)
+    check(h, lp, oracle.step(model, prev, h0, q), dtype, "zero h_in, B=1")
+    assert lp[0, 2] == lp[0, 3]
+    m.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_empty_batches_are_no_ops(dtype):
+    cfg, model = small_model(dtype)
+    m = load_model(model, dtype, 16)
+    e_i = torch.zeros(0, dtype=torch.int32, device="cuda:0")
+    rn.rnnlm_step(m, e_i, torch.zeros((0, cfg.H), device="cuda:0"), torch.zeros((0, 4), dtype=torch.int32, device="cuda:0"),
+                  torch.zeros((0, cfg.H), device="cuda:0"), torch.zeros((0, 4), device="cuda:0"))
+    # K = 0: hidden update still happens
+    x = make_step_inputs(cfg, np.random.default_rng(0))
+    h, lp = gpu_step(m, x["prev"], x["h_in"], np.zeros((16, 0), np.int32))
+    ref = oracle.step(model, x["prev"], x["h_in"], np.zeros((16, 0), np.int32))
+    assert lp.shape == (16, 0)
+    assert np.max(np.abs(h - ref["h_out"])) <= TOL[dtype][1]
+    torch.cuda.synchronize()
+    assert m.last_error() == 0
+    m.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_row_of_query_fan_out_and_duplicates(dtype):
+    cfg, model = small_model(dtype)
+    m = load_model(model, dtype, 64)
+    rng = np.random.default_rng(5)
+    x = make_step_inputs(cfg, rng)
+    N = 50
+    roq = rng.integers(0, cfg.B, N).astype(np.int32)
+    q = rng.integers(0, cfg.V, (N, 4)).astype(np.int32)
+    q[10], roq[10] = q[3], roq[3]                        # a repeated lookup
+    h, lp = gpu_step(m, x["prev"], x["h_in"], q, row_of_query=roq)
+    check(h, lp, oracle.step(model, x["prev"], x["h_in"], q, row_of_query=roq), dtype, "fan-out")
+    assert np.array_equal(lp[10], lp[3])
+    m.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bad_indices_raise_flags_and_nan_only_where_they_apply(dtype):
+    cfg, model = small_model(dtype)
+    m = load_model(model, dtype, 64)
+    x = make_step_inputs(cfg, np.random.default_rng(1))
+    good_h, good_lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+    assert m.last_error() == 0
+    prev = x["prev"].copy(); prev[3] = cfg.V             # one past the end
+    q = x["query"].copy(); q[5, 1] = -1
+    h, lp = gpu_step(m, prev, x["h_in"], q)
+    assert m.last_error() == rn.FLAG_BAD_PREV_WORD | rn.FLAG_BAD_QUERY_WORD
+    assert m.last_error() == 0                            # reading clears the flag
+    assert np.all(np.isnan(h[3])) and np.all(np.isnan(lp[3]))
+    assert np.isnan(lp[5, 1])
+    ok_rows = [r for r in range(cfg.B) if r != 3]
+    assert np.array_equal(h[ok_rows], good_h[ok_rows])
+    mask = np.ones_like(lp, bool); mask[3] = False; mask[5, 1] = False
+    assert np.array_equal(lp[mask], good_lp[mask])
+    roq = np.arange(cfg.B, dtype=np.int32); roq[2] = cfg.B
+    h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"], row_of_query=roq)
+    assert m.last_error() == rn.FLAG_BAD_ROW
+    assert np.all(np.isnan(lp[2])) and np.array_equal(lp[[0, 1, 3]], good_lp[[0, 1, 3]])
+    m.close()
+
+
+def test_range_and_argument_errors_with_a_real_model():
+    cfg, model = small_model("bf16")
+    m = load_model(model, "bf16", 8)
+    x = make_step_inputs(cfg, np.random.default_rng(1))    # 16 rows > max_B = 8
+    with pytest.raises(rn.RnnlmError) as e:
+        gpu_step(m, x["prev"], x["h_in"], x["query"])
+    assert e.value.status == -4
+    h = torch.zeros((4, cfg.H), device="cuda:0")
+    with pytest.raises(rn.RnnlmError) as e:               # h_out aliasing h_in
+        rn.rnnlm_step(m, torch.zeros(4, dtype=torch.int32, device="cuda:0"), h,
+                      torch.zeros((4, 2), dtype=torch.int32, device="cuda:0"), h, torch.zeros((4, 2), device="cuda:0"))
+    assert e.value.status == -1
+    with pytest.raises(rn.RnnlmError):
+        m.set_option(99, 0)
+    m.close()
+    with pytest.raises(ValueError):
+        m.handle
+
+
+def test_running_maximum_fallback_when_logits_are_huge():
+    """Weights so large that no fixed offset fits fp32: the library must fall back to the
+    running maximum by itself, and the forced fixed offset must be refused."""
+    rng = np.random.default_rng(2)
+    V, H, B, K = 400, 64, 40, 4
+    model = {"U": rng.normal(0, 0.5, (V, H)).astype(np.float32), "W": rng.normal(0, 0.1, (H, H)).astype(np.float32),
+             "O": rng.normal(0, 4.0, (H, V)).astype(np.float32), "bias": rng.normal(0, 1, V).astype(np.float32)}
+    m = load_model(model, "f32", B)
+    with pytest.raises(rn.RnnlmError):
+        m.set_option(rn.OPT_LSE_MODE, 2)
+    prev, h_in, q = rng.integers(0, V, B), rng.random((B, H)), rng.integers(0, V, (B, K))
+    h, lp = gpu_step(m, prev, h_in, q)
+    ref = oracle.step(model, prev, h_in, q)
+    assert np.max(np.abs(h - ref["h_out"])) <= 1e-5
+    # logits are O(100): fp32 cannot hold them to 1e-5 absolute; 1e-6 relative to |z| can be asked
+    scale = np.max(np.abs(ref["logprob"]))
+    assert np.max(np.abs(lp - ref["logprob"])) <= 5e-6 * scale + 1e-5
+    m.close()
