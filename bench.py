@@ -1,0 +1,138 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched RNNLM step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One step = one pass of the whole hot path over one batch of the headline workload
+(V = 65536, H = 512, B = N = 1024 hypotheses, K = 32 query words each, bf16 weights):
+grouping of the history ids, hidden update, fused output projection + log-sum-exp, query
+gather -- a single rnnlm_step_dedup call, inputs already resident in HBM.  Prints ONE JSON
+line: whole-job hypothesis-steps/s, the roofline of the dominant kernel (output projection
++ log-sum-exp, MFMA-bound) timed with HIP events on its stream, and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--outproj-kernel", type=int, default=0, help="0 auto, 1 plain, 2 staged")
+    ap.add_argument("--lse-mode", type=int, default=0, help="0 auto, 1 running max, 2 fixed offset")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the step shards trivially over rows, "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2007_11794_amd as rn
+    from workloads import CONFIGS, bf16_bits, make_model, make_step_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    rn.lib()                                   # raises if librnnlm.so is not built
+    dev = "cuda:0"
+    cfg = CONFIGS[3]
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    m = rn.rnnlm_load(cfg.V, cfg.H, rn.RNNLM_BF16, bf16_bits(model["U"]), bf16_bits(model["W"]),
+                      bf16_bits(model["O"]), None, cfg.N)
+    m.set_option(rn.OPT_OUTPROJ_KERNEL, args.outproj_kernel)
+    m.set_option(rn.OPT_LSE_MODE, args.lse_mode)
+
+    N, K, H = cfg.N, cfg.K, cfg.H
+    keys = torch.from_numpy(x["keys"].view(np.int64)).to(dev)
+    prev = torch.from_numpy(x["prev"]).to(dev)
+    h_in = torch.from_numpy(x["h_in"]).to(dev)
+    query = torch.from_numpy(x["query"]).to(dev)
+    rep = torch.empty(N, dtype=torch.int32, device=dev)
+    inv = torch.empty(N, dtype=torch.int32, device=dev)
+    nu = torch.zeros(1, dtype=torch.int32, device=dev)
+    h_out = torch.zeros((N, H), device=dev)
+    lp = torch.zeros((N, K), device=dev)
+    ws = torch.empty(rn.rnnlm_dedup_workspace_bytes(N), dtype=torch.uint8, device=dev)
+
+    def step():
+        rn.rnnlm_step_dedup(m, keys, prev, h_in, query, rep, inv, nu, h_out, lp, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert int(nu.item()) == cfg.B and m.last_error() == 0
+    ms_per_step = dt / args.steps * 1e3
+    value = N * args.steps / dt
+
+    # dominant kernel: output projection + log-sum-exp, timed alone with HIP events on its stream
+    k3_ms = m.time_outproj(cfg.B, 50)
+    k3_ms = min(k3_ms, m.time_outproj(cfg.B, 50))
+    flops = 2.0 * cfg.B * cfg.H * cfg.V
+    achieved = flops / (k3_ms * 1e-3) / 1e12
+    roofline = {"kernel": "outproj_lse", "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # calibrate on one row per thread, then size the sample to roughly 12 s of wall time
+        threads = oracle.max_threads()
+        t = time.perf_counter()
+        oracle.step(model, x["prev"][:threads], x["h_in"][:threads], x["query"][:threads])
+        t_round = time.perf_counter() - t
+        rows = min(cfg.B, threads * max(1, int(round(12.0 / max(t_round, 1e-3)))))
+        t = time.perf_counter()
+        ref = oracle.step(model, x["prev"][:rows], x["h_in"][:rows], x["query"][:rows])
+        cdt = time.perf_counter() - t
+        err = float(np.max(np.abs(lp.cpu().numpy()[:rows] - ref["logprob"])))
+        cpu = {"value": round(rows / cdt, 2), "unit": "hypothesis-steps/s", "cores": threads, "kind": "oracle",
+               "sample": "first %d of %d rows of the same step (hidden update + full-vocabulary "
+                         "log-sum-exp + queries), %.1f s wall" % (rows, cfg.B, cdt),
+               "max_abs_dlogprob_vs_gpu": err}
+
+    out = {
+        "metric": "RNNLM hypothesis-steps/sec (V=65536,H=512,B=1024)",
+        "value": round(value, 1),
+        "unit": "hypothesis-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "large_vocab (headline): V=65536 H=512 B=N=1024 K=32, bf16 weights N(0,0.03), "
+                               "Zipf(1.1) word ids, h_in=sigmoid(N(0,1)), one step incl. history-id grouping",
+                   "V": cfg.V, "H": cfg.H, "B": cfg.B, "K": cfg.K},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    m.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

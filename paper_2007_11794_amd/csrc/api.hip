@@ -39,8 +39,8 @@ void free_dev(rnnlm_model *m) {
     (void)hipFree(const_cast<float *>(d.half_rowsum_W));
     (void)hipFree(const_cast<float *>(d.bias));
     (void)hipFree(const_cast<float *>(d.half_colsum_O));
-    (void)hipFree(const_cast<float *>(d.cvec));
-    (void)hipFree(const_cast<float *>(d.cvec_fixed));
+    (void)hipFree(const_cast<float *>(d.cvec2));
+    (void)hipFree(const_cast<float *>(d.cvec2_fixed));
     (void)hipFree(d.d);
     (void)hipFree(d.part);
     (void)hipFree(d.flag);
@@ -113,8 +113,8 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     HIP_TRY(hipMalloc(&p, (size_t)Hp * 4)); d.half_rowsum_W = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.bias = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.half_colsum_O = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec_fixed = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec2 = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec2_fixed = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.d = p;
     HIP_TRY(hipMalloc(&p, (size_t)max_Bp * kMaxSplits * sizeof(float2))); d.part = static_cast<float2 *>(p);
     HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
@@ -168,7 +168,7 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
         if (!isfinite(d.m2_fixed)) d.m2_fixed = 0.f;
     }
     HIP_TRY(launch_fill_cvec(bias_stage, d.half_colsum_O, V, Vp, d.m2_fixed, const_cast<float *>(d.bias),
-                             const_cast<float *>(d.cvec), const_cast<float *>(d.cvec_fixed), nullptr));
+                             const_cast<float *>(d.cvec2), const_cast<float *>(d.cvec2_fixed), nullptr));
     HIP_TRY(hipDeviceSynchronize());
     (void)hipFree(O_stage); (void)hipFree(bias_stage); (void)hipFree(upper); (void)hipFree(lower);
     *out = m;

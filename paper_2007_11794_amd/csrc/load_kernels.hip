@@ -61,9 +61,9 @@ __global__ __launch_bounds__(256) void fill_cvec_kernel(const float *__restrict_
     if (v < V) {
         float b = bias ? bias[v] : 0.f;
         bias_out[v] = b;
-        float c = b + half_colsum[v];
+        float c = (b + half_colsum[v]) * kLog2e;
         cvec[v] = c;
-        cvec_fixed[v] = c - m2_fixed * kLn2;
+        cvec_fixed[v] = c - m2_fixed;
     } else {
         cvec[v] = -INFINITY;
         cvec_fixed[v] = -INFINITY;

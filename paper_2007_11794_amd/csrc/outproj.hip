@@ -5,8 +5,8 @@
 // per vocabulary split, one (max, sum) pair of the base-2 log-sum-exp.
 //
 // With h' = 1/2 + d the logit is  z = (bias + 1/2 colsum(O)) + sum_j O[j][v] d[j]; the
-// bracket is the per-word constant cvec[v] the accumulators start from (-inf for the padded
-// words beyond V, which then add 2^-inf = 0).  Two ways to take the sum:
+// bracket, times log2(e), is the per-word constant cvec2[v] (-inf for the padded words
+// beyond V, which then add 2^-inf = 0).  Two ways to take the sum:
 //   running maximum  per lane (m, s): always valid;
 //   fixed offset     since |d| <= 1/2 every base-2 logit is <= m2_fixed, a bound computed
 //                    at load time; s = sum 2^(x - m2_fixed) needs no maximum and no
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void outproj_plain_bf16_kernel(
     const int Hp = m.Hp;
     const bf16_t *Ot = static_cast<const bf16_t *>(m.Ot);
     const bf16_t *drow = static_cast<const bf16_t *>(m.d) + (size_t)(b0 + col) * Hp;
-    const float *cvec = FIXED ? m.cvec_fixed : m.cvec;
+    const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
     const int split = blockIdx.x;
     const int nblocks = m.Vp / 32;
     const int blk_begin = split * blocks_per_split;
@@ -65,13 +65,7 @@ __global__ __launch_bounds__(256) void outproj_plain_bf16_kernel(
     for (int blk = blk_begin; blk < blk_end; ++blk) {
         const int v0 = blk * 32;
         const bf16_t *orow = Ot + (size_t)(v0 + col) * Hp;
-        f32x16 acc;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            f32x4 c = *reinterpret_cast<const f32x4 *>(cvec + v0 + 8 * q + 4 * g);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[4 * q + i] = c[i];
-        }
+        f32x16 acc = {0};
         for (int k0 = 8 * g; k0 < Hp; k0 += 16) {
             bf16x8 of = *reinterpret_cast<const bf16x8 *>(orow + k0);
             bf16x8 df = *reinterpret_cast<const bf16x8 *>(drow + k0);
@@ -79,7 +73,11 @@ __global__ __launch_bounds__(256) void outproj_plain_bf16_kernel(
         }
         float x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = acc[i] * kLog2e;
+        for (int q = 0; q < 4; ++q) {
+            f32x4 c = *reinterpret_cast<const f32x4 *>(cvec + v0 + 8 * q + 4 * g);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) x[4 * q + i] = fmaf(acc[4 * q + i], kLog2e, c[i]);
+        }
         lse2_accumulate16<FIXED>(x, mrun, srun);
     }
     // lanes l and l+32 hold the two halves of a row
@@ -104,7 +102,7 @@ __global__ __launch_bounds__(256) void outproj_plain_f32_kernel(
     const int Hp = m.Hp;
     const float *Ot = static_cast<const float *>(m.Ot);
     const float *d = static_cast<const float *>(m.d);
-    const float *cvec = FIXED ? m.cvec_fixed : m.cvec;
+    const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
     const int split = blockIdx.x;
     const int nblocks = m.Vp / kFN;
     const int blk_begin = split * blocks_per_split;
@@ -123,11 +121,11 @@ __global__ __launch_bounds__(256) void outproj_plain_f32_kernel(
     for (int blk = blk_begin; blk < blk_end; ++blk) {
         const int v0 = blk * kFN;
         float acc[4][4];
-        f32x4 cv = *reinterpret_cast<const f32x4 *>(cvec + v0 + tx * 4);
+        const f32x4 cv = *reinterpret_cast<const f32x4 *>(cvec + v0 + tx * 4);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[r][c] = cv[c];
+            for (int c = 0; c < 4; ++c) acc[r][c] = 0.f;
         for (int k0 = 0; k0 < Hp; k0 += kFK) {
             // rows of d beyond B are stale scratch; rows are independent, so whatever they
             // hold only reaches partials that are never written
@@ -151,7 +149,7 @@ __global__ __launch_bounds__(256) void outproj_plain_f32_kernel(
         for (int r = 0; r < 4; ++r) {
             float x[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) x[c] = acc[r][c] * kLog2e;
+            for (int c = 0; c < 4; ++c) x[c] = fmaf(acc[r][c], kLog2e, cv[c]);
             if (FIXED) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) srun[r] += fast_exp2(x[c]);

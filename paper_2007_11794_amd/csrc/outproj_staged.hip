@@ -8,13 +8,17 @@
 // weights are streamed exactly once per row group and the hidden block never moves:
 //   - a workgroup (8 waves) owns 256 rows; each wave keeps ITS 32 rows of d for the whole
 //     reduction length in registers (Hp/16 MFMA B-operands, 128 VGPRs at Hp = 512);
-//   - the weights of 64 words (64 x Hp bf16, 64 KB at Hp = 512) form one LDS stage, filled
-//     by direct global->LDS loads (no VGPR round trip) one tile ahead of use; two stages;
-//   - per tile a wave issues 2 x Hp/16 MFMA 32x32x16: A = 32 words x 16 k from LDS,
-//     B = 16 k x 32 rows from registers, so lane l holds 16 logits of ONE row and the sum
-//     over words stays inside the lane;
-//   - the exp-and-add of tile t is interleaved, instruction by instruction, with the MFMAs
-//     of tile t+1, so the vector ALU works in the shadow of the matrix core.
+//   - the weights of 32 words (32 x Hp bf16, 32 KB at Hp = 512) form one LDS stage; four
+//     stages are filled round-robin by direct global->LDS loads (no VGPR round trip), two to
+//     three blocks ahead of use;
+//   - per block a wave issues Hp/16 chained MFMA 32x32x16: A = 32 words x 16 k from LDS
+//     (read four steps ahead), B = 16 k x 32 rows from registers, so lane l holds 16 logits
+//     of ONE row and the sum over words stays inside the lane;
+//   - the exp-and-add of block i is interleaved, instruction by instruction, with the MFMAs
+//     of block i+1, so the vector ALU works in the shadow of the matrix core;
+//   - one workgroup barrier per block.  It publishes the landing of block i+1 while block i
+//     is being computed, so no wave ever waits at a barrier for data it is about to use, and
+//     the first operands of block i+1 are already in registers when block i ends.
 // LDS rows are XOR-swizzled in 16-byte chunks (chunk c of word r sits at c ^ (r & 15)) so
 // that the 16 lanes served together by one ds_read_b128 hit 16 different bank groups.  The
 // direct loads write LDS linearly (lane i -> base + 16 i), so the swizzle is applied on the
@@ -30,45 +34,157 @@ namespace rnnlm {
 
 namespace {
 
-typedef __attribute__((address_space(3))) void *lds_ptr_t;
-
-__device__ __forceinline__ lds_ptr_t to_lds(const void *p) {
-    return reinterpret_cast<lds_ptr_t>(reinterpret_cast<uintptr_t>(p));
-}
-
 constexpr int kThreads = 512;
-constexpr int kCvecBytes = kStagedWords * 4;
+constexpr int kStages = 4;
+constexpr int kCSlots = 8;                       // ring of per-block constants (32 floats each)
+constexpr int kCSlotBytes = kStagedWords * 4;
+constexpr int kPrefetch = 4;                     // A operands read this many k-steps ahead
 
 template <int HP>
 struct StagedCfg {
-    static constexpr int KS = HP / 16;                       // MFMA k-steps
+    static constexpr int KS = HP / 16;                       // MFMA k-steps per block
     static constexpr int CPR = HP / 8;                       // 16-byte chunks per word row
     static constexpr int kStageChunks = kStagedWords * CPR;
     static constexpr int kStageBytes = kStageChunks * 16;
-    static constexpr int kLoadsPerThread = kStageChunks / kThreads;
-    static constexpr int kLdsBytes = 2 * kStageBytes + 2 * kCvecBytes;
+    static constexpr int kLoadsPerThread = kStageChunks / kThreads;     // weight loads per block
+    static constexpr int kLoadsPerBlock = kLoadsPerThread + 1;          // + one for the constants
+    static constexpr int kLdsBytes = kStages * kStageBytes + kCSlots * kCSlotBytes;
     static_assert(kStageChunks % kThreads == 0, "stage must be a whole number of loads per thread");
     static_assert(CPR >= 16, "swizzle needs at least 16 chunks per row");
+    static_assert(kLoadsPerBlock <= 6, "s_waitcnt immediates below assume few loads per block");
 };
 
-// Start the direct global->LDS loads of one 64-word tile (weights and constants).
+// Direct global->LDS load of 16 bytes per lane: lane i of the wave writes LDS bytes
+// [lds_base + 16 i, lds_base + 16 i + 16) with the 16 bytes at sbase + voff (its own voff).
+// sbase and lds_base must be the same in all lanes (they travel in SGPRs / M0).  Written as
+// inline assembly on purpose: when the compiler knows of a pending LDS-DMA it makes every
+// later LDS read wait for ALL outstanding LDS reads (lgkmcnt(0)) instead of just its own,
+// which stalls the MFMA pipeline; completion is awaited explicitly with vmcnt before the
+// workgroup barrier that publishes the data.
+__device__ __forceinline__ void lds_dma_16(const void *sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)reinterpret_cast<uintptr_t>(p);         // LDS offsets are the low 32 bits
+}
+
+// Wait until at most N of this wave's vector-memory operations are outstanding.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 16, "");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);                  // lgkmcnt and expcnt left alone
+}
+
+// Per-thread constants of the block loader.
 template <int HP>
-__device__ __forceinline__ void issue_tile_loads(const bf16_t *__restrict__ Ot,
-                                                 const float *__restrict__ cvec, int v0, char *stage,
-                                                 char *cstage) {
-    using C = StagedCfg<HP>;
-    const int tid = threadIdx.x, wave = tid >> 6;
+struct Loader {
+    uint32_t voff[StagedCfg<HP>::kLoadsPerThread];           // byte offset in the block of words
+    uint32_t wave;                                           // wave index, in an SGPR
+    int lane;
+    __device__ __forceinline__ void init() {
+        using C = StagedCfg<HP>;
+        const int tid = threadIdx.x;
+        wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        lane = tid & 63;
 #pragma unroll
-    for (int q = 0; q < C::kLoadsPerThread; ++q) {
-        const int f = q * kThreads + tid;                    // physical chunk this lane fills
-        const int r = f / C::CPR, p = f % C::CPR;
-        const int c = p ^ (r & 15);                          // logical chunk that belongs there
-        const bf16_t *src = Ot + (size_t)(v0 + r) * HP + c * 8;
-        char *dst_wave = stage + (size_t)(q * kThreads + wave * 64) * 16;   // wave-uniform base
-        __builtin_amdgcn_global_load_lds(src, to_lds(dst_wave), 16, 0, 0);
+        for (int q = 0; q < C::kLoadsPerThread; ++q) {
+            const int f = q * kThreads + tid;                // physical chunk this lane fills
+            const int r = f / C::CPR, p = f % C::CPR;
+            const int c = p ^ (r & 15);                      // logical chunk that belongs there
+            voff[q] = (uint32_t)(r * HP * 2 + c * 16);
+        }
     }
-    if (tid < kStagedWords / 4)
-        __builtin_amdgcn_global_load_lds(cvec + v0 + tid * 4, to_lds(cstage), 16, 0, 0);
+    // Start the loads of the 32-word block whose first word is v0 into stage / constant slot.
+    __device__ __forceinline__ void issue(const bf16_t *Ot, const float *cvec, int v0, uint32_t stage_lds,
+                                          uint32_t cslot_lds) const {
+        using C = StagedCfg<HP>;
+        const bf16_t *blk = Ot + (size_t)v0 * HP;
+#pragma unroll
+        for (int q = 0; q < C::kLoadsPerThread; ++q)
+            lds_dma_16(blk, voff[q], stage_lds + (q * kThreads + wave * 64) * 16);
+        // the 32 constants of the block: 16 bytes per wave, by its lane 0
+        if (lane == 0) lds_dma_16(cvec + v0, wave * 16, cslot_lds + wave * 16);
+    }
+};
+
+// Fold sixteen base-2 logits of one row into the (max, sum) pair.
+template <bool FIXED>
+__device__ __forceinline__ void lse2_fold16(const float (&x)[16], float &mrun, float &srun) {
+    if (FIXED) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) srun += fast_exp2(x[i]);          // offset already inside x
+    } else {
+        float mx = x[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
+        const float mn = fmaxf(mrun, mx);
+        if (mn != -INFINITY) {
+            float tsum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tsum += fast_exp2(x[i] - mn);
+            srun = srun * fast_exp2(mrun - mn) + tsum;
+            mrun = mn;
+        }
+    }
+}
+
+// Base-2 logits of a finished block: x = acc * log2(e) + c2, c2 = the block's constants.
+__device__ __forceinline__ void finish_logits(const f32x16 &acc, const f32x4 *cn, int g, float (&x)[16]) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f32x4 c = cn[2 * q + g];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[4 * q + i] = fmaf(acc[4 * q + i], kLog2e, c[i]);
+    }
+}
+
+#define RNNLM_A_FRAG(stage, ks) \
+    (*reinterpret_cast<const bf16x8 *>((stage) + aoff[(ks) & 7] + ((ks) >> 3) * 256))
+
+// One 32-word block for this wave's 32 rows.
+//   stage      LDS stage of this block; a[] already holds its first kPrefetch A operands
+//   next_stage LDS stage of the following block (nullptr: none); on return a[] holds ITS first
+//              kPrefetch A operands -- that block was published one barrier earlier
+//   pacc, pcn  the previous block's raw accumulators and its constants: its exp-and-add is
+//              spread over this block's k-steps (fixed offset) or done up front (running max)
+template <int HP, bool FIXED>
+__device__ __forceinline__ void staged_block(const char *stage, const char *next_stage, const int (&aoff)[8],
+                                             bf16x8 (&a)[kPrefetch], const bf16x8 (&dreg)[HP / 16], int g,
+                                             f32x16 &pacc, const f32x4 *pcn, float &mrun, float &srun) {
+    constexpr int KS = HP / 16;
+    static_assert(KS >= 2 * kPrefetch, "");
+    f32x16 acc = {0};
+    if (!FIXED) {
+        float x[16];
+        finish_logits(pacc, pcn, g, x);
+        lse2_fold16<false>(x, mrun, srun);
+    }
+    f32x4 c = pcn[g];                                         // constants of logits 0..3
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 cur = a[ks % kPrefetch];
+        if (ks + kPrefetch < KS) a[ks % kPrefetch] = RNNLM_A_FRAG(stage, ks + kPrefetch);
+        else if (next_stage) a[ks % kPrefetch] = RNNLM_A_FRAG(next_stage, ks + kPrefetch - KS);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[ks], acc, 0, 0, 0);
+        if (FIXED) {
+            // sixteen logits of the previous block spread evenly over the KS steps; the
+            // constants of the next four are requested one step before they are needed
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if ((e * KS) / 16 == ks) srun += fast_exp2(fmaf(pacc[e], kLog2e, c[e % 4]));
+#pragma unroll
+            for (int q = 1; q < 4; ++q)
+                if (ks == (4 * q * KS) / 16 - 1) c = pcn[2 * q + g];
+        }
+        // keep this order: the compiler's scheduler would otherwise sink every LDS read to
+        // just before its MFMA and expose the LDS latency on each step
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    pacc = acc;
 }
 
 template <int HP, bool FIXED>
@@ -78,133 +194,85 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
     using C = StagedCfg<HP>;
     constexpr int KS = C::KS;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    char *const cring = lds + kStages * C::kStageBytes;
     const int B = B_dev ? *B_dev : rows;
     const StagedPlan plan = staged_plan(B, wg_per_xcd);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
     const bf16_t *Ot = static_cast<const bf16_t *>(m.Ot);
-    const float *cvec = FIXED ? m.cvec_fixed : m.cvec;
-    const int T = m.Vp / kStagedWords;
+    const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
+    const int T = m.Vp / kStagedWords;                       // 32-word blocks in the vocabulary
     const int items = plan.RG * plan.Sx;
-    const int swz = col & 15;
+    const uint32_t lds0 = lds_address(lds), cring0 = lds_address(cring);
+    Loader<HP> loader;
+    loader.init();
+    // Swizzled LDS offsets of this lane's A operand: chunk (2 ks + g) of word `col`.  Only the
+    // low 4 bits of the chunk index take part in the swizzle, so eight per-lane offsets
+    // (aoff[ks % 8]) plus compile-time constants cover all k-steps.
+    int aoff[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) aoff[j] = col * (C::CPR * 16) + ((((2 * j) | g) ^ (col & 15)) * 16);
 
     for (int item = local; item < items; item += wg_per_xcd) {
         const int rg = item % plan.RG, split = xcd + kXcds * (item / plan.RG);
-        const int t_begin = (int)(((long long)split * T) / plan.S);
-        const int t_end = (int)(((long long)(split + 1) * T) / plan.S);
+        const int blk0 = (int)(((long long)split * T) / plan.S);
+        const int nblk = (int)(((long long)(split + 1) * T) / plan.S) - blk0;
         const int b = rg * kStagedRows + wave * 32 + col;     // this lane's row
 
-        // this wave's rows of d, all k, as MFMA B-operands (rows beyond B hold stale finite or
-        // NaN scratch; rows are independent and those lanes' results are dropped)
+        // Blocks 0 and 1 first, then this wave's rows of d (all k, as MFMA B operands; rows
+        // beyond B hold stale scratch: rows are independent and those lanes' results are dropped).
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (i < nblk)
+                loader.issue(Ot, cvec, (blk0 + i) * kStagedWords, lds0 + i * C::kStageBytes, cring0 + i * kCSlotBytes);
         bf16x8 dreg[KS];
         {
             const bf16_t *drow = static_cast<const bf16_t *>(m.d) + (size_t)b * HP + 8 * g;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) dreg[ks] = *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
         }
-
         float mrun = FIXED ? m.m2_fixed : -INFINITY, srun = 0.f;
-        // logits of the previous tile, still to be exponentiated; -inf adds 2^-inf = 0
-        f32x16 pacc0, pacc1;
+        // raw accumulators of the previous block, still to be exponentiated; -inf adds 2^-inf = 0
+        f32x16 pacc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { pacc0[i] = -INFINITY; pacc1[i] = -INFINITY; }
+        for (int i = 0; i < 16; ++i) pacc[i] = -INFINITY;
 
-        if (t_begin < t_end)
-            issue_tile_loads<HP>(Ot, cvec, t_begin * kStagedWords, lds, lds + 2 * C::kStageBytes);
+        wait_vmcnt<0>();
+        __syncthreads();                                      // blocks 0 and 1 are published
+#pragma unroll
+        for (int i = 2; i < 4; ++i)
+            if (i < nblk)
+                loader.issue(Ot, cvec, (blk0 + i) * kStagedWords, lds0 + i * C::kStageBytes, cring0 + i * kCSlotBytes);
 
-        for (int t = t_begin; t < t_end; ++t) {
-            const int sidx = (t - t_begin) & 1;
-            char *stage = lds + sidx * C::kStageBytes;
-            const char *cstage = lds + 2 * C::kStageBytes + sidx * kCvecBytes;
-            __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): my loads of tile t landed
-            __syncthreads();                                  // everyone's landed; stage sidx^1 is free
-            if (t + 1 < t_end)
-                issue_tile_loads<HP>(Ot, cvec, (t + 1) * kStagedWords, lds + (sidx ^ 1) * C::kStageBytes,
-                                     lds + 2 * C::kStageBytes + (sidx ^ 1) * kCvecBytes);
-
-            // accumulators start from the per-word constants
-            f32x16 acc0, acc1;
-            {
-                const f32x4 *cn = reinterpret_cast<const f32x4 *>(cstage);
+        bf16x8 a[kPrefetch];
+        if (nblk > 0) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4 c0 = cn[2 * q + g], c1 = cn[8 + 2 * q + g];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) { acc0[4 * q + i] = c0[i]; acc1[4 * q + i] = c1[i]; }
-                }
-            }
-            const char *row0 = stage + (size_t)col * (C::CPR * 16);
-            const char *row1 = row0 + (size_t)32 * (C::CPR * 16);
-
-            if (FIXED) {
-                // one slice of the previous tile's exp-and-add per k-step
-                constexpr int EPS = 32 / KS > 0 ? 32 / KS : 1;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const int p = ((2 * ks + g) ^ swz) * 16;
-                    bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(row0 + p);
-                    bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(row1 + p);
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, dreg[ks], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, dreg[ks], acc1, 0, 0, 0);
-#pragma unroll
-                    for (int e = ks * EPS; e < (ks + 1) * EPS && e < 32; ++e) {
-                        float z = e < 16 ? pacc0[e & 15] : pacc1[e & 15];
-                        srun += fast_exp2(z * kLog2e);
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const int p = ((2 * ks + g) ^ swz) * 16;
-                    bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(row0 + p);
-                    bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(row1 + p);
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, dreg[ks], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, dreg[ks], acc1, 0, 0, 0);
-                    if (ks == KS / 4 || ks == (3 * KS) / 4) {
-                        const f32x16 &pa = (ks == KS / 4) ? pacc0 : pacc1;
-                        float mx = pa[0];
-#pragma unroll
-                        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, pa[i]);
-                        mx *= kLog2e;
-                        const float mn = fmaxf(mrun, mx);
-                        if (mn != -INFINITY) {
-                            float tsum = 0.f;
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) tsum += fast_exp2(fmaf(pa[i], kLog2e, -mn));
-                            srun = srun * fast_exp2(mrun - mn) + tsum;
-                            mrun = mn;
-                        }
-                    }
-                }
-            }
-            pacc0 = acc0;
-            pacc1 = acc1;
+            for (int i = 0; i < kPrefetch; ++i) a[i] = RNNLM_A_FRAG(lds, i);
         }
-
-        {                                                     // the last tile's exp-and-add
-            if (FIXED) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) srun += fast_exp2(pacc0[i] * kLog2e);
-#pragma unroll
-                for (int i = 0; i < 16; ++i) srun += fast_exp2(pacc1[i] * kLog2e);
-            } else {
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const f32x16 &pa = h ? pacc1 : pacc0;
-                    float mx = pa[0];
-#pragma unroll
-                    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, pa[i]);
-                    mx *= kLog2e;
-                    const float mn = fmaxf(mrun, mx);
-                    if (mn != -INFINITY) {
-                        float tsum = 0.f;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) tsum += fast_exp2(fmaf(pa[i], kLog2e, -mn));
-                        srun = srun * fast_exp2(mrun - mn) + tsum;
-                        mrun = mn;
-                    }
-                }
+        for (int bi = 0; bi < nblk; ++bi) {
+            if (bi > 0) {
+                // Publish block bi+1: my loads of it have landed (the only younger ones are
+                // those of block bi+2), then everybody's.  Everybody is also done with block
+                // bi-1, so its stage takes block bi+3.
+                if (bi + 2 < nblk) wait_vmcnt<C::kLoadsPerBlock>();
+                else wait_vmcnt<0>();
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if (bi + 3 < nblk)
+                    loader.issue(Ot, cvec, (blk0 + bi + 3) * kStagedWords, lds0 + ((bi + 3) & 3) * C::kStageBytes,
+                                 cring0 + ((bi + 3) & 7) * kCSlotBytes);
             }
+            const char *stage = lds + (bi & 3) * C::kStageBytes;
+            const char *next_stage = (bi + 1 < nblk) ? lds + ((bi + 1) & 3) * C::kStageBytes : nullptr;
+            // constants of the previous block (for block 0 any landed slot: its pacc is -inf)
+            const f32x4 *pcn = reinterpret_cast<const f32x4 *>(cring + ((bi ? bi - 1 : 0) & 7) * kCSlotBytes);
+            staged_block<HP, FIXED>(stage, next_stage, aoff, a, dreg, g, pacc, pcn, mrun, srun);
+        }
+        if (nblk > 0) {                                       // the last block's exp-and-add
+            float x[16];
+            finish_logits(pacc, reinterpret_cast<const f32x4 *>(cring + ((nblk - 1) & 7) * kCSlotBytes), g, x);
+            lse2_fold16<FIXED>(x, mrun, srun);
         }
         // lanes l and l+32 hold the two halves of a row
         const float m2 = __shfl_xor(mrun, 32, 64), s2 = __shfl_xor(srun, 32, 64);
@@ -214,6 +282,7 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
         __syncthreads();                                      // LDS is reused by the next item
     }
 }
+#undef RNNLM_A_FRAG
 
 template <int HP>
 hipError_t launch_hp(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset, int wg_per_xcd,

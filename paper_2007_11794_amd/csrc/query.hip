@@ -13,6 +13,8 @@ namespace rnnlm {
 
 namespace {
 
+constexpr int kQueryBatch = 8;
+
 template <typename T>
 __global__ __launch_bounds__(256) void query_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K, SplitInfo si,
@@ -43,22 +45,41 @@ __global__ __launch_bounds__(256) void query_kernel(
     const T *Ot = static_cast<const T *>(m.Ot);
     const float *hrow = h_out + (size_t)r * H;
     const bool vec_ok = (H % 4) == 0;
-    for (int k = wave; k < K; k += 4) {
-        const int q = query_word[(size_t)n * K + k];
-        if (q < 0 || q >= m.V) {
-            if (lane == 0) { atomicOr(m.flag, RNNLM_FLAG_BAD_QUERY_WORD); out[k] = quiet_nan(); }
-            continue;
-        }
-        float acc = 0.f;
-        for (int j0 = lane * 8; j0 < Hp; j0 += 512) {
-            float w8[8], h8[8];
-            load8_weights(Ot, (size_t)q * Hp + j0, w8);
-            load8_row(hrow, j0, H, vec_ok, 0.f, h8);
+    // A wave answers the queries k = wave, wave + 4, ...; kQueryBatch of them at a time so
+    // that their weight rows are all requested before the first is used.
+    for (int kb = wave; kb < K; kb += 4 * kQueryBatch) {
+        int q[kQueryBatch];
+        bool ok[kQueryBatch];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc = fmaf(w8[i], h8[i], acc);
+        for (int u = 0; u < kQueryBatch; ++u) {
+            const int k = kb + 4 * u;
+            q[u] = (k < K) ? query_word[(size_t)n * K + k] : 0;
+            ok[u] = (k < K) && q[u] >= 0 && q[u] < m.V;
         }
-        acc = wave_sum(acc);
-        if (lane == 0) out[k] = (acc + m.bias[q]) - lse;
+        float acc[kQueryBatch];
+#pragma unroll
+        for (int u = 0; u < kQueryBatch; ++u) acc[u] = 0.f;
+        for (int j0 = lane * 8; j0 < Hp; j0 += 512) {
+            float h8[8];
+            load8_row(hrow, j0, H, vec_ok, 0.f, h8);
+            float w8[kQueryBatch][8];
+#pragma unroll
+            for (int u = 0; u < kQueryBatch; ++u) load8_weights(Ot, (size_t)(ok[u] ? q[u] : 0) * Hp + j0, w8[u]);
+#pragma unroll
+            for (int u = 0; u < kQueryBatch; ++u)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[u] = fmaf(w8[u][i], h8[i], acc[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kQueryBatch; ++u) {
+            const int k = kb + 4 * u;
+            if (k >= K) continue;                        // wave-uniform
+            const float z = wave_sum(acc[u]);
+            if (lane == 0) {
+                if (ok[u]) out[k] = (z + m.bias[q[u]]) - lse;
+                else { atomicOr(m.flag, RNNLM_FLAG_BAD_QUERY_WORD); out[k] = quiet_nan(); }
+            }
+        }
     }
 }
 

@@ -24,19 +24,26 @@ __device__ __forceinline__ float sigmoid_f32(float a) {
 }
 
 // ----------------------------------------------------------------------------- bf16 / MFMA
-// One wave computes a 32 (units j) x 32 (rows b) block: D[j][b] = sum_i W[j][i] d[b][i].
+// A workgroup of 4 waves computes a 32 (units j) x 32 (rows b) block
+// D[j][b] = sum_i W[j][i] d[b][i]; wave w takes the quarter w of the reduction length and
+// issues all of its loads before the first MFMA (the kernel is bound by load latency, not
+// by bytes or flops), the four partial blocks are added through LDS, and wave w finishes
+// the units 8 w .. 8 w + 7 of the block.
 // MFMA 32x32x16 operand layout (lane l, g = l / 32):
 //   A: 8 consecutive k of row (l % 32), starting at 8 g;   B: same for column (l % 32);
 //   D: acc[i] is row 8 (i / 4) + 4 g + i % 4, column l % 32.
-__global__ __launch_bounds__(64) void recur_bf16_kernel(
+constexpr int kRecurUnroll = 8;      // k-steps whose loads are in flight together
+
+__global__ __launch_bounds__(256) void recur_bf16_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
     float *__restrict__ h_out) {
     const int B = B_dev ? *B_dev : rows;
     const int b0 = blockIdx.y * 32;
     if (b0 >= B) return;
+    __shared__ f32x4 red[4][4][64];                  // [source wave][quarter of acc][lane]
     const int j0 = blockIdx.x * 32;
-    const int lane = threadIdx.x, col = lane & 31, g = lane >> 5;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, col = lane & 31, g = lane >> 5;
     const int H = m.H, Hp = m.Hp;
     const bf16_t *W = static_cast<const bf16_t *>(m.W);
     const bf16_t *U = static_cast<const bf16_t *>(m.U);
@@ -48,57 +55,72 @@ __global__ __launch_bounds__(64) void recur_bf16_kernel(
     const bool vec_ok = (H % 4) == 0;
     const bf16_t *wrow = W + (size_t)(j0 + col) * Hp;
 
-    f32x16 acc = {0};
-    for (int k0 = 8 * g; k0 < Hp; k0 += 16) {
-        bf16x8 wf = *reinterpret_cast<const bf16x8 *>(wrow + k0);
-        float h8[8];
-        if (row_ok) load8_row(hrow, k0, H, vec_ok, 0.5f, h8);
-        else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) h8[i] = 0.5f;
-        }
-        u32x4 hi, lo;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float d0 = h8[2 * i] - 0.5f, d1 = h8[2 * i + 1] - 0.5f;
-            uint16_t h0 = f32_to_bf16(d0), h1 = f32_to_bf16(d1);
-            hi[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-            lo[i] = pack_bf16x2(d0 - bf16_to_f32(h0), d1 - bf16_to_f32(h1));
-        }
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, hi), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, lo), acc, 0, 0, 0);
-    }
+    // this lane finishes the four units j = j0 + 8 wave + 4 g .. +3 of row b
+    const int je = j0 + 8 * wave + 4 * g;
+    const int w = row_ok ? prev_word[src] : 0;          // its embedding row is fetched below,
+    const f32x4 rs = *reinterpret_cast<const f32x4 *>(m.half_rowsum_W + je);   // after the operands
 
-    if (!row_ok) return;
-    const int w = prev_word[src];
+    const int kq = Hp / 4;                           // this wave's share of k (a multiple of 16)
+    const int k_begin = wave * kq + 8 * g, k_end = (wave + 1) * kq;
+    f32x16 acc = {0};
+    for (int kb = k_begin; kb < k_end; kb += 16 * kRecurUnroll) {
+        bf16x8 wf[kRecurUnroll];
+        float h8[kRecurUnroll][8];
+#pragma unroll
+        for (int u = 0; u < kRecurUnroll; ++u) {
+            const int k0 = kb + 16 * u;
+            if (k0 < k_end) {
+                wf[u] = *reinterpret_cast<const bf16x8 *>(wrow + k0);
+                if (row_ok) load8_row(hrow, k0, H, vec_ok, 0.5f, h8[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kRecurUnroll; ++u) {
+            const int k0 = kb + 16 * u;
+            if (k0 < k_end) {
+                u32x4 hi, lo;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float d0 = row_ok ? h8[u][2 * i] - 0.5f : 0.f, d1 = row_ok ? h8[u][2 * i + 1] - 0.5f : 0.f;
+                    hi[i] = pack_bf16x2(d0, d1);
+                    lo[i] = pack_bf16x2(d0 - __uint_as_float(hi[i] << 16), d1 - __uint_as_float(hi[i] & 0xFFFF0000u));
+                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], __builtin_bit_cast(bf16x8, hi), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u], __builtin_bit_cast(bf16x8, lo), acc, 0, 0, 0);
+            }
+        }
+    }
     const bool w_ok = (w >= 0 && w < m.V);
-    if (!w_ok && g == 0 && blockIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
-    const bf16_t *urow = U + (size_t)(w_ok ? w : 0) * Hp;
-    bf16_t *drow = static_cast<bf16_t *>(m.d) + (size_t)b * Hp;
+    const uint2 u4 = *reinterpret_cast<const uint2 *>(U + (size_t)(w_ok ? w : 0) * Hp + je);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int j = j0 + 8 * q + 4 * g;              // four consecutive units
-        uint2 u4 = *reinterpret_cast<const uint2 *>(urow + j);
-        f32x4 rs = *reinterpret_cast<const f32x4 *>(m.half_rowsum_W + j);
-        float u[4] = {__uint_as_float(u4.x << 16), __uint_as_float(u4.x & 0xFFFF0000u),
-                      __uint_as_float(u4.y << 16), __uint_as_float(u4.y & 0xFFFF0000u)};
-        float hp[4];
+    for (int q = 0; q < 4; ++q)
+        red[wave][q][lane] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+    __syncthreads();
+    if (!row_ok) return;
+    f32x4 a4 = red[0][wave][lane];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float a = acc[4 * q + i] + rs[i] + u[i];
-            hp[i] = w_ok ? sigmoid_f32(a) : quiet_nan();
-        }
-        uint2 dpk;
-        dpk.x = pack_bf16x2(hp[0] - 0.5f, hp[1] - 0.5f);
-        dpk.y = pack_bf16x2(hp[2] - 0.5f, hp[3] - 0.5f);
-        *reinterpret_cast<uint2 *>(drow + j) = dpk;   // padded units get sigmoid(0) - 1/2 = 0
-        if (vec_ok && j + 4 <= H) {
-            *reinterpret_cast<f32x4 *>(h_out + (size_t)b * H + j) = f32x4{hp[0], hp[1], hp[2], hp[3]};
-        } else {
+    for (int sw = 1; sw < 4; ++sw) {                 // fixed order: deterministic
+        f32x4 t = red[sw][wave][lane];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (j + i < H) h_out[(size_t)b * H + j + i] = hp[i];
-        }
+        for (int i = 0; i < 4; ++i) a4[i] += t[i];
+    }
+    if (!w_ok && g == 0 && wave == 0 && blockIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
+    const float u[4] = {__uint_as_float(u4.x << 16), __uint_as_float(u4.x & 0xFFFF0000u),
+                        __uint_as_float(u4.y << 16), __uint_as_float(u4.y & 0xFFFF0000u)};
+    float hp[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) hp[i] = w_ok ? sigmoid_f32(a4[i] + rs[i] + u[i]) : quiet_nan();
+    uint2 dpk;
+    dpk.x = pack_bf16x2(hp[0] - 0.5f, hp[1] - 0.5f);
+    dpk.y = pack_bf16x2(hp[2] - 0.5f, hp[3] - 0.5f);
+    // padded units (zero weights, zero embedding) come out as sigmoid(0) - 1/2 = 0
+    *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
+    if (vec_ok && je + 4 <= H) {
+        *reinterpret_cast<f32x4 *>(h_out + (size_t)b * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (je + i < H) h_out[(size_t)b * H + je + i] = hp[i];
     }
 }
 
@@ -173,7 +195,7 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16) {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);
-        hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(64), 0, stream, m, rows, B_dev, row_src,
+        hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
                            prev_word, h_in, h_out);
     } else {
         dim3 grid(m.Hp / kRJ, (rows + kRB - 1) / kRB);

@@ -27,10 +27,10 @@ struct ModelDev {
     const float *half_rowsum_W;   // [Hp]  0.5 * sum_i W[j][i]
     const float *bias;            // [V]
     const float *half_colsum_O;   // [V]   0.5 * sum_j O[j][v]
-    // Additive constant of every logit, bias[v] + 0.5*colsum_O[v]; -inf for the padded
-    // words v >= V so they add nothing to the sum.
-    const float *cvec;            // [Vp]
-    const float *cvec_fixed;      // [Vp]  cvec - m2_fixed * ln 2
+    // Additive constant of every base-2 logit, (bias[v] + 0.5*colsum_O[v]) * log2(e); -inf
+    // for the padded words v >= V so they add nothing to the sum.
+    const float *cvec2;           // [Vp]
+    const float *cvec2_fixed;     // [Vp]  cvec2 - m2_fixed
     float m2_fixed;    // upper bound of every base-2 logit z*log2(e), valid because |h' - 0.5| <= 0.5
     // scratch
     void *d;           // [max_Bp][Hp]  h' - 0.5 in the weights' type
@@ -74,7 +74,7 @@ struct SplitInfo {
 };
 
 constexpr int kStagedRows = 256;   // rows per workgroup of the staged kernel
-constexpr int kStagedWords = 64;   // words per LDS stage
+constexpr int kStagedWords = 32;   // words per LDS stage
 constexpr int kXcds = 8;           // workgroup id modulo 8 = the XCD (L2 domain) it runs on
 
 // Work split of the staged kernel for B rows on a grid of kXcds * wg_per_xcd workgroups:
@@ -109,7 +109,7 @@ hipError_t launch_col_stats(const void *O_dev, const float *bias_or_null, int dt
                             float *half_colsum /*[V]*/, float *upper /*[V]*/, float *lower /*[V]*/,
                             hipStream_t stream);
 hipError_t launch_fill_cvec(const float *bias_or_null, const float *half_colsum, int V, int Vp,
-                            float m2_fixed, float *bias_out, float *cvec, float *cvec_fixed,
+                            float m2_fixed, float *bias_out, float *cvec2, float *cvec2_fixed,
                             hipStream_t stream);
 
 }  // namespace rnnlm
