@@ -32,6 +32,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--outproj-kernel", type=int, default=0, help="0 auto, 1 plain, 2 staged")
     ap.add_argument("--lse-mode", type=int, default=0, help="0 auto, 1 running max, 2 fixed offset")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy kernel, as the known-size "
+                         "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the step shards trivially over rows, "
@@ -70,6 +73,13 @@ def main() -> int:
 
     def step():
         rn.rnnlm_step_dedup(m, keys, prev, h_in, query, rep, inv, nu, h_out, lp, ws)
+
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
