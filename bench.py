@@ -22,6 +22,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published
+# HBM bytes per launch of the output-projection kernel on this workload, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain copy of known size; cannot be measured live.
+# Source and commands: profiles/step_kernels_cfg3_large_vocab_hbm_traffic.md
+OUTPROJ_TRAFFIC_BYTES = {"staged": 78.0e6}
 
 
 def main() -> int:
@@ -99,7 +103,9 @@ def main() -> int:
     flops = 2.0 * cfg.B * cfg.H * cfg.V
     achieved = flops / (k3_ms * 1e-3) / 1e12
     roofline = {"kernel": "outproj_lse", "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) else None,
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
                 "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
 
     cpu = None
