@@ -63,8 +63,9 @@ enum rnnlm_option {
      * 1 = always the running maximum;  2 = always the fixed offset (EINVAL if unusable). */
     RNNLM_OPT_LSE_MODE = 1,
     /* Which output-projection kernel: 0 = automatic (default), 1 = the plain any-shape
-     * kernel, 2 = the LDS-staged kernel with the hidden block held in registers
-     * (EINVAL if the model's shape does not allow it). */
+     * kernel, 2 = the LDS-staged kernel with the hidden block held in registers (bf16,
+     * H <= 512), 3 = the LDS-tiled kernel for any hidden size (bf16).  EINVAL if the model
+     * does not allow the choice. */
     RNNLM_OPT_OUTPROJ_KERNEL = 2
 };
 

@@ -193,6 +193,9 @@ int choose_splits(int row_blocks, int col_blocks, int target_groups) {
 // defined in outproj_staged.hip
 hipError_t launch_outproj_staged(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                  SplitInfo *splits, hipStream_t stream);
+// defined in outproj_tiled.hip
+hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                                SplitInfo *splits, hipStream_t stream);
 
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream) {
@@ -202,6 +205,8 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
     if (m.dtype == RNNLM_BF16) {
         const bool staged = kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128);
         if (staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
+        const bool tiled = kernel_choice == 3 || (kernel_choice == 0 && rows >= 64);
+        if (tiled) return launch_outproj_tiled(m, rows, B_dev, fixed_offset, splits, stream);
         const int row_groups = (rows + 127) / 128, col_blocks = m.Vp / 32;
         int S = choose_splits(row_groups, col_blocks, 1024);
         int per = (col_blocks + S - 1) / S;

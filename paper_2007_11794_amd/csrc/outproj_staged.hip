@@ -54,31 +54,6 @@ struct StagedCfg {
     static_assert(kLoadsPerBlock <= 6, "s_waitcnt immediates below assume few loads per block");
 };
 
-// Direct global->LDS load of 16 bytes per lane: lane i of the wave writes LDS bytes
-// [lds_base + 16 i, lds_base + 16 i + 16) with the 16 bytes at sbase + voff (its own voff).
-// sbase and lds_base must be the same in all lanes (they travel in SGPRs / M0).  Written as
-// inline assembly on purpose: when the compiler knows of a pending LDS-DMA it makes every
-// later LDS read wait for ALL outstanding LDS reads (lgkmcnt(0)) instead of just its own,
-// which stalls the MFMA pipeline; completion is awaited explicitly with vmcnt before the
-// workgroup barrier that publishes the data.
-__device__ __forceinline__ void lds_dma_16(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_base), "v"(voff), "s"(sbase)
-                 : "memory");
-}
-
-__device__ __forceinline__ uint32_t lds_address(const void *p) {
-    return (uint32_t)reinterpret_cast<uintptr_t>(p);         // LDS offsets are the low 32 bits
-}
-
-// Wait until at most N of this wave's vector-memory operations are outstanding.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 16, "");
-    __builtin_amdgcn_s_waitcnt(0x0F70 | N);                  // lgkmcnt and expcnt left alone
-}
-
 // Per-thread constants of the block loader.
 template <int HP>
 struct Loader {
@@ -110,27 +85,6 @@ struct Loader {
         if (lane == 0) lds_dma_16(cvec + v0, wave * 16, cslot_lds + wave * 16);
     }
 };
-
-// Fold sixteen base-2 logits of one row into the (max, sum) pair.
-template <bool FIXED>
-__device__ __forceinline__ void lse2_fold16(const float (&x)[16], float &mrun, float &srun) {
-    if (FIXED) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) srun += fast_exp2(x[i]);          // offset already inside x
-    } else {
-        float mx = x[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, x[i]);
-        const float mn = fmaxf(mrun, mx);
-        if (mn != -INFINITY) {
-            float tsum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) tsum += fast_exp2(x[i] - mn);
-            srun = srun * fast_exp2(mrun - mn) + tsum;
-            mrun = mn;
-        }
-    }
-}
 
 // Base-2 logits of a finished block: x = acc * log2(e) + c2, c2 = the block's constants.
 __device__ __forceinline__ void finish_logits(const f32x16 &acc, const f32x4 *cn, int g, float (&x)[16]) {

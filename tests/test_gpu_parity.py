@@ -74,8 +74,9 @@ def test_config2_chained_steps_full():
     (777, 256, 130, 5),       # staged kernel at Hp = 256
     (1000, 100, 70, 3),       # the paper's hidden size: H not a multiple of anything useful
     (300, 64, 33, 2),
+    (2000, 1024, 200, 4),     # hidden size beyond the staged kernel: tiled kernel by default
 ])
-@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("kernel", [1, 2, 3])
 @pytest.mark.parametrize("lse_mode", [1, 2])
 def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
     cfg = CONFIGS[3].scaled(V=V, H=H, B=B, K=K)
@@ -83,6 +84,10 @@ def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
     m = load_model(model, "bf16", B)
     m.set_option(rn.OPT_LSE_MODE, lse_mode)
+    if kernel == 2 and H > 512:
+        with pytest.raises(rn.RnnlmError):
+            m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
+        kernel = 0                      # automatic choice instead (the tiled kernel at this size)
     m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
     h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
     check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), "bf16",
@@ -142,6 +147,9 @@ def test_config5_stress_full_size_sampled():
     rows = np.sort(np.concatenate([[0, cfg.B - 1], np.random.default_rng(9).choice(np.arange(1, cfg.B - 1), 14, replace=False)]))
     sampled_rows_check(cfg, model, x, h, lp, rows, "cfg5 (16 sampled rows)")
     assert np.all(np.isfinite(lp)) and np.all(lp < 0) and np.all(np.isfinite(h))
+    m.set_option(rn.OPT_OUTPROJ_KERNEL, 1)        # every row: the plain kernel agrees with the default one
+    h1, lp1 = gpu_step(m, x["prev"], x["h_in"], x["query"])
+    assert np.array_equal(h1, h) and np.max(np.abs(lp1 - lp)) <= 1e-4
     assert m.last_error() == 0
     m.close()
 
