@@ -117,11 +117,12 @@ __device__ __forceinline__ uint32_t lds_address(const void *p) {
     return (uint32_t)reinterpret_cast<uintptr_t>(p);         // LDS offsets are the low 32 bits
 }
 
-// Wait until at most N of this wave's vector-memory operations are outstanding.
+// Wait until at most N of this wave's vector-memory operations are outstanding (vmcnt is a
+// 6-bit field on gfx9: bits 3:0 and 15:14 of the immediate; lgkmcnt and expcnt left alone).
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 16, "");
-    __builtin_amdgcn_s_waitcnt(0x0F70 | N);                  // lgkmcnt and expcnt left alone
+    static_assert(N >= 0 && N < 64, "");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 __device__ __forceinline__ float quiet_nan() { return __uint_as_float(0x7FC00000u); }

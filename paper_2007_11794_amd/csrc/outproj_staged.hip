@@ -191,7 +191,9 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
 #pragma unroll
         for (int i = 0; i < 16; ++i) pacc[i] = -INFINITY;
 
-        wait_vmcnt<0>();
+        // Blocks 0 and 1 have landed once at most the KS younger loads of d are outstanding; d
+        // itself is awaited operand by operand as the first block's MFMAs consume it.
+        wait_vmcnt<(KS < 64 ? KS : 63)>();
         __syncthreads();                                      // blocks 0 and 1 are published
 #pragma unroll
         for (int i = 2; i < 4; ++i)
