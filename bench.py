@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published
+PEAK_FP32_TFLOPS = 157.3         # MI355X fp32 vector (and fp32 matrix), published
 # HBM bytes per launch of the output-projection kernel on this workload, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain copy of known size; cannot be measured live.
 # Source and commands: profiles/step_kernels_cfg3_large_vocab_hbm_traffic.md
@@ -59,16 +60,17 @@ def main() -> int:
     rn.lib()                                   # raises if librnnlm.so is not built
     dev = "cuda:0"
     cfg = CONFIGS[args.config]
-    if cfg.dtype != "bf16":
-        print("bench.py: only the bf16 workloads (3, 4, 5) are benchmarked here", file=sys.stderr)
-        return 2
+    bf16 = cfg.dtype == "bf16"
     model = make_model(cfg)
     if cfg.unique_frac is not None:
         x = DecodeTrace(cfg).first()               # N raw queries, about 30 % distinct histories
     else:
         x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
-    m = rn.rnnlm_load(cfg.V, cfg.H, rn.RNNLM_BF16, bf16_bits(model["U"]), bf16_bits(model["W"]),
-                      bf16_bits(model["O"]), None, cfg.N)
+    if bf16:
+        m = rn.rnnlm_load(cfg.V, cfg.H, rn.RNNLM_BF16, bf16_bits(model["U"]), bf16_bits(model["W"]),
+                          bf16_bits(model["O"]), None, cfg.N)
+    else:
+        m = rn.rnnlm_load(cfg.V, cfg.H, rn.RNNLM_F32, model["U"], model["W"], model["O"], None, cfg.N)
     m.set_option(rn.OPT_OUTPROJ_KERNEL, args.outproj_kernel)
     m.set_option(rn.OPT_LSE_MODE, args.lse_mode)
 
@@ -113,8 +115,9 @@ def main() -> int:
     k3_ms = min(k3_ms, m.time_outproj(B, reps))
     flops = 2.0 * B * cfg.H * cfg.V
     achieved = flops / (k3_ms * 1e-3) / 1e12
-    roofline = {"kernel": "outproj_lse", "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    roofline = {"kernel": "outproj_lse", "bound": "mfma" if bf16 else "alu", "achieved": round(achieved, 2), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) and args.config == 3 else None,
                 "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
                 "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
@@ -154,12 +157,12 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s%s: V=%d H=%d N=%d raw queries (%d distinct histories) K=%d, bf16 weights "
-                               "N(0,%g), Zipf(%g) word ids, h_in=sigmoid(N(0,1)), one step incl. history-id grouping"
+        "config": {"workload": "%s%s: V=%d H=%d N=%d raw queries (%d distinct histories) K=%d, %s weights "
+                               "N(0,%g), Zipf(%g) word ids (0 = uniform), one step incl. history-id grouping"
                                % (cfg.name, " (headline)" if args.config == 3 else "", cfg.V, cfg.H, cfg.N, B, cfg.K,
-                                  cfg.sigma, cfg.zipf_s),
+                                  cfg.dtype, cfg.sigma, cfg.zipf_s or 0),
                    "V": cfg.V, "H": cfg.H, "B": B, "N": cfg.N, "K": cfg.K},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -124,66 +124,97 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
     }
 }
 
-// ----------------------------------------------------------------------------- fp32 / ALU
-// A 16 (rows) x 64 (units) tile per workgroup of 256 threads; thread t owns unit t % 64 and
-// the four rows 4 (t / 64) .. +3.  K is walked in chunks of 32 through LDS.
-constexpr int kRB = 16, kRJ = 64, kRK = 32;
+// ----------------------------------------------------------------------------- fp32 / MFMA
+// Same shape as the bf16 kernel (32 x 32 block per workgroup, reduction length split over the
+// four waves, all loads of a wave in flight together), with the full-precision fp32 matrix
+// instruction 32x32x2: per lane one float of A (row l % 32, k = l / 32) and one of B.  A lane
+// loads four consecutive k at a time (lane half g takes k0 + 4 g .. + 3); MFMA number e of the
+// group multiplies the k pair {k0 + e, k0 + 4 + e}, the same pairing for both operands.
+constexpr int kRecurGroups = 8;      // groups of 8 k whose loads are in flight together
+
+__device__ __forceinline__ f32x4 load4_row(const float *row, int k0, int H, bool vec_ok, float fill) {
+    if (vec_ok && k0 + 4 <= H) return *reinterpret_cast<const f32x4 *>(row + k0);
+    f32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (k0 + i < H) ? row[k0 + i] : fill;
+    return v;
+}
 
 __global__ __launch_bounds__(256) void recur_f32_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
     float *__restrict__ h_out) {
     const int B = B_dev ? *B_dev : rows;
-    const int b0 = blockIdx.y * kRB;
+    const int b0 = blockIdx.y * 32;
     if (b0 >= B) return;
-    const int j0 = blockIdx.x * kRJ;
+    __shared__ f32x4 red[4][4][64];                  // [source wave][quarter of acc][lane]
+    const int j0 = blockIdx.x * 32;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, col = lane & 31, g = lane >> 5;
     const int H = m.H, Hp = m.Hp;
     const float *W = static_cast<const float *>(m.W);
     const float *U = static_cast<const float *>(m.U);
-    __shared__ float ds[kRB][kRK];
-    __shared__ float ws[kRJ][kRK + 1];
-    const int t = threadIdx.x, tj = t & 63, tb = (t >> 6) * 4;
 
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int k0 = 0; k0 < Hp; k0 += kRK) {
-        // d tile: 16 x 32 values, two per thread
-        for (int e = t; e < kRB * kRK; e += 256) {
-            int r = e / kRK, k = e % kRK;
-            int b = b0 + r;
-            float v = 0.f;
-            if (b < B && k0 + k < H) {
-                int src = row_src ? row_src[b] : b;
-                v = h_in[(size_t)src * H + k0 + k] - 0.5f;
+    const int b = b0 + col;
+    const bool row_ok = b < B;
+    const int src = row_ok ? (row_src ? row_src[b] : b) : 0;
+    const float *hrow = h_in + (size_t)src * H;
+    const bool vec_ok = (H % 4) == 0;
+    const float *wrow = W + (size_t)(j0 + col) * Hp;
+    const int je = j0 + 8 * wave + 4 * g;            // the four units this lane finishes
+    const int w = row_ok ? prev_word[src] : 0;
+    const f32x4 rs = *reinterpret_cast<const f32x4 *>(m.half_rowsum_W + je);
+
+    const int kq = Hp / 4;                           // this wave's share of k (a multiple of 16)
+    const int k_begin = wave * kq + 4 * g, k_end = (wave + 1) * kq;
+    f32x16 acc = {0};
+    for (int kb = k_begin; kb < k_end; kb += 8 * kRecurGroups) {
+        f32x4 wf[kRecurGroups], hf[kRecurGroups];
+#pragma unroll
+        for (int u = 0; u < kRecurGroups; ++u) {
+            const int k0 = kb + 8 * u;
+            if (k0 < k_end) {
+                wf[u] = *reinterpret_cast<const f32x4 *>(wrow + k0);
+                hf[u] = row_ok ? load4_row(hrow, k0, H, vec_ok, 0.5f) : f32x4{0.5f, 0.5f, 0.5f, 0.5f};
             }
-            ds[r][k] = v;
         }
-        // W tile: 64 x 32 values, eight per thread (padded rows/columns of W are zero)
-        for (int e = t; e < kRJ * kRK; e += 256) {
-            int r = e / kRK, k = e % kRK;
-            ws[r][k] = W[(size_t)(j0 + r) * Hp + k0 + k];
-        }
-        __syncthreads();
 #pragma unroll
-        for (int k = 0; k < kRK; ++k) {
-            float wv = ws[tj][k];
+        for (int u = 0; u < kRecurGroups; ++u) {
+            const int k0 = kb + 8 * u;
+            if (k0 < k_end) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r] = fmaf(wv, ds[tb + r][k], acc[r]);
+                for (int e = 0; e < 4; ++e)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[u][e], hf[u][e] - 0.5f, acc, 0, 0, 0);
+            }
         }
-        __syncthreads();
     }
-    const int j = j0 + tj;
+    const bool w_ok = (w >= 0 && w < m.V);
+    const f32x4 u4 = *reinterpret_cast<const f32x4 *>(U + (size_t)(w_ok ? w : 0) * Hp + je);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int b = b0 + tb + r;
-        if (b >= B) continue;
-        const int src = row_src ? row_src[b] : b;
-        const int w = prev_word[src];
-        const bool w_ok = (w >= 0 && w < m.V);
-        if (!w_ok && j == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
-        float a = acc[r] + m.half_rowsum_W[j] + U[(size_t)(w_ok ? w : 0) * Hp + j];
-        float hp = w_ok ? sigmoid_f32(a) : quiet_nan();
-        static_cast<float *>(m.d)[(size_t)b * Hp + j] = hp - 0.5f;
-        if (j < H) h_out[(size_t)b * H + j] = hp;
+    for (int q = 0; q < 4; ++q)
+        red[wave][q][lane] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+    __syncthreads();
+    if (!row_ok) return;
+    f32x4 a4 = red[0][wave][lane];
+#pragma unroll
+    for (int sw = 1; sw < 4; ++sw) {                 // fixed order: deterministic
+        f32x4 t = red[sw][wave][lane];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a4[i] += t[i];
+    }
+    if (!w_ok && g == 0 && wave == 0 && blockIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
+    f32x4 hp, dv;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        hp[i] = w_ok ? sigmoid_f32(a4[i] + rs[i] + u4[i]) : quiet_nan();
+        dv[i] = hp[i] - 0.5f;                        // padded units: sigmoid(0) - 1/2 = 0
+    }
+    *reinterpret_cast<f32x4 *>(static_cast<float *>(m.d) + (size_t)b * Hp + je) = dv;
+    if (vec_ok && je + 4 <= H) {
+        *reinterpret_cast<f32x4 *>(h_out + (size_t)b * H + je) = hp;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (je + i < H) h_out[(size_t)b * H + je + i] = hp[i];
     }
 }
 
@@ -198,7 +229,7 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
         hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
                            prev_word, h_in, h_out);
     } else {
-        dim3 grid(m.Hp / kRJ, (rows + kRB - 1) / kRB);
+        dim3 grid(m.Hp / 32, (rows + 31) / 32);
         hipLaunchKernelGGL(recur_f32_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
                            prev_word, h_in, h_out);
     }
