@@ -201,7 +201,6 @@ int rnnlm_set_option(rnnlm_model *model, int option, int value) {
         case RNNLM_OPT_OUTPROJ_KERNEL:
             if (value < 0 || value > 3) return RNNLM_EINVAL;
             if (value == 2 && !outproj_staged_supported(model->dev)) return RNNLM_EINVAL;
-            if (value == 3 && model->dev.dtype != RNNLM_BF16) return RNNLM_EINVAL;
             model->outproj_kernel = value;
             return RNNLM_OK;
         default:

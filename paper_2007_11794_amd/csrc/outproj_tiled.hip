@@ -1,4 +1,4 @@
-// Output projection + log-sum-exp, LDS-tiled bf16 MFMA kernel for ANY hidden size.
+// Output projection + log-sum-exp, LDS-tiled MFMA kernel for ANY hidden size, bf16 or fp32.
 //
 // Same result as the other output-projection kernels (normalising over all words of the
 // vocabulary, Section 2.1 of the paper).  This is the form for models whose hidden block
@@ -6,10 +6,13 @@
 // travel through LDS.
 //   - a workgroup (4 waves, 2 x 2) owns 128 rows and walks the 128-word tiles of its
 //     vocabulary split; a wave owns 64 words x 64 rows = four 32x32 accumulators;
-//   - the reduction length is cut in chunks of 64; a chunk is 128 x 64 weights + 128 x 64
-//     hidden values (16 KB each), double-buffered, filled by direct global->LDS loads;
-//   - per 16-wide k-step a wave reads two A operands (words) and two B operands (rows) and
-//     issues four MFMA 32x32x16, so every LDS read feeds two MFMAs;
+//   - the reduction length is cut in chunks of 128 bytes per row (64 bf16 or 32 fp32); a chunk
+//     is 128 rows of weights + 128 rows of hidden values (16 KB each), double-buffered, filled
+//     by direct global->LDS loads;
+//   - per 16-byte k-step a wave reads two A operands (words) and two B operands (rows) and
+//     issues four MFMA 32x32x16 (bf16) or sixteen MFMA 32x32x2 (fp32, the full-precision
+//     matrix instruction: one float per lane and operand, so a 16-byte read feeds four of
+//     them; lane half g supplies k0 + 4 g + e to MFMA e, the same pairing for both operands);
 //   - MFMA roles as in the staged kernel (A = words, B = rows): a lane holds sixteen logits
 //     of ONE row per accumulator, the sum over words stays in the lane;
 //   - after the last chunk of a tile the 64 logits per lane are exponentiated and added.
@@ -23,13 +26,32 @@ namespace rnnlm {
 namespace {
 
 constexpr int kTThreads = 256;
-constexpr int kTRows = 128, kTWords = 128, kTK = 64;
-constexpr int kTOperandBytes = 128 * kTK * 2;                 // 16 KB: one operand, one chunk
+constexpr int kTRows = 128, kTWords = 128;
+constexpr int kTOperandBytes = 128 * 128;                     // 16 KB: one operand, one chunk of 128 B per row
 constexpr int kTStageBytes = 2 * kTOperandBytes;              // words then rows
 constexpr int kTLdsBytes = 2 * kTStageBytes + 2 * kTRows * 8; // + final cross-wave reduction
-constexpr int kTLoads = 128 * (kTK / 8) / kTThreads;          // 16-byte loads per thread per operand (4)
+constexpr int kTLoads = 128 * 8 / kTThreads;                  // 16-byte loads per thread per operand (4)
 
-template <bool FIXED>
+// Four 32x32 accumulators += (two A operands) x (two B operands), 16 bytes of k per lane.
+__device__ __forceinline__ void mma_2x2(f32x16 (&acc)[2][2], const bf16x8 (&a)[2], const bf16x8 (&d)[2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], d[j], acc[i][j], 0, 0, 0);
+}
+__device__ __forceinline__ void mma_2x2(f32x16 (&acc)[2][2], const f32x4 (&a)[2], const f32x4 (&d)[2]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][e], d[j][e], acc[i][j], 0, 0, 0);
+}
+template <typename T> struct Frag;
+template <> struct Frag<bf16_t> { typedef bf16x8 type; };
+template <> struct Frag<float> { typedef f32x4 type; };
+
+template <typename T, bool FIXED>
 __global__ __launch_bounds__(kTThreads) void outproj_tiled_kernel(ModelDev m, int rows,
                                                                   const int *__restrict__ B_dev, int RG,
                                                                   int S) {
@@ -42,11 +64,13 @@ __global__ __launch_bounds__(kTThreads) void outproj_tiled_kernel(ModelDev m, in
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int wm = wave & 1, wn = wave >> 1;                  // word half, row half of the tile
     const int Hp = m.Hp;
-    const bf16_t *Ot = static_cast<const bf16_t *>(m.Ot);
-    const bf16_t *D = static_cast<const bf16_t *>(m.d);
+    constexpr int kTK = 128 / (int)sizeof(T);                  // k per chunk
+    typedef typename Frag<T>::type frag_t;
+    const T *Ot = static_cast<const T *>(m.Ot);
+    const T *D = static_cast<const T *>(m.d);
     const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
-    const int T = m.Vp / kTWords;
-    const int t_begin = (int)(((long long)split * T) / S), t_end = (int)(((long long)(split + 1) * T) / S);
+    const int ntiles = m.Vp / kTWords;
+    const int t_begin = (int)(((long long)split * ntiles) / S), t_end = (int)(((long long)(split + 1) * ntiles) / S);
     const int nk = Hp / kTK;                                   // chunks per tile
     const int nchunks = (t_end - t_begin) * nk;
 
@@ -56,14 +80,14 @@ __global__ __launch_bounds__(kTThreads) void outproj_tiled_kernel(ModelDev m, in
     for (int q = 0; q < kTLoads; ++q) {
         const int f = q * kTThreads + tid;
         const int r = f >> 3, p = f & 7, c = p ^ ((r >> 1) & 7);
-        voff[q] = (uint32_t)(r * Hp * 2 + c * 16);
+        voff[q] = (uint32_t)(r * Hp * (int)sizeof(T) + c * 16);
     }
     const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = lds_address(lds);
     auto issue = [&](int chunk, int stage) {
         const int t = t_begin + chunk / nk, k0 = (chunk % nk) * kTK;
-        const bf16_t *wsrc = Ot + (size_t)t * kTWords * Hp + k0;
-        const bf16_t *dsrc = D + (size_t)b0 * Hp + k0;
+        const T *wsrc = Ot + (size_t)t * kTWords * Hp + k0;
+        const T *dsrc = D + (size_t)b0 * Hp + k0;
         const uint32_t base = lds0 + stage * kTStageBytes + wave_s * 1024;
 #pragma unroll
         for (int q = 0; q < kTLoads; ++q) lds_dma_16(wsrc, voff[q], base + q * (kTThreads * 16));
@@ -107,14 +131,11 @@ __global__ __launch_bounds__(kTThreads) void outproj_tiled_kernel(ModelDev m, in
         const char *st = lds + stage * kTStageBytes;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(st + aoff[0][ks]);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(st + aoff[1][ks]);
-            const bf16x8 d0 = *reinterpret_cast<const bf16x8 *>(st + boff[0][ks]);
-            const bf16x8 d1 = *reinterpret_cast<const bf16x8 *>(st + boff[1][ks]);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, d0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, d1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, d0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, d1, acc[1][1], 0, 0, 0);
+            const frag_t a[2] = {*reinterpret_cast<const frag_t *>(st + aoff[0][ks]),
+                                 *reinterpret_cast<const frag_t *>(st + aoff[1][ks])};
+            const frag_t d[2] = {*reinterpret_cast<const frag_t *>(st + boff[0][ks]),
+                                 *reinterpret_cast<const frag_t *>(st + boff[1][ks])};
+            mma_2x2(acc, a, d);
         }
         if (kc == nk - 1) {                                    // the tile is complete: exp-and-add
             const int v0 = (t_begin + chunk / nk) * kTWords + wm * 64;
@@ -154,23 +175,24 @@ __global__ __launch_bounds__(kTThreads) void outproj_tiled_kernel(ModelDev m, in
     }
 }
 
-}  // namespace
-
-hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
-                                SplitInfo *splits, hipStream_t stream) {
+template <typename T>
+hipError_t launch_tiled_t(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset, SplitInfo *splits,
+                          hipStream_t stream) {
     static bool attr_set[2] = {false, false};
     const int which = fixed_offset ? 1 : 0;
-    const void *fn = fixed_offset ? reinterpret_cast<const void *>(outproj_tiled_kernel<true>)
-                                  : reinterpret_cast<const void *>(outproj_tiled_kernel<false>);
+    const void *fn = fixed_offset ? reinterpret_cast<const void *>(outproj_tiled_kernel<T, true>)
+                                  : reinterpret_cast<const void *>(outproj_tiled_kernel<T, false>);
     if (!attr_set[which]) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kTLdsBytes);
         if (e != hipSuccess) return e;
         attr_set[which] = true;
     }
-    const int RG = (rows + kTRows - 1) / kTRows;
-    // about two workgroups per compute unit (64 KB of LDS each); splits in multiples of 8 so
-    // that the row groups streaming the same weights share an XCD
+    const int RG = (rows + kTRows - 1) / kTRows, T128 = m.Vp / kTWords;
+    // about two workgroups per compute unit (64 KB of LDS each) but never more splits than
+    // 128-word tiles; splits in multiples of 8 so that the row groups streaming the same
+    // weights share an XCD
     int Sx = 512 / (kXcds * RG);
+    if (Sx > T128 / kXcds) Sx = T128 / kXcds;
     if (Sx < 1) Sx = 1;
     if (Sx > kMaxSplits / kXcds) Sx = kMaxSplits / kXcds;
     const int S = kXcds * Sx;
@@ -178,10 +200,18 @@ hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, b
     splits->staged_wg_per_xcd = 0;
     dim3 grid(kXcds * RG * Sx), block(kTThreads);
     if (fixed_offset)
-        hipLaunchKernelGGL(outproj_tiled_kernel<true>, grid, block, kTLdsBytes, stream, m, rows, B_dev, RG, S);
+        hipLaunchKernelGGL((outproj_tiled_kernel<T, true>), grid, block, kTLdsBytes, stream, m, rows, B_dev, RG, S);
     else
-        hipLaunchKernelGGL(outproj_tiled_kernel<false>, grid, block, kTLdsBytes, stream, m, rows, B_dev, RG, S);
+        hipLaunchKernelGGL((outproj_tiled_kernel<T, false>), grid, block, kTLdsBytes, stream, m, rows, B_dev, RG, S);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                                SplitInfo *splits, hipStream_t stream) {
+    if (m.dtype == RNNLM_BF16) return launch_tiled_t<bf16_t>(m, rows, B_dev, fixed_offset, splits, stream);
+    return launch_tiled_t<float>(m, rows, B_dev, fixed_offset, splits, stream);
 }
 
 }  // namespace rnnlm

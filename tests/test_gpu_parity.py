@@ -102,10 +102,13 @@ def test_f32_reduced_elementwise_both_lse_modes(V, H, B, K):
     model = make_model(cfg)
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
     m = load_model(model, "f32", B)
-    for lse_mode in (1, 2):
-        m.set_option(rn.OPT_LSE_MODE, lse_mode)
-        h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
-        check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), "f32", "f32 V=%d lse=%d" % (V, lse_mode))
+    ref = oracle.step(model, x["prev"], x["h_in"], x["query"])
+    for kernel in (1, 3):                       # plain FMA kernel, LDS-tiled fp32-MFMA kernel
+        m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
+        for lse_mode in (1, 2):
+            m.set_option(rn.OPT_LSE_MODE, lse_mode)
+            h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+            check(h, lp, ref, "f32", "f32 V=%d kernel=%d lse=%d" % (V, kernel, lse_mode))
     m.close()
 
 
