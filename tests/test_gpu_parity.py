@@ -74,7 +74,8 @@ def test_config2_chained_steps_full():
     (777, 256, 130, 5),       # staged kernel at Hp = 256
     (1000, 100, 70, 3),       # the paper's hidden size: H not a multiple of anything useful
     (300, 64, 33, 2),
-    (2000, 1024, 200, 4),     # hidden size beyond the staged kernel: tiled kernel by default
+    (2000, 1024, 200, 4),     # hidden size beyond the staged kernel: tiled kernel (128-row tiles) by default
+    (1500, 640, 300, 4),      # tiled kernel with 256-row tiles, hidden size not a power of two
 ])
 @pytest.mark.parametrize("kernel", [1, 2, 3])
 @pytest.mark.parametrize("lse_mode", [1, 2])
