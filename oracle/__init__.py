@@ -41,6 +41,18 @@ def _load():
         lib.oracle_step.argtypes = [I, I, I, I, I, P, P, P, P, P, P, P, P, P, P, P, P, I]
         lib.oracle_step.restype = I
         lib.oracle_max_threads.restype = I
+        lib.oracle_cache_new.argtypes = [I, I]
+        lib.oracle_cache_new.restype = P
+        lib.oracle_cache_free.argtypes = [P]
+        lib.oracle_cache_free.restype = None
+        lib.oracle_cache_reset.argtypes = [P]
+        lib.oracle_cache_reset.restype = None
+        lib.oracle_cache_stats.argtypes = [P, P]
+        lib.oracle_cache_stats.restype = None
+        lib.oracle_step_cached.argtypes = [P, I, I, I, I] + [P] * 15 + [I]
+        lib.oracle_step_cached.restype = I
+        lib.oracle_pack_ids.argtypes = [P, P, I, P]
+        lib.oracle_pack_ids.restype = None
         _lib = lib
     return _lib
 
@@ -101,4 +113,76 @@ def step(model: dict, prev, h_in, query, row_of_query=None, want_full: bool = Fa
     out = {"h_out": h_out, "lse": lse, "logprob": logprob}
     if want_full:
         out["full_logp"] = full
+    return out
+
+
+class Cache:
+    """The cache of RnnlmProb kept between steps (Table 1; Sections 4.2 and 5.3): at most
+    `capacity` histories, nothing is ever removed; reset() starts a new utterance."""
+
+    def __init__(self, H: int, capacity: int):
+        self._h = _load().oracle_cache_new(int(H), int(capacity))
+        if not self._h:
+            raise MemoryError("oracle_cache_new failed")
+        self.H, self.capacity = int(H), int(capacity)
+
+    def reset(self) -> None:
+        _load().oracle_cache_reset(self._h)
+
+    def stats(self) -> dict:
+        out = np.zeros(5, dtype=np.int64)
+        _load().oracle_cache_stats(self._h, _ptr(out))
+        return dict(zip(("entries", "lookups", "hits", "misses", "unstored"), (int(x) for x in out)))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.oracle_cache_free(self._h)
+            self._h = None
+
+
+def step_cached(model: dict, cache: Optional[Cache], ids, prev, h_in, query, base_score=None,
+                num_threads: int = 0) -> dict:
+    """One step over N raw queries through the cache (None: no cache outlives the step).
+    Returns n_unique, rep, inverse, float64 h_out[n_unique,H], lse[n_unique], score[N,K]
+    (log-probability minus base_score) and stats = (distinct, hits, computed, entries)."""
+    U = _c(model["U"], np.float32)
+    W = _c(model["W"], np.float32)
+    O = _c(model["O"], np.float32)
+    bias = model.get("bias")
+    bias = None if bias is None else _c(bias, np.float32)
+    V, H = U.shape
+    ids = _c(ids, np.uint64)
+    prev = _c(prev, np.int32)
+    h_in = _c(h_in, np.float32)
+    query = _c(query, np.int32)
+    N, K = query.shape
+    assert ids.shape == (N,) and prev.shape == (N,) and h_in.shape == (N, H)
+    if base_score is not None:
+        base_score = _c(base_score, np.float32)
+        assert base_score.shape == (N, K)
+    n1 = max(N, 1)
+    rep = np.zeros(n1, dtype=np.int32)
+    inverse = np.zeros(n1, dtype=np.int32)
+    h_out = np.zeros((n1, H), dtype=np.float64)
+    lse = np.zeros(n1, dtype=np.float64)
+    score = np.zeros((N, K), dtype=np.float64)
+    stats = np.zeros(4, dtype=np.int32)
+    rc = _load().oracle_step_cached(cache._h if cache is not None else None, V, H, N, K,
+                                    _ptr(U), _ptr(W), _ptr(O), _ptr(bias), _ptr(ids), _ptr(prev),
+                                    _ptr(h_in), _ptr(query), _ptr(base_score), _ptr(rep), _ptr(inverse),
+                                    _ptr(h_out), _ptr(lse), _ptr(score), _ptr(stats), num_threads)
+    if rc < 0:
+        raise ValueError("oracle_step_cached failed (%d)" % rc)
+    return {"n_unique": rc, "rep": rep[:rc].copy(), "inverse": inverse[:N].copy(),
+            "h_out": h_out[:rc].copy(), "lse": lse[:rc].copy(), "score": score,
+            "stats": tuple(int(x) for x in stats)}
+
+
+def pack_ids(ctx, small_lm) -> np.ndarray:
+    """The packed 8-byte history index of Section 3.2 (context index in the high half)."""
+    ctx = _c(ctx, np.uint32)
+    small_lm = _c(small_lm, np.uint32)
+    assert ctx.shape == small_lm.shape and ctx.ndim == 1
+    out = np.zeros(ctx.shape[0], dtype=np.uint64)
+    _load().oracle_pack_ids(_ptr(ctx), _ptr(small_lm), ctx.shape[0], _ptr(out))
     return out

@@ -19,6 +19,9 @@
  *              normalised over all V words (the cost Section 2.1 names):
  *              logp[v] = z[v] - (m + log sum_u exp(z[u] - m)),  m = max_u z[u].
  *   query      only logp at the queried words is returned.
+ *   cache      the same lookup kept between steps (Table 1 as a whole; Sections 4.2, 5.3),
+ *              the score difference handed back after it, and the packed 8-byte index of
+ *              Section 3.2: oracle_step_cached, oracle_pack_ids further down.
  *
  * Everything is summed left to right in double.  Weights arrive as float (bf16 models
  * pass values that are exact in float) and are widened exactly.  h' is never rounded
@@ -139,6 +142,167 @@ int oracle_step(int V, int H, int B, int K, int N,
         free(z);
     }
     return bad ? -2 : 0;
+}
+
+/* ------------------------------------------------------------------------------------
+ * RnnlmProb with a cache that outlives one step (Table 1; Section 4.2), keyed by the 8-byte
+ * history index of Section 3.2.  The cache holds at most `capacity` entries (the size
+ * boundary of Section 5.3); the paper removes nothing from a bounded cache, so once it is
+ * full a new history is still computed and answered but not kept.  An entry stores what the
+ * output of a history depends on: its updated hidden vector h' and the normaliser lse.
+ */
+typedef struct oracle_cache {
+    int H, capacity, count;
+    uint64_t *keys;     /* [capacity] */
+    double *h;          /* [capacity][H] */
+    double *lse;        /* [capacity] */
+    long long lookups, hits, misses, unstored;   /* running totals over distinct histories */
+} oracle_cache;
+
+oracle_cache *oracle_cache_new(int H, int capacity)
+{
+    if (H <= 0 || capacity < 0) return NULL;
+    oracle_cache *c = (oracle_cache *)calloc(1, sizeof(oracle_cache));
+    if (!c) return NULL;
+    c->H = H;
+    c->capacity = capacity;
+    size_t cap = capacity > 0 ? (size_t)capacity : 1;
+    c->keys = (uint64_t *)malloc(cap * sizeof(uint64_t));
+    c->h = (double *)malloc(cap * (size_t)H * sizeof(double));
+    c->lse = (double *)malloc(cap * sizeof(double));
+    if (!c->keys || !c->h || !c->lse) { free(c->keys); free(c->h); free(c->lse); free(c); return NULL; }
+    return c;
+}
+
+void oracle_cache_free(oracle_cache *c)
+{
+    if (!c) return;
+    free(c->keys); free(c->h); free(c->lse); free(c);
+}
+
+/* Start of an utterance: forget everything (Section 4.2 resets per utterance). */
+void oracle_cache_reset(oracle_cache *c)
+{
+    c->count = 0;
+    c->lookups = c->hits = c->misses = c->unstored = 0;
+}
+
+void oracle_cache_stats(const oracle_cache *c, long long out[5])
+{
+    out[0] = c->count; out[1] = c->lookups; out[2] = c->hits; out[3] = c->misses; out[4] = c->unstored;
+}
+
+/*
+ * One step over N raw queries with the cache (c == NULL: no cache outlives the step).
+ *   ids[N], prev[N], h_in[N][H], query[N][K]; base_score[N][K] or NULL.
+ * Walks the queries in order, as RnnlmProb is called: a history met earlier in this step
+ * reuses that result (steps 2-3); a history found in the cache takes the stored (h', lse)
+ * whatever prev/h_in say now; any other history is computed from the prev/h_in of its first
+ * query and, while there is room, stored (step 14).  The arithmetic of the computed
+ * histories is independent of the walk, so it is evaluated for all of them together.
+ * Outputs: rep[U], inverse[N] as oracle_dedup; h_out[U][H], lse[U] in group order;
+ *   score[n][k] = logp(query[n][k] | history n) - base_score[n][k]
+ * (Section 4.2, last paragraph: the value handed back is the difference to the short-span
+ * n-gram score); step_stats = {distinct, found in cache, computed, entries afterwards}.
+ * Returns the number of distinct histories, or < 0 as oracle_step.
+ */
+int oracle_step_cached(oracle_cache *c, int V, int H, int N, int K,
+                       const float *U, const float *W, const float *O, const float *bias,
+                       const uint64_t *ids, const int32_t *prev, const float *h_in,
+                       const int32_t *query, const float *base_score,
+                       int32_t *rep, int32_t *inverse,
+                       double *h_out, double *lse, double *score, int32_t step_stats[4],
+                       int num_threads)
+{
+    if (c && c->H != H) return -1;
+    int nu = 0, nhit = 0, nmiss = 0;
+    int32_t *entry = (int32_t *)malloc((size_t)(N > 0 ? N : 1) * sizeof(int32_t));  /* cache entry or -1 */
+    int32_t *miss_rows = (int32_t *)malloc((size_t)(N > 0 ? N : 1) * sizeof(int32_t));
+    if (!entry || !miss_rows) { free(entry); free(miss_rows); return -2; }
+    for (int n = 0; n < N; ++n) {
+        int u = -1;
+        for (int t = 0; t < nu; ++t)
+            if (ids[rep[t]] == ids[n]) { u = t; break; }
+        if (u < 0) {
+            u = nu++;
+            rep[u] = n;
+            entry[u] = -1;
+            if (c)
+                for (int e = 0; e < c->count; ++e)
+                    if (c->keys[e] == ids[n]) { entry[u] = e; break; }
+            if (entry[u] >= 0) ++nhit;
+            else miss_rows[nmiss++] = u;
+        }
+        inverse[n] = u;
+    }
+    /* ComputeRnnlm for the histories that were not cached */
+    int rc = 0;
+    if (nmiss > 0) {
+        int32_t *mprev = (int32_t *)malloc((size_t)nmiss * sizeof(int32_t));
+        float *mh = (float *)malloc((size_t)nmiss * H * sizeof(float));
+        double *mho = (double *)malloc((size_t)nmiss * H * sizeof(double));
+        double *mlse = (double *)malloc((size_t)nmiss * sizeof(double));
+        if (!mprev || !mh || !mho || !mlse) rc = -2;
+        if (rc == 0) {
+            for (int m = 0; m < nmiss; ++m) {
+                int n = rep[miss_rows[m]];
+                mprev[m] = prev[n];
+                for (int i = 0; i < H; ++i) mh[(size_t)m * H + i] = h_in[(size_t)n * H + i];
+            }
+            rc = oracle_step(V, H, nmiss, 0, 0, U, W, O, bias, mprev, mh, NULL, NULL, mho, mlse, NULL, NULL,
+                             num_threads);
+        }
+        if (rc == 0)
+            for (int m = 0; m < nmiss; ++m) {
+                int u = miss_rows[m];
+                for (int j = 0; j < H; ++j) h_out[(size_t)u * H + j] = mho[(size_t)m * H + j];
+                lse[u] = mlse[m];
+            }
+        free(mprev); free(mh); free(mho); free(mlse);
+    }
+    if (rc != 0) { free(entry); free(miss_rows); return rc; }
+    /* cached histories: the stored values; new ones: stored in order of first appearance */
+    for (int u = 0; u < nu; ++u) {
+        if (entry[u] >= 0) {
+            for (int j = 0; j < H; ++j) h_out[(size_t)u * H + j] = c->h[(size_t)entry[u] * H + j];
+            lse[u] = c->lse[entry[u]];
+        } else if (c) {
+            if (c->count < c->capacity) {
+                int e = c->count++;
+                c->keys[e] = ids[rep[u]];
+                for (int j = 0; j < H; ++j) c->h[(size_t)e * H + j] = h_out[(size_t)u * H + j];
+                c->lse[e] = lse[u];
+            } else {
+                ++c->unstored;
+            }
+        }
+    }
+    if (c) { c->lookups += nu; c->hits += nhit; c->misses += nmiss; }
+    /* the queried words */
+    for (int n = 0; n < N && rc == 0; ++n) {
+        const double *h = h_out + (size_t)inverse[n] * H;
+        for (int k = 0; k < K; ++k) {
+            int q = query[(size_t)n * K + k];
+            if (q < 0 || q >= V) { rc = -1; break; }
+            double z = bias ? (double)bias[q] : 0.0;
+            for (int j = 0; j < H; ++j) z += (double)O[(size_t)j * V + q] * h[j];
+            double p = z - lse[inverse[n]];
+            if (base_score) p -= (double)base_score[(size_t)n * K + k];
+            score[(size_t)n * K + k] = p;
+        }
+    }
+    if (step_stats) {
+        step_stats[0] = nu; step_stats[1] = nhit; step_stats[2] = nmiss; step_stats[3] = c ? c->count : 0;
+    }
+    free(entry); free(miss_rows);
+    return rc != 0 ? rc : nu;
+}
+
+/* The 8-byte value of Section 3.2: the RNNLM context index and the index of the small
+ * (graph-building) LM in one number, context index in the high half. */
+void oracle_pack_ids(const uint32_t *ctx, const uint32_t *small_lm, int N, uint64_t *ids)
+{
+    for (int n = 0; n < N; ++n) ids[n] = ((uint64_t)ctx[n] << 32) | (uint64_t)small_lm[n];
 }
 
 int oracle_max_threads(void)
