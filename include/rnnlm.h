@@ -12,10 +12,11 @@
  *   - Plain C ABI.  Every function returns an rnnlm_status (0 = OK, < 0 = error) except
  *     where stated; nothing throws or aborts.
  *   - rnnlm_load takes HOST pointers and copies; the caller keeps its buffers.
- *   - rnnlm_dedup / rnnlm_step / rnnlm_step_dedup take DEVICE pointers owned by the caller
- *     and are asynchronous on `hip_stream` (a hipStream_t passed as void*; NULL = the
- *     default stream).  No call here synchronises, allocates or frees device memory
- *     except rnnlm_load, rnnlm_free and rnnlm_last_error.
+ *   - rnnlm_dedup / rnnlm_step / rnnlm_step_dedup / rnnlm_step_cached / rnnlm_pack_ids take
+ *     DEVICE pointers owned by the caller and are asynchronous on `hip_stream` (a
+ *     hipStream_t passed as void*; NULL = the default stream).  No call here synchronises,
+ *     allocates or frees device memory except rnnlm_load, rnnlm_free, rnnlm_last_error,
+ *     rnnlm_cache_create, rnnlm_cache_free and rnnlm_cache_stats.
  *   - float / int32 / uint64 arrays are dense, row-major, naturally aligned; `h_in` and
  *     `h_out` rows must start on 16-byte boundaries when H is a multiple of 4 (any
  *     allocator's base alignment gives this).
@@ -159,6 +160,65 @@ int rnnlm_step_dedup(const rnnlm_model *model, int N, int K,
                      int32_t *rep, int32_t *inverse, int32_t *n_unique,
                      float *h_out, float *logprob,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * ---- Cache kept between steps (Table 1 as a whole; Sections 4.2 and 5.3) ----------------
+ *
+ * rnnlm_step_dedup forgets everything when it returns.  The paper's Cache lives for an
+ * utterance (or longer, within a size boundary): a history that was computed in an earlier
+ * step is looked up, not computed again.  An rnnlm_cache keeps, on the device, for up to
+ * `capacity` history ids the updated hidden vector and the normaliser of that history.
+ * Nothing is ever removed: when it is full, further new histories are computed and answered
+ * but not kept (Section 5.3 bounds the size and leaves a removal policy open).
+ */
+typedef struct rnnlm_cache rnnlm_cache;   /* opaque, owned by the library */
+
+/* Create an empty cache for `model` (calls may pass up to the model's max_B queries).
+ * capacity >= 0 entries; device memory ~ capacity * (4 H + 36) bytes.  Synchronous. */
+int rnnlm_cache_create(const rnnlm_model *model, int capacity, rnnlm_cache **out);
+
+/* Release a cache.  NULL is a no-op.  Synchronises the device. */
+int rnnlm_cache_free(rnnlm_cache *cache);
+
+/* Forget every entry and zero the counters (start of an utterance, Section 4.2).
+ * Asynchronous on `hip_stream`. */
+int rnnlm_cache_reset(rnnlm_cache *cache, void *hip_stream);
+
+/* Wait for `hip_stream`, then write to the HOST array out[5]: entries held, and the running
+ * totals over distinct histories per step: looked up, found, computed, computed but not
+ * kept because the cache was full. */
+int rnnlm_cache_stats(rnnlm_cache *cache, void *hip_stream, int64_t out[5]);
+
+/*
+ * rnnlm_step_dedup through the cache: the distinct histories of this call that the cache
+ * holds take their stored hidden vector and normaliser (whatever prev_word / h_in say now);
+ * only the others are computed, and they are stored, in order of first appearance, while
+ * there is room.  Arguments as rnnlm_step_dedup, plus
+ *   cache        the cache, or NULL for none (then exactly rnnlm_step_dedup)
+ *   base_score   dev f32[N][K] or NULL: subtracted from the log-probabilities, so that the
+ *                value that leaves the device is the difference to the short-span n-gram
+ *                score the search already applied (Section 4.2, last paragraph)
+ *   score        dev f32[N][K] out: logprob - base_score
+ *   step_stats   dev i32[4] out or NULL: distinct histories, found in the cache, computed,
+ *                entries held afterwards
+ * h_out rows of histories found in the cache are copies of the stored vectors.  A stored
+ * value is returned bit for bit as it was first computed.  Calls that share a cache must be
+ * ordered on one stream.  Requires N <= max_B of the model the cache was created for.
+ */
+int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache_or_null, int N, int K,
+                      const uint64_t *history_ids, const int32_t *prev_word, const float *h_in,
+                      const int32_t *query_word, const float *base_score_or_null,
+                      int32_t *rep, int32_t *inverse, int32_t *n_unique,
+                      float *h_out, float *score, int32_t *step_stats_or_null,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The packed 8-byte index of Section 3.2: ids[n] = ctx_idx[n] << 32 | small_lm_idx[n]
+ * (RNNLM context index in the high half, index of the graph-building LM in the low half).
+ * All device pointers; asynchronous on `hip_stream`.
+ */
+int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N, uint64_t *ids,
+                   void *hip_stream);
 
 /*
  * Measurement aid: run only the output-projection + log-sum-exp kernel on the hidden

@@ -23,7 +23,8 @@ _lib = None
 
 EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rnnlm_last_error",
            "rnnlm_dedup_workspace_bytes", "rnnlm_dedup", "rnnlm_step", "rnnlm_step_dedup",
-           "rnnlm_time_outproj"]
+           "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
+           "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids"]
 
 
 class RnnlmError(RuntimeError):
@@ -65,6 +66,18 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_step_dedup.restype = I
         L.rnnlm_time_outproj.argtypes = [P, I, I, P, ctypes.POINTER(ctypes.c_float)]
         L.rnnlm_time_outproj.restype = I
+        L.rnnlm_cache_create.argtypes = [P, I, ctypes.POINTER(P)]
+        L.rnnlm_cache_create.restype = I
+        L.rnnlm_cache_free.argtypes = [P]
+        L.rnnlm_cache_free.restype = I
+        L.rnnlm_cache_reset.argtypes = [P, P]
+        L.rnnlm_cache_reset.restype = I
+        L.rnnlm_cache_stats.argtypes = [P, P, ctypes.POINTER(ctypes.c_int64)]
+        L.rnnlm_cache_stats.restype = I
+        L.rnnlm_step_cached.argtypes = [P, P, I, I, P, P, P, P, P, P, P, P, P, P, P, P, Z, P]
+        L.rnnlm_step_cached.restype = I
+        L.rnnlm_pack_ids.argtypes = [P, P, I, P, P]
+        L.rnnlm_pack_ids.restype = I
         _lib = L
     return _lib
 
@@ -207,3 +220,80 @@ def rnnlm_step_dedup(model: RnnlmModel, history_ids, prev_word, h_in, query_word
                                   _dev(workspace, torch.uint8, "workspace"),
                                   0 if workspace is None else workspace.numel(), _stream(stream)),
            "rnnlm_step_dedup")
+
+
+class RnnlmCache:
+    """Handle returned by rnnlm_cache_create."""
+
+    def __init__(self, handle: int, capacity: int):
+        self._h = handle
+        self.capacity = capacity
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("cache already freed")
+        return self._h
+
+    def reset(self, stream=None):
+        _check(lib().rnnlm_cache_reset(self.handle, _stream(stream)), "rnnlm_cache_reset")
+
+    def stats(self, stream=None) -> dict:
+        out = (ctypes.c_int64 * 5)()
+        _check(lib().rnnlm_cache_stats(self.handle, _stream(stream), out), "rnnlm_cache_stats")
+        return dict(zip(("entries", "lookups", "hits", "misses", "unstored"), (int(x) for x in out)))
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, None
+            _check(lib().rnnlm_cache_free(h), "rnnlm_cache_free")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def rnnlm_cache_create(model: RnnlmModel, capacity: int) -> RnnlmCache:
+    out = ctypes.c_void_p()
+    _check(lib().rnnlm_cache_create(model.handle, int(capacity), ctypes.byref(out)), "rnnlm_cache_create")
+    return RnnlmCache(out.value, int(capacity))
+
+
+def rnnlm_step_cached(model: RnnlmModel, cache: Optional[RnnlmCache], history_ids, prev_word, h_in,
+                      query_word, rep, inverse, n_unique, h_out, score, workspace, base_score=None,
+                      step_stats=None, stream=None):
+    import torch
+    N = int(history_ids.shape[0])
+    K = int(query_word.shape[1]) if query_word.dim() == 2 else 0
+    if (prev_word.shape != (N,) or h_in.shape != (N, model.H) or h_out.shape != (N, model.H)
+            or query_word.shape[0] != N or score.shape != (N, K)
+            or rep.shape != (N,) or inverse.shape != (N,)):
+        raise TypeError("shape mismatch")
+    if base_score is not None and base_score.shape != (N, K):
+        raise TypeError("base_score must have shape (N, K)")
+    if step_stats is not None and step_stats.shape != (4,):
+        raise TypeError("step_stats must have shape (4,)")
+    _check(lib().rnnlm_step_cached(model.handle, cache.handle if cache is not None else None, N, K,
+                                   _dev(history_ids, torch.int64, "history_ids"),
+                                   _dev(prev_word, torch.int32, "prev_word"), _dev(h_in, torch.float32, "h_in"),
+                                   _dev(query_word, torch.int32, "query_word"),
+                                   _dev(base_score, torch.float32, "base_score"),
+                                   _dev(rep, torch.int32, "rep"), _dev(inverse, torch.int32, "inverse"),
+                                   _dev(n_unique, torch.int32, "n_unique"),
+                                   _dev(h_out, torch.float32, "h_out"), _dev(score, torch.float32, "score"),
+                                   _dev(step_stats, torch.int32, "step_stats"),
+                                   _dev(workspace, torch.uint8, "workspace"),
+                                   0 if workspace is None else workspace.numel(), _stream(stream)),
+           "rnnlm_step_cached")
+
+
+def rnnlm_pack_ids(ctx_idx, small_lm_idx, ids, stream=None):
+    """ctx_idx, small_lm_idx: int32 device tensors holding u32 bit patterns [N]; ids int64 [N] out."""
+    import torch
+    N = int(ctx_idx.shape[0])
+    if small_lm_idx.shape != (N,) or ids.shape != (N,):
+        raise TypeError("shape mismatch")
+    _check(lib().rnnlm_pack_ids(_dev(ctx_idx, torch.int32, "ctx_idx"), _dev(small_lm_idx, torch.int32, "small_lm_idx"),
+                                N, _dev(ids, torch.int64, "ids"), _stream(stream)), "rnnlm_pack_ids")

@@ -247,10 +247,10 @@ int rnnlm_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word,
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
     SplitInfo splits = {1, 0};
-    if (launch_recur(d, B, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_recur(d, B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
     if (launch_outproj(d, B, nullptr, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
         return RNNLM_EDEVICE;
-    if (launch_query(d, B, nullptr, N, K, splits, query_word, row_of_query_or_null, h_out, logprob, s) !=
+    if (launch_query(d, B, nullptr, N, K, splits, query_word, row_of_query_or_null, h_out, nullptr, nullptr, logprob, s) !=
         hipSuccess)
         return RNNLM_EDEVICE;
     return RNNLM_OK;
@@ -260,24 +260,134 @@ int rnnlm_step_dedup(const rnnlm_model *model, int N, int K, const uint64_t *his
                      const int32_t *prev_word, const float *h_in, const int32_t *query_word, int32_t *rep,
                      int32_t *inverse, int32_t *n_unique, float *h_out, float *logprob, void *workspace,
                      size_t workspace_bytes, void *hip_stream) {
+    return rnnlm_step_cached(model, nullptr, N, K, history_ids, prev_word, h_in, query_word, nullptr, rep,
+                             inverse, n_unique, h_out, logprob, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K, const uint64_t *history_ids,
+                      const int32_t *prev_word, const float *h_in, const int32_t *query_word,
+                      const float *base_score, int32_t *rep, int32_t *inverse, int32_t *n_unique, float *h_out,
+                      float *score, int32_t *step_stats, void *workspace, size_t workspace_bytes,
+                      void *hip_stream) {
     int rc = check_step_args(model, N, K, N);
     if (rc != RNNLM_OK) return rc;
     if (!n_unique) return RNNLM_EINVAL;
     if (N > 0 && (!history_ids || !prev_word || !h_in || !rep || !inverse || !h_out)) return RNNLM_EINVAL;
-    if (N > 0 && K > 0 && (!query_word || !logprob)) return RNNLM_EINVAL;
+    if (N > 0 && K > 0 && (!query_word || !score)) return RNNLM_EINVAL;
     if (N > 0 && h_out == h_in) return RNNLM_EINVAL;
+    if (cache && (cache->dev.H != model->dev.H || N > cache->max_B)) return RNNLM_ERANGE;
     rc = rnnlm_dedup(history_ids, N, rep, inverse, n_unique, workspace, workspace_bytes, hip_stream);
-    if (rc != RNNLM_OK || N == 0) return rc;
+    if (rc != RNNLM_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
     SplitInfo splits = {1, 0};
-    // Grids cover N rows; the kernels read the true number of rows from *n_unique.
-    if (launch_recur(d, N, n_unique, rep, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
-    if (launch_outproj(d, N, n_unique, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
+    if (!cache) {
+        if (N == 0) return RNNLM_OK;
+        // Grids cover N rows; the kernels read the true number of rows from *n_unique.
+        if (launch_recur(d, N, n_unique, rep, nullptr, prev_word, h_in, h_out, s) != hipSuccess)
+            return RNNLM_EDEVICE;
+        if (launch_outproj(d, N, n_unique, use_fixed_offset(model), model->outproj_kernel, &splits, s) !=
+            hipSuccess)
+            return RNNLM_EDEVICE;
+        if (launch_query(d, N, n_unique, N, K, splits, query_word, inverse, h_out, nullptr, base_score, score,
+                         s) != hipSuccess)
+            return RNNLM_EDEVICE;
+        return RNNLM_OK;
+    }
+    const CacheDev &c = cache->dev;
+    if (launch_cache_lookup(c, history_ids, rep, n_unique, step_stats, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (N == 0) return RNNLM_OK;
+    // Only the histories the cache does not hold are computed: *c.n_miss rows, row r taken
+    // from raw query c.miss_src[r], its hidden vector written to row c.miss_dst[r] of h_out.
+    if (launch_recur(d, N, c.n_miss, c.miss_src, c.miss_dst, prev_word, h_in, h_out, s) != hipSuccess)
         return RNNLM_EDEVICE;
-    if (launch_query(d, N, n_unique, N, K, splits, query_word, inverse, h_out, logprob, s) != hipSuccess)
+    if (launch_outproj(d, N, c.n_miss, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (launch_cache_commit(c, d, N, n_unique, splits, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_query(d, N, n_unique, N, K, splits, query_word, inverse, h_out, c.lse_rows, base_score, score,
+                     s) != hipSuccess)
         return RNNLM_EDEVICE;
     return RNNLM_OK;
+}
+
+int rnnlm_cache_create(const rnnlm_model *model, int capacity, rnnlm_cache **out) {
+    if (!out) return RNNLM_EINVAL;
+    *out = nullptr;
+    if (!model || capacity < 0) return RNNLM_EINVAL;
+    if (capacity > (1 << 26)) return RNNLM_ERANGE;
+    rnnlm_cache *c = new (std::nothrow) rnnlm_cache();
+    if (!c) return RNNLM_ENOMEM;
+    memset(c, 0, sizeof(*c));
+    int status = RNNLM_OK;
+    CacheDev &d = c->dev;
+    d.capacity = capacity;
+    d.table_size = 64;
+    while (d.table_size < 2 * capacity) d.table_size <<= 1;
+    d.H = model->dev.H;
+    c->max_B = model->max_B;
+    const size_t nb = (size_t)model->max_B, cap1 = capacity > 0 ? (size_t)capacity : 1;
+    void *p;
+    HIP_TRY(hipMalloc(&p, (size_t)d.table_size * sizeof(CacheCell))); d.table = static_cast<CacheCell *>(p);
+    HIP_TRY(hipMalloc(&p, cap1 * d.H * 4)); d.store_h = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, cap1 * 4)); d.store_lse = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); d.n_entries = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, 4 * sizeof(long long))); d.totals = static_cast<long long *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.entry_of = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_of = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_src = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_dst = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.lse_rows = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); d.n_miss = static_cast<int *>(p);
+    HIP_TRY(hipMemset(d.n_miss, 0, 4));
+    HIP_TRY(launch_cache_reset(d, nullptr));
+    HIP_TRY(hipDeviceSynchronize());
+    *out = c;
+    return RNNLM_OK;
+fail:
+    rnnlm_cache_free(c);
+    (void)hipGetLastError();
+    return status;
+}
+
+int rnnlm_cache_free(rnnlm_cache *cache) {
+    if (!cache) return RNNLM_OK;
+    hipError_t e = hipDeviceSynchronize();
+    CacheDev &d = cache->dev;
+    (void)hipFree(d.table); (void)hipFree(d.store_h); (void)hipFree(d.store_lse); (void)hipFree(d.n_entries);
+    (void)hipFree(d.totals); (void)hipFree(d.entry_of); (void)hipFree(d.miss_of); (void)hipFree(d.miss_src);
+    (void)hipFree(d.miss_dst); (void)hipFree(d.lse_rows); (void)hipFree(d.n_miss);
+    delete cache;
+    return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
+}
+
+int rnnlm_cache_reset(rnnlm_cache *cache, void *hip_stream) {
+    if (!cache) return RNNLM_EINVAL;
+    return launch_cache_reset(cache->dev, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? RNNLM_OK
+                                                                                               : RNNLM_EDEVICE;
+}
+
+int rnnlm_cache_stats(rnnlm_cache *cache, void *hip_stream, int64_t out[5]) {
+    if (!cache || !out) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int entries = 0;
+    long long totals[4] = {0, 0, 0, 0};
+    if (hipMemcpyAsync(&entries, cache->dev.n_entries, 4, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (hipMemcpyAsync(totals, cache->dev.totals, sizeof(totals), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return RNNLM_EDEVICE;
+    out[0] = entries;
+    for (int i = 0; i < 4; ++i) out[1 + i] = totals[i];
+    return RNNLM_OK;
+}
+
+int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N, uint64_t *ids,
+                   void *hip_stream) {
+    if (N < 0) return RNNLM_EINVAL;
+    if (N > 0 && (!ctx_idx || !small_lm_idx || !ids)) return RNNLM_EINVAL;
+    return launch_pack_ids(ctx_idx, small_lm_idx, N, ids, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? RNNLM_OK
+               : RNNLM_EDEVICE;
 }
 
 int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream, float *ms_per_launch) {

@@ -1,0 +1,183 @@
+// The cache of RnnlmProb kept on the device between steps (Table 1 as a whole; Section 4.2:
+// once-computed results are reused for the same context; Section 5.3: a size boundary).
+//
+// Key: the 8-byte history id (Section 3.2).  Value: what every answer for that history is
+// made of -- its updated hidden vector h' (fp32) and its natural-log normaliser -- so a
+// history found here skips the hidden update and the whole-vocabulary normalisation; only
+// the H-long dot products of its queried words remain.  Entries are numbered in the order
+// in which they were stored (Table 1 step 10) and never removed; the table is open
+// addressing over 16-byte cells, at most half full.
+//
+// One step through the cache, after the grouping of the step's own ids:
+//   lookup   one workgroup: probe every distinct history; the ones not found are numbered in
+//            order of appearance by a prefix sum (row of the block that is computed now),
+//            get the next entries while there is room, and their keys are inserted;
+//   (hidden update and output projection run on the numbered rows only)
+//   commit   per distinct history: normaliser into lse_rows; new entries are written to the
+//            stores, found ones copy their stored h' to the caller's h_out.
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+constexpr int kLookupThreads = 1024;
+
+__global__ __launch_bounds__(256) void cache_reset_kernel(CacheDev c) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < c.table_size) {
+        CacheCell cell;
+        cell.key = 0;
+        cell.entry = -1;
+        cell.pad = 0;
+        c.table[i] = cell;
+    }
+    if (i == 0) *c.n_entries = 0;
+    if (i < 4) c.totals[i] = 0;
+}
+
+__global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
+    CacheDev c, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
+    const int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
+    __shared__ int wsum[kLookupThreads / 64 + 1];
+    const int U = *n_unique;
+    const int base = *c.n_entries;          // read by everyone before thread 0 updates it below
+    const uint32_t mask = (uint32_t)(c.table_size - 1);
+    int n_miss = 0;                         // misses numbered so far (same in every thread)
+    for (int u0 = 0; u0 < U; u0 += kLookupThreads) {
+        const int u = u0 + (int)threadIdx.x;
+        const bool active = u < U;
+        uint64_t key = 0;
+        int found = -1;
+        int raw = 0;
+        if (active) {
+            raw = rep[u];
+            key = ids[raw];
+            if (c.capacity > 0) {
+                // At most capacity <= table_size / 2 cells are taken: a free cell is always met.
+                uint32_t h = mix64(key) & mask;
+                for (int probe = 0; probe < c.table_size; ++probe) {
+                    const CacheCell cell = c.table[h];
+                    if (cell.entry < 0) break;
+                    if (cell.key == key) { found = cell.entry; break; }
+                    h = (h + 1) & mask;
+                }
+            }
+        }
+        const int miss = (active && found < 0) ? 1 : 0;
+        int total;
+        const int rank = n_miss + block_exclusive_scan(miss, wsum, total);
+        // The scan's barriers separate this chunk's probes from its insertions; a later chunk
+        // probes after the barrier of its own scan call... so order them explicitly as well.
+        if (active) {
+            if (miss) {
+                const int entry = (base + rank < c.capacity) ? base + rank : -1;
+                c.miss_of[u] = rank;
+                c.miss_src[rank] = raw;
+                c.miss_dst[rank] = u;
+                c.entry_of[u] = entry;
+                if (entry >= 0) {
+                    uint32_t h = mix64(key) & mask;
+                    for (int probe = 0; probe < c.table_size; ++probe) {
+                        if (atomicCAS(&c.table[h].entry, -1, entry) == -1) {
+                            c.table[h].key = key;      // nobody reads keys until the next barrier
+                            break;
+                        }
+                        h = (h + 1) & mask;
+                    }
+                }
+            } else {
+                c.miss_of[u] = -1;
+                c.entry_of[u] = found;
+            }
+        }
+        n_miss += total;
+        __threadfence_block();
+        __syncthreads();                    // insertions of this chunk are visible to the next probes
+    }
+    if (threadIdx.x == 0) {
+        const int stored = min(n_miss, max(c.capacity - base, 0));
+        *c.n_miss = n_miss;
+        *c.n_entries = base + stored;
+        c.totals[0] += U;
+        c.totals[1] += U - n_miss;
+        c.totals[2] += n_miss;
+        c.totals[3] += n_miss - stored;
+        if (step_stats) {
+            step_stats[0] = U;
+            step_stats[1] = U - n_miss;
+            step_stats[2] = n_miss;
+            step_stats[3] = base + stored;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void cache_commit_kernel(CacheDev c, ModelDev m,
+                                                            const int32_t *__restrict__ n_unique,
+                                                            SplitInfo si, float *__restrict__ h_out) {
+    const int u = blockIdx.x;
+    if (u >= *n_unique) return;
+    const int H = c.H;
+    const int row = c.miss_of[u], entry = c.entry_of[u];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float *hrow = h_out + (size_t)u * H;
+    if (row >= 0) {
+        // computed in this step: its partials are in row `row` of the block of *n_miss rows
+        if (wave == 0) {
+            const int splits = si.fixed_splits > 0 ? si.fixed_splits
+                                                   : staged_plan(*c.n_miss, si.staged_wg_per_xcd).S;
+            const float lse = lse_from_partials(m.part + (size_t)row * kMaxSplits, splits, lane);
+            if (lane == 0) {
+                c.lse_rows[u] = lse;
+                if (entry >= 0) c.store_lse[entry] = lse;
+            }
+        }
+        if (entry >= 0) {
+            float *dst = c.store_h + (size_t)entry * H;
+            for (int j = threadIdx.x; j < H; j += 256) dst[j] = hrow[j];
+        }
+    } else {
+        const float *src = c.store_h + (size_t)entry * H;
+        for (int j = threadIdx.x; j < H; j += 256) hrow[j] = src[j];
+        if (threadIdx.x == 0) c.lse_rows[u] = c.store_lse[entry];
+    }
+}
+
+__global__ __launch_bounds__(256) void pack_ids_kernel(const uint32_t *__restrict__ ctx,
+                                                        const uint32_t *__restrict__ small_lm, int N,
+                                                        uint64_t *__restrict__ ids) {
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n < N) ids[n] = ((uint64_t)ctx[n] << 32) | (uint64_t)small_lm[n];
+}
+
+}  // namespace
+
+hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream) {
+    const int n = c.table_size > 4 ? c.table_size : 4;
+    hipLaunchKernelGGL(cache_reset_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, c);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_lookup(const CacheDev &c, const uint64_t *ids, const int32_t *rep,
+                               const int32_t *n_unique, int32_t *step_stats, hipStream_t stream) {
+    hipLaunchKernelGGL(cache_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, rep, n_unique,
+                       step_stats);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_commit(const CacheDev &c, const ModelDev &m, int rows, const int32_t *n_unique,
+                               SplitInfo splits, float *h_out, hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(cache_commit_kernel, dim3(rows), dim3(256), 0, stream, c, m, n_unique, splits, h_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_ids(const uint32_t *ctx, const uint32_t *small_lm, int N, uint64_t *ids,
+                           hipStream_t stream) {
+    if (N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pack_ids_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, ctx, small_lm, N, ids);
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm

@@ -24,14 +24,6 @@ constexpr int kSmallN = 4096;
 constexpr int kSmallCap = 8192;                      // LDS slots of the small path
 constexpr int kSmallThreads = 1024;
 
-__device__ __forceinline__ uint32_t mix64(uint64_t k) {
-    // splitmix64 finaliser
-    k ^= k >> 30; k *= 0xBF58476D1CE4E5B9ull;
-    k ^= k >> 27; k *= 0x94D049BB133111EBull;
-    k ^= k >> 31;
-    return (uint32_t)k;
-}
-
 __host__ __device__ inline int table_capacity(int N) {
     int cap = 64;
     while (cap < 2 * N) cap <<= 1;
@@ -52,36 +44,6 @@ __device__ __forceinline__ int find_or_insert(KeyPtr tkeys, int cap, uint64_t ke
         h = (h + 1) & (uint32_t)(cap - 1);
     }
     return -1;   // unreachable for N <= cap/2
-}
-
-// Block-wide exclusive prefix sum of one int per thread; returns the exclusive prefix and,
-// through `total`, the block sum.  `wsum` is LDS scratch of blockDim.x/64 + 1 ints.
-__device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int &total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    int incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(incl, off, 64);
-        if (lane >= off) incl += t;
-    }
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    if (wave == 0) {
-        int w = (lane < nwaves) ? wsum[lane] : 0;
-        int wi = w;
-#pragma unroll
-        for (int off = 1; off < 16; off <<= 1) {
-            int t = __shfl_up(wi, off, 64);
-            if (lane >= off) wi += t;
-        }
-        if (lane < nwaves) wsum[lane] = wi - w;       // exclusive prefix of the wave sums
-        if (lane == nwaves - 1) wsum[nwaves] = wi;    // block total
-    }
-    __syncthreads();
-    int excl = wsum[wave] + incl - v;
-    total = wsum[nwaves];
-    __syncthreads();                                  // wsum may be reused by the caller
-    return excl;
 }
 
 // ------------------------------------------------------------------------------ small path

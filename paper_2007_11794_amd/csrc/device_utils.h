@@ -125,6 +125,58 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// 64-bit key -> 32 well-mixed bits (hash tables of history ids).
+__device__ __forceinline__ uint32_t mix64(uint64_t k) {
+    // splitmix64 finaliser
+    k ^= k >> 30; k *= 0xBF58476D1CE4E5B9ull;
+    k ^= k >> 27; k *= 0x94D049BB133111EBull;
+    k ^= k >> 31;
+    return (uint32_t)k;
+}
+
+// Block-wide exclusive prefix sum of one int per thread; returns the exclusive prefix and,
+// through `total`, the block sum.  `wsum` is LDS scratch of blockDim.x/64 + 1 ints.
+__device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int &total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        int w = (lane < nwaves) ? wsum[lane] : 0;
+        int wi = w;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            int t = __shfl_up(wi, off, 64);
+            if (lane >= off) wi += t;
+        }
+        if (lane < nwaves) wsum[lane] = wi - w;       // exclusive prefix of the wave sums
+        if (lane == nwaves - 1) wsum[nwaves] = wi;    // block total
+    }
+    __syncthreads();
+    int excl = wsum[wave] + incl - v;
+    total = wsum[nwaves];
+    __syncthreads();                                  // wsum may be reused by the caller
+    return excl;
+}
+
+// Natural-log normaliser of one row from its `splits` per-split (max, sum) partials of the
+// base-2 log-sum-exp, merged in a fixed order by one whole wave (every lane gets the result).
+__device__ __forceinline__ float lse_from_partials(const float2 *part_row, int splits, int lane) {
+    float pm = -INFINITY, ps = 0.f;
+    for (int s = lane; s < splits; s += 64) {
+        float2 p = part_row[s];
+        lse2_merge(pm, ps, p.x, p.y);
+    }
+    const float mm = wave_max(pm);
+    const float ss = wave_sum(mm == -INFINITY ? 0.f : ps * fast_exp2(pm - mm));
+    return (mm + fast_log2(ss)) * 0.6931471805599453f;
+}
+
 __device__ __forceinline__ float quiet_nan() { return __uint_as_float(0x7FC00000u); }
 
 }  // namespace rnnlm

@@ -150,6 +150,7 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     char *const cring = lds + kStages * C::kStageBytes;
     const int B = B_dev ? *B_dev : rows;
+    if (B <= 0) return;                                       // uniform: nothing to do, no barrier met
     const StagedPlan plan = staged_plan(B, wg_per_xcd);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;

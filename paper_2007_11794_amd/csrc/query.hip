@@ -1,7 +1,8 @@
 // Query gather: only the log-probabilities the search asked for leave the device
 // (the paper's aim of exchanging as little as possible, Section 3.2; the returned value is
 // the p of Table 1 step 6):
-//     logprob[n][k] = z[r][q] - lse[r],  r = row_of_query[n],  q = query_word[n][k],
+//     logprob[n][k] = z[r][q] - lse[r] (- base_score[n][k], the difference the last paragraph
+//     of Section 4.2 sends back),  r = row_of_query[n],  q = query_word[n][k],
 // with z[r][q] = bias[q] + sum_j O[j][q] h'[r][j] recomputed as one H-long dot product per
 // queried word from the fp32 h' and the [V][H] copy of O (one contiguous row per word), and
 // lse[r] assembled from the per-split (max, sum) partials of the output projection in a
@@ -19,7 +20,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void query_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K, SplitInfo si,
     const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
-    const float *__restrict__ h_out, float *__restrict__ logprob) {
+    const float *__restrict__ h_out, const float *__restrict__ lse_rows,
+    const float *__restrict__ base_score, float *__restrict__ logprob) {
     const int B = B_dev ? *B_dev : rows;
     const int n = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -31,16 +33,15 @@ __global__ __launch_bounds__(256) void query_kernel(
         for (int k = threadIdx.x; k < K; k += 256) out[k] = quiet_nan();
         return;
     }
-    // lse of row r, in base 2: every wave assembles it, lane l taking splits l, l+64, ...
-    const int splits = si.fixed_splits > 0 ? si.fixed_splits : staged_plan(B, si.staged_wg_per_xcd).S;
-    float pm = -INFINITY, ps = 0.f;
-    for (int s = lane; s < splits; s += 64) {
-        float2 p = m.part[(size_t)r * kMaxSplits + s];
-        lse2_merge(pm, ps, p.x, p.y);
+    // lse of row r: handed in, or assembled by every wave from the partials, lane l taking
+    // splits l, l+64, ...
+    float lse;
+    if (lse_rows) {
+        lse = lse_rows[r];
+    } else {
+        const int splits = si.fixed_splits > 0 ? si.fixed_splits : staged_plan(B, si.staged_wg_per_xcd).S;
+        lse = lse_from_partials(m.part + (size_t)r * kMaxSplits, splits, lane);
     }
-    float mm = wave_max(pm);
-    float ss = wave_sum(mm == -INFINITY ? 0.f : ps * fast_exp2(pm - mm));
-    const float lse = (mm + fast_log2(ss)) * kLn2;
 
     const T *Ot = static_cast<const T *>(m.Ot);
     const float *hrow = h_out + (size_t)r * H;
@@ -76,7 +77,10 @@ __global__ __launch_bounds__(256) void query_kernel(
             if (k >= K) continue;                        // wave-uniform
             const float z = wave_sum(acc[u]);
             if (lane == 0) {
-                if (ok[u]) out[k] = (z + m.bias[q[u]]) - lse;
+                if (ok[u]) {
+                    const float lp = (z + m.bias[q[u]]) - lse;
+                    out[k] = base_score ? lp - base_score[(size_t)n * K + k] : lp;
+                }
                 else { atomicOr(m.flag, RNNLM_FLAG_BAD_QUERY_WORD); out[k] = quiet_nan(); }
             }
         }
@@ -87,14 +91,15 @@ __global__ __launch_bounds__(256) void query_kernel(
 
 hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, int K, SplitInfo splits,
                         const int32_t *query_word, const int32_t *row_of_query,
-                        const float *h_out, float *logprob, hipStream_t stream) {
+                        const float *h_out, const float *lse_rows, const float *base_score,
+                        float *logprob, hipStream_t stream) {
     if (N <= 0 || K <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16)
         hipLaunchKernelGGL(query_kernel<bf16_t>, dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
-                           query_word, row_of_query, h_out, logprob);
+                           query_word, row_of_query, h_out, lse_rows, base_score, logprob);
     else
         hipLaunchKernelGGL(query_kernel<float>, dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
-                           query_word, row_of_query, h_out, logprob);
+                           query_word, row_of_query, h_out, lse_rows, base_score, logprob);
     return hipGetLastError();
 }
 

@@ -36,7 +36,7 @@ constexpr int kRecurUnroll = 8;      // k-steps whose loads are in flight togeth
 
 __global__ __launch_bounds__(256) void recur_bf16_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
-    const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
+    const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
     float *__restrict__ h_out) {
     const int B = B_dev ? *B_dev : rows;
     const int b0 = blockIdx.y * 32;
@@ -97,6 +97,7 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
         red[wave][q][lane] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
     __syncthreads();
     if (!row_ok) return;
+    const int bo = row_dst ? row_dst[b] : b;         // row of h_out; the operand block keeps row b
     f32x4 a4 = red[0][wave][lane];
 #pragma unroll
     for (int sw = 1; sw < 4; ++sw) {                 // fixed order: deterministic
@@ -116,11 +117,11 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
     // padded units (zero weights, zero embedding) come out as sigmoid(0) - 1/2 = 0
     *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
     if (vec_ok && je + 4 <= H) {
-        *reinterpret_cast<f32x4 *>(h_out + (size_t)b * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
+        *reinterpret_cast<f32x4 *>(h_out + (size_t)bo * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (je + i < H) h_out[(size_t)b * H + je + i] = hp[i];
+            if (je + i < H) h_out[(size_t)bo * H + je + i] = hp[i];
     }
 }
 
@@ -142,7 +143,7 @@ __device__ __forceinline__ f32x4 load4_row(const float *row, int k0, int H, bool
 
 __global__ __launch_bounds__(256) void recur_f32_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
-    const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
+    const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
     float *__restrict__ h_out) {
     const int B = B_dev ? *B_dev : rows;
     const int b0 = blockIdx.y * 32;
@@ -194,6 +195,7 @@ __global__ __launch_bounds__(256) void recur_f32_kernel(
         red[wave][q][lane] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
     __syncthreads();
     if (!row_ok) return;
+    const int bo = row_dst ? row_dst[b] : b;         // row of h_out; the operand block keeps row b
     f32x4 a4 = red[0][wave][lane];
 #pragma unroll
     for (int sw = 1; sw < 4; ++sw) {                 // fixed order: deterministic
@@ -210,28 +212,28 @@ __global__ __launch_bounds__(256) void recur_f32_kernel(
     }
     *reinterpret_cast<f32x4 *>(static_cast<float *>(m.d) + (size_t)b * Hp + je) = dv;
     if (vec_ok && je + 4 <= H) {
-        *reinterpret_cast<f32x4 *>(h_out + (size_t)b * H + je) = hp;
+        *reinterpret_cast<f32x4 *>(h_out + (size_t)bo * H + je) = hp;
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (je + i < H) h_out[(size_t)b * H + je + i] = hp[i];
+            if (je + i < H) h_out[(size_t)bo * H + je + i] = hp[i];
     }
 }
 
 }  // namespace
 
 hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int32_t *row_src,
-                        const int32_t *prev_word, const float *h_in, float *h_out,
-                        hipStream_t stream) {
+                        const int32_t *row_dst, const int32_t *prev_word, const float *h_in,
+                        float *h_out, hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16) {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);
         hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
-                           prev_word, h_in, h_out);
+                           row_dst, prev_word, h_in, h_out);
     } else {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);
         hipLaunchKernelGGL(recur_f32_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
-                           prev_word, h_in, h_out);
+                           row_dst, prev_word, h_in, h_out);
     }
     return hipGetLastError();
 }

@@ -38,7 +38,35 @@ struct ModelDev {
     int *flag;         // sticky rnnlm_device_flag bits
 };
 
+// Device-side view of a cache kept between steps (cache.hip).
+struct CacheCell {          // one slot of the open-addressing table
+    uint64_t key;
+    int32_t entry;          // index into the stores, -1 = free
+    int32_t pad;
+};
+struct CacheDev {
+    int capacity;           // entries the stores can hold
+    int table_size;         // power of two >= 2 * capacity
+    int H;
+    CacheCell *table;       // [table_size]
+    float *store_h;         // [capacity][H]  updated hidden vectors
+    float *store_lse;       // [capacity]     natural-log normalisers
+    int *n_entries;         // [1]
+    long long *totals;      // [4] looked up, found, computed, computed but not kept
+    // per-step scratch, each [max_B]
+    int32_t *entry_of;      // distinct history u -> its entry (found or newly given), or -1
+    int32_t *miss_of;       // u -> row of this step's computed block, or -1 when found
+    int32_t *miss_src;      // computed row -> raw query that holds its prev word and h_in
+    int32_t *miss_dst;      // computed row -> u
+    float *lse_rows;        // [max_B] normaliser of every distinct history of the step
+    int *n_miss;            // [1]
+};
 }  // namespace rnnlm
+
+struct rnnlm_cache {
+    rnnlm::CacheDev dev;
+    int max_B;
+};
 
 struct rnnlm_model {
     rnnlm::ModelDev dev;
@@ -60,10 +88,11 @@ hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inve
 
 // Hidden update.  rows = number of rows the grid must cover (>= the true B); the true B is
 // *B_dev when B_dev != nullptr, else rows.  row_src (nullable) maps row b to the raw row
-// that holds its prev word and h_in.
+// that holds its prev word and h_in; row_dst (nullable) maps it to its row of h_out (the
+// operand block m.d always takes row b).
 hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int32_t *row_src,
-                        const int32_t *prev_word, const float *h_in, float *h_out,
-                        hipStream_t stream);
+                        const int32_t *row_dst, const int32_t *prev_word, const float *h_in,
+                        float *h_out, hipStream_t stream);
 
 // How many (max, sum) partials per row the output projection left in m.part: a fixed
 // number, or (staged kernel, whose split count follows the true number of rows that only
@@ -97,10 +126,26 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
                           int kernel_choice, SplitInfo *splits, hipStream_t stream);
 bool outproj_staged_supported(const ModelDev &m);
 
-// Query gather: logprob[n][k] = z[row(n)][query[n][k]] - lse[row(n)].
+// Query gather: logprob[n][k] = z[row(n)][query[n][k]] - lse[row(n)] - base_score[n][k].
+// lse comes from lse_rows[row] when that is given, else from the partials in m.part;
+// base_score may be null.
 hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, int K, SplitInfo splits,
                         const int32_t *query_word, const int32_t *row_of_query,
-                        const float *h_out, float *logprob, hipStream_t stream);
+                        const float *h_out, const float *lse_rows, const float *base_score,
+                        float *logprob, hipStream_t stream);
+
+// ---- cache kept between steps (cache.hip)
+hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream);
+// Looks the distinct histories ids[rep[u]], u < *n_unique, up; numbers the ones not found
+// (in order of u), gives them entries while there is room and inserts their keys.
+hipError_t launch_cache_lookup(const CacheDev &c, const uint64_t *ids, const int32_t *rep,
+                               const int32_t *n_unique, int32_t *step_stats, hipStream_t stream);
+// After the computed block is done: normalisers of all distinct histories into c.lse_rows,
+// new entries into the stores, stored hidden vectors of found histories into h_out.
+hipError_t launch_cache_commit(const CacheDev &c, const ModelDev &m, int rows, const int32_t *n_unique,
+                               SplitInfo splits, float *h_out, hipStream_t stream);
+hipError_t launch_pack_ids(const uint32_t *ctx, const uint32_t *small_lm, int N, uint64_t *ids,
+                           hipStream_t stream);
 
 // Load-time helpers.
 hipError_t launch_transpose_O(const void *O_dev /*[H][V]*/, void *Ot /*[Vp][Hp]*/, int dtype,

@@ -70,3 +70,32 @@ def gpu_step_dedup(m: rn.RnnlmModel, keys, prev, h_in, query):
     return {"n_unique": U, "rep": rep.cpu().numpy()[:U], "inverse": inv.cpu().numpy(),
             "h_out": h_out.cpu().numpy()[:U], "h_out_rest": h_out.cpu().numpy()[U:],
             "logprob": lp.cpu().numpy()}
+
+
+class CachedStepper:
+    """Device buffers for repeated rnnlm_step_cached calls of up to N raw queries."""
+
+    def __init__(self, m: rn.RnnlmModel, cache, N: int, K: int):
+        self.m, self.cache, self.N, self.K = m, cache, N, K
+        self.ws = torch.empty(max(rn.rnnlm_dedup_workspace_bytes(N), 16), device=DEV, dtype=torch.uint8)
+
+    def step(self, keys, prev, h_in, query, base_score=None):
+        N, K = query.shape
+        k_t = keys_tensor(keys) if N else torch.zeros(0, dtype=torch.int64, device=DEV)
+        prev_t = torch.from_numpy(np.ascontiguousarray(prev, np.int32)).to(DEV)
+        h_t = torch.from_numpy(np.ascontiguousarray(h_in, np.float32)).to(DEV)
+        q_t = torch.from_numpy(np.ascontiguousarray(query, np.int32)).to(DEV)
+        b_t = None if base_score is None else torch.from_numpy(np.ascontiguousarray(base_score, np.float32)).to(DEV)
+        rep = torch.full((N,), -1, device=DEV, dtype=torch.int32)
+        inv = torch.full((N,), -1, device=DEV, dtype=torch.int32)
+        nu = torch.full((1,), -1, device=DEV, dtype=torch.int32)
+        stats = torch.full((4,), -1, device=DEV, dtype=torch.int32)
+        h_out = torch.full((N, self.m.H), float("nan"), device=DEV, dtype=torch.float32)
+        score = torch.full((N, K), float("nan"), device=DEV, dtype=torch.float32)
+        rn.rnnlm_step_cached(self.m, self.cache, k_t, prev_t, h_t, q_t, rep, inv, nu, h_out, score, self.ws,
+                             base_score=b_t, step_stats=stats)
+        torch.cuda.synchronize()
+        U = int(nu.item())
+        return {"n_unique": U, "rep": rep.cpu().numpy()[:U], "inverse": inv.cpu().numpy(),
+                "h_out": h_out.cpu().numpy()[:U], "h_out_rest": h_out.cpu().numpy()[U:],
+                "score": score.cpu().numpy(), "stats": tuple(int(v) for v in stats.cpu().numpy())}

@@ -1,0 +1,199 @@
+"""GPU tests of the cache kept between steps (rnnlm_step_cached, rnnlm_cache_*, rnnlm_pack_ids)
+against the oracle's RnnlmProb-with-cache, through the C ABI.
+
+Bars: grouping indices and the hit / computed / stored counts bit-exact; values within the
+step's tolerances; a value answered from the cache bit-identical to the one first computed.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2007_11794_amd as rn
+from workloads import CONFIGS, DecodeTrace, bf16_bits, make_model, round_to_bf16
+
+from harness import DEV, CachedStepper, gpu_step_dedup, load_model
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (2e-3, 1e-3)}      # (score, h)
+
+
+def small_model(rng, V, H, dtype, sigma):
+    m = {"U": rng.normal(0, sigma, (V, H)).astype(np.float32),
+         "W": rng.normal(0, sigma, (H, H)).astype(np.float32),
+         "O": rng.normal(0, sigma, (H, V)).astype(np.float32),
+         "bias": rng.normal(0, 0.5, V).astype(np.float32)}
+    if dtype == "bf16":
+        for k in ("U", "W", "O"):
+            m[k] = round_to_bf16(m[k])
+    return m
+
+
+def draw_step(rng, V, H, N, K, pool):
+    ids = rng.choice(pool, size=N).astype(np.uint64)
+    prev = rng.integers(0, V, N).astype(np.int32)
+    h_in = rng.uniform(0, 1, (N, H)).astype(np.float32)
+    first = {}
+    for n in range(N):                       # rows of one id agree within a step
+        f = first.setdefault(int(ids[n]), n)
+        prev[n], h_in[n] = prev[f], h_in[f]
+    query = rng.integers(0, V, (N, K)).astype(np.int32)
+    base = rng.normal(-6, 2, (N, K)).astype(np.float32)
+    return ids, prev, h_in, query, base
+
+
+def compare(out, ref, dtype, what):
+    tol_s, tol_h = TOL[dtype]
+    assert out["n_unique"] == ref["n_unique"], what
+    assert np.array_equal(out["rep"], ref["rep"]) and np.array_equal(out["inverse"], ref["inverse"]), what
+    assert out["stats"] == ref["stats"], (what, out["stats"], ref["stats"])
+    assert np.all(np.isnan(out["h_out_rest"])), what
+    dh = np.max(np.abs(out["h_out"].astype(np.float64) - ref["h_out"])) if out["h_out"].size else 0.0
+    ds = np.max(np.abs(out["score"].astype(np.float64) - ref["score"])) if out["score"].size else 0.0
+    print("%s stats=%s max|dh|=%.3g max|dscore|=%.3g" % (what, out["stats"], dh, ds), flush=True)
+    assert np.all(np.isfinite(out["h_out"])) and np.all(np.isfinite(out["score"])), what
+    assert dh <= tol_h and ds <= tol_s, (what, dh, ds)
+
+
+@pytest.mark.parametrize("dtype,V,H,kernel", [
+    ("bf16", 8200, 256, 0),      # staged output projection
+    ("bf16", 4099, 160, 0),      # Hp = 192: tiled / plain kernels
+    ("bf16", 8200, 256, 1),
+    ("f32", 3001, 96, 0),
+])
+@pytest.mark.parametrize("capacity", [100000, 150, 0])
+def test_steps_through_the_cache_match_the_oracle(dtype, V, H, kernel, capacity):
+    rng = np.random.default_rng(V + H + capacity)
+    K = 5
+    model = small_model(rng, V, H, dtype, 0.05)
+    m = load_model(model, dtype, 700)
+    if kernel:
+        m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
+    cache = rn.rnnlm_cache_create(m, capacity)
+    ocache = oracle.Cache(H, capacity)
+    pool = (np.arange(400, dtype=np.uint64) << np.uint64(32)) | np.uint64(0xABCD)
+    pool[3] = np.uint64(0xFFFFFFFFFFFFFFFF)
+    pool[4] = np.uint64(0)
+    st = CachedStepper(m, cache, 700, K)
+    for step, N in enumerate([300, 700, 64, 1, 513]):
+        ids, prev, h_in, query, base = draw_step(rng, V, H, N, K, pool)
+        use_base = base if step % 2 == 0 else None
+        out = st.step(ids, prev, h_in, query, use_base)
+        ref = oracle.step_cached(model, ocache, ids, prev, h_in, query, base_score=use_base)
+        compare(out, ref, dtype, "%s V=%d H=%d cap=%d step %d" % (dtype, V, H, capacity, step))
+    s = cache.stats()
+    assert s == ocache.stats()
+    assert m.last_error() == 0
+    cache.close()
+    m.close()
+
+
+def test_answer_from_cache_is_bit_identical_and_ignores_new_inputs():
+    rng = np.random.default_rng(5)
+    V, H, N, K = 6000, 128, 400, 6
+    model = small_model(rng, V, H, "bf16", 0.05)
+    m = load_model(model, "bf16", N)
+    cache = rn.rnnlm_cache_create(m, 1000)
+    st = CachedStepper(m, cache, N, K)
+    ids, prev, h_in, query, _ = draw_step(rng, V, H, N, K, np.arange(1, 120, dtype=np.uint64))
+    a = st.step(ids, prev, h_in, query)
+    assert a["stats"] == (a["n_unique"], 0, a["n_unique"], a["n_unique"])
+    # all histories are now held: nothing is computed, and changed prev / h_in change nothing
+    b = st.step(ids, (prev + 7) % V, (1.0 - h_in).astype(np.float32), query)
+    assert b["stats"] == (a["n_unique"], a["n_unique"], 0, a["n_unique"])
+    assert np.array_equal(a["h_out"], b["h_out"])
+    assert np.array_equal(a["score"], b["score"])
+    # a permutation of the raw queries: every query keeps its answer
+    perm = rng.permutation(N)
+    c = st.step(ids[perm], prev[perm], h_in[perm], query[perm])
+    assert c["stats"][1:3] == (a["n_unique"], 0)
+    assert np.array_equal(c["score"], a["score"][perm])
+    # after a reset everything is computed again, with the inputs given now
+    cache.reset()
+    d = st.step(ids, prev, h_in, query)
+    assert d["stats"] == a["stats"]
+    assert np.array_equal(d["score"], a["score"])           # same inputs, same computation
+    assert cache.stats() == dict(entries=a["n_unique"], lookups=a["n_unique"], hits=0,
+                                 misses=a["n_unique"], unstored=0)
+    cache.close()
+    m.close()
+
+
+def test_without_cache_equals_step_dedup_and_base_score_is_subtracted():
+    rng = np.random.default_rng(6)
+    V, H, N, K = 5000, 256, 300, 4
+    model = small_model(rng, V, H, "bf16", 0.05)
+    m = load_model(model, "bf16", N)
+    ids, prev, h_in, query, base = draw_step(rng, V, H, N, K, np.arange(50, dtype=np.uint64))
+    plain = gpu_step_dedup(m, ids, prev, h_in, query)
+    st = CachedStepper(m, None, N, K)
+    a = st.step(ids, prev, h_in, query)
+    assert np.array_equal(a["score"], plain["logprob"]) and np.array_equal(a["h_out"], plain["h_out"])
+    b = st.step(ids, prev, h_in, query, base)
+    assert np.array_equal(b["score"], plain["logprob"] - base)      # one fp32 subtraction
+    ref = oracle.step_cached(model, None, ids, prev, h_in, query, base_score=base)
+    assert np.max(np.abs(b["score"] - ref["score"])) <= TOL["bf16"][0]
+    m.close()
+
+
+def test_empty_batch_and_argument_errors():
+    rng = np.random.default_rng(7)
+    model = small_model(rng, 500, 64, "f32", 0.1)
+    m = load_model(model, "f32", 32)
+    other = load_model(small_model(rng, 500, 32, "f32", 0.1), "f32", 32)
+    cache = rn.rnnlm_cache_create(m, 10)
+    st = CachedStepper(m, cache, 32, 3)
+    out = st.step(np.zeros(0, np.uint64), np.zeros(0, np.int32), np.zeros((0, 64), np.float32),
+                  np.zeros((0, 3), np.int32))
+    assert out["n_unique"] == 0 and out["stats"] == (0, 0, 0, 0)
+    with pytest.raises(rn.RnnlmError) as e:
+        rn.rnnlm_cache_create(m, -1)
+    assert e.value.status == -1
+    # a cache made for another hidden size is refused before anything is launched
+    st2 = CachedStepper(other, cache, 32, 3)
+    with pytest.raises(rn.RnnlmError) as e:
+        st2.step(np.arange(4, dtype=np.uint64), np.zeros(4, np.int32), np.zeros((4, 32), np.float32),
+                 np.zeros((4, 3), np.int32))
+    assert e.value.status == -4
+    cache.close()
+    other.close()
+    m.close()
+
+
+def test_config4_trace_through_the_cache():
+    """The decode trace at full size (N = 4096, V = 65536, H = 512), 6 steps: half of the
+    distinct histories of a step were seen in the step before and must come from the cache."""
+    cfg = CONFIGS[4]
+    model = make_model(cfg)
+    m = load_model(model, cfg.dtype, cfg.N)
+    cache = rn.rnnlm_cache_create(m, 20000)
+    ocache = oracle.Cache(cfg.H, 20000)
+    st = CachedStepper(m, cache, cfg.N, cfg.K)
+    tr_g, tr_o = DecodeTrace(cfg), DecodeTrace(cfg)
+    xg, xo = tr_g.first(), tr_o.first()
+    for step in range(6):
+        out = st.step(xg["keys"], xg["prev"], xg["h_in"], xg["query"])
+        ref = oracle.step_cached(model, ocache, xo["keys"], xo["prev"], xo["h_in"], xo["query"])
+        compare(out, ref, "bf16", "cfg4 cached step %d" % step)
+        if step:
+            assert out["stats"][1] == int(xg["carried"].sum()) > 0
+        xg = tr_g.next(xg, out["h_out"], out["inverse"])
+        xo = tr_o.next(xo, ref["h_out"], ref["inverse"])
+    assert m.last_error() == 0
+    cache.close()
+    m.close()
+
+
+def test_pack_ids_bit_exact():
+    rng = np.random.default_rng(8)
+    for N in (0, 1, 255, 256, 10001):
+        ctx = rng.integers(0, 2 ** 32, N, dtype=np.uint64).astype(np.uint32)
+        small = rng.integers(0, 2 ** 32, N, dtype=np.uint64).astype(np.uint32)
+        if N > 2:
+            ctx[0], small[0] = 0xFFFFFFFF, 0xFFFFFFFF
+            ctx[1], small[1] = 0, 0
+        ids = torch.zeros(N, dtype=torch.int64, device=DEV)
+        rn.rnnlm_pack_ids(torch.from_numpy(ctx.view(np.int32)).to(DEV), torch.from_numpy(small.view(np.int32)).to(DEV), ids)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy().view(np.uint64), oracle.pack_ids(ctx, small))
