@@ -40,6 +40,10 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3,
                     help="workload number (default 3 = the headline one the metric is quoted on; "
                          "4 and 5 are the decode-trace and stress workloads)")
+    ap.add_argument("--cache", type=int, default=None, metavar="CAPACITY",
+                    help="config 4 only: time a decode trace of --trace-steps steps through a cache of "
+                         "CAPACITY histories kept between the steps (reset at the start of every pass)")
+    ap.add_argument("--trace-steps", type=int, default=8)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy kernel, as the known-size "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -89,6 +93,43 @@ def main() -> int:
     def step():
         rn.rnnlm_step_dedup(m, keys, prev, h_in, query, rep, inv, nu, h_out, lp, ws)
 
+    cache_info = None
+    if args.cache is not None:
+        if cfg.unique_frac is None:
+            print("bench.py: --cache needs the decode-trace workload (--config 4)", file=sys.stderr)
+            return 2
+        # The trace is built once, untimed: step t+1 grows from the hidden vectors step t returned.
+        tr = DecodeTrace(cfg)
+        xt, trace = tr.first(), []
+        for _ in range(args.trace_steps):
+            dev_in = tuple(torch.from_numpy(a).to(dev) for a in
+                           (xt["keys"].view(np.int64), xt["prev"], xt["h_in"], xt["query"]))
+            rn.rnnlm_step_dedup(m, *dev_in, rep, inv, nu, h_out, lp, ws)
+            torch.cuda.synchronize()
+            trace.append(dev_in)
+            xt = tr.next(xt, h_out.cpu().numpy(), inv.cpu().numpy())
+        cache = rn.rnnlm_cache_create(m, args.cache)
+        stats = torch.zeros(4, dtype=torch.int32, device=dev)
+
+        def step():                                 # one pass over the whole trace = one utterance
+            cache.reset()
+            for dev_in in trace:
+                rn.rnnlm_step_cached(m, cache, *dev_in, rep, inv, nu, h_out, lp, ws, step_stats=stats)
+
+        def uncached_pass():
+            for dev_in in trace:
+                rn.rnnlm_step_dedup(m, *dev_in, rep, inv, nu, h_out, lp, ws)
+
+        for _ in range(3):
+            uncached_pass()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            uncached_pass()
+        torch.cuda.synchronize()
+        cache_info = {"capacity": args.cache, "trace_steps": args.trace_steps,
+                      "uncached_value": round(N * args.trace_steps * 20 / (time.perf_counter() - t0), 1)}
+
     if args.calibrate_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
         dst = torch.empty_like(src)
@@ -108,6 +149,13 @@ def main() -> int:
     assert (B == cfg.B or cfg.unique_frac is not None) and m.last_error() == 0
     ms_per_step = dt / args.steps * 1e3
     value = N * args.steps / dt
+    if cache_info is not None:                      # a "step" was a pass over the whole trace
+        ms_per_step /= args.trace_steps
+        value *= args.trace_steps
+        st = cache.stats()
+        cache_info.update(hit_ratio=round(st["hits"] / max(st["lookups"], 1), 4), entries=st["entries"],
+                          note="value = raw queries / s over the trace through the cache; hit_ratio over "
+                               "distinct histories per step; uncached_value = same trace without the cache")
 
     # dominant kernel: output projection + log-sum-exp, timed alone with HIP events on its stream
     reps = 50 if args.config == 3 else 10
@@ -167,6 +215,8 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if cache_info is not None:
+        out["cache"] = cache_info
     print(json.dumps(out))
     m.close()
     return 0

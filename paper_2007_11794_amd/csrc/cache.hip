@@ -37,6 +37,15 @@ __global__ __launch_bounds__(256) void cache_reset_kernel(CacheDev c) {
     if (i < 4) c.totals[i] = 0;
 }
 
+// One workgroup.  A round covers kLookupPer * 1024 distinct histories: every thread first
+// requests the first table cell of all its kLookupPer histories (the usual probe ends there),
+// then finishes the probes, then the round's misses are numbered chunk by chunk in order of
+// u, and last the new keys are inserted.  Insertions happen only after every probe of the
+// round is over (barriers of the scans in between), so no probe reads a half-written cell;
+// the keys of one step are distinct, so a later round can never look for a key that an
+// earlier round of the same step inserted.
+constexpr int kLookupPer = 4;
+
 __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
     CacheDev c, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
     const int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
@@ -45,56 +54,70 @@ __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
     const int base = *c.n_entries;          // read by everyone before thread 0 updates it below
     const uint32_t mask = (uint32_t)(c.table_size - 1);
     int n_miss = 0;                         // misses numbered so far (same in every thread)
-    for (int u0 = 0; u0 < U; u0 += kLookupThreads) {
-        const int u = u0 + (int)threadIdx.x;
-        const bool active = u < U;
-        uint64_t key = 0;
-        int found = -1;
-        int raw = 0;
-        if (active) {
-            raw = rep[u];
-            key = ids[raw];
-            if (c.capacity > 0) {
-                // At most capacity <= table_size / 2 cells are taken: a free cell is always met.
-                uint32_t h = mix64(key) & mask;
-                for (int probe = 0; probe < c.table_size; ++probe) {
-                    const CacheCell cell = c.table[h];
-                    if (cell.entry < 0) break;
-                    if (cell.key == key) { found = cell.entry; break; }
-                    h = (h + 1) & mask;
-                }
+    for (int u0 = 0; u0 < U; u0 += kLookupPer * kLookupThreads) {
+        uint64_t key[kLookupPer];
+        int raw[kLookupPer], found[kLookupPer];
+        uint32_t h[kLookupPer];
+        CacheCell cell[kLookupPer];
+#pragma unroll
+        for (int i = 0; i < kLookupPer; ++i) {
+            const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
+            raw[i] = (u < U) ? rep[u] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < kLookupPer; ++i) {
+            const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
+            key[i] = (u < U) ? ids[raw[i]] : 0;
+            h[i] = mix64(key[i]) & mask;
+            cell[i] = c.table[h[i]];
+        }
+#pragma unroll
+        for (int i = 0; i < kLookupPer; ++i) {
+            found[i] = -1;
+            // At most capacity <= table_size / 2 cells are taken: a free cell is always met.
+            for (int probe = 0; probe < c.table_size; ++probe) {
+                if (cell[i].entry < 0) break;
+                if (cell[i].key == key[i]) { found[i] = cell[i].entry; break; }
+                h[i] = (h[i] + 1) & mask;
+                cell[i] = c.table[h[i]];
             }
         }
-        const int miss = (active && found < 0) ? 1 : 0;
-        int total;
-        const int rank = n_miss + block_exclusive_scan(miss, wsum, total);
-        // The scan's barriers separate this chunk's probes from its insertions; a later chunk
-        // probes after the barrier of its own scan call... so order them explicitly as well.
-        if (active) {
+        int entry[kLookupPer];
+#pragma unroll
+        for (int i = 0; i < kLookupPer; ++i) {
+            const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
+            const bool active = u < U;
+            const int miss = (active && found[i] < 0) ? 1 : 0;
+            int total;
+            const int rank = n_miss + block_exclusive_scan(miss, wsum, total);
+            n_miss += total;
+            entry[i] = -1;
             if (miss) {
-                const int entry = (base + rank < c.capacity) ? base + rank : -1;
+                entry[i] = (base + rank < c.capacity) ? base + rank : -1;
                 c.miss_of[u] = rank;
-                c.miss_src[rank] = raw;
+                c.miss_src[rank] = raw[i];
                 c.miss_dst[rank] = u;
-                c.entry_of[u] = entry;
-                if (entry >= 0) {
-                    uint32_t h = mix64(key) & mask;
-                    for (int probe = 0; probe < c.table_size; ++probe) {
-                        if (atomicCAS(&c.table[h].entry, -1, entry) == -1) {
-                            c.table[h].key = key;      // nobody reads keys until the next barrier
-                            break;
-                        }
-                        h = (h + 1) & mask;
-                    }
-                }
-            } else {
+                c.entry_of[u] = entry[i];
+            } else if (active) {
                 c.miss_of[u] = -1;
-                c.entry_of[u] = found;
+                c.entry_of[u] = found[i];
             }
         }
-        n_miss += total;
+        // every probe of this round is done (the scans above contain barriers)
+#pragma unroll
+        for (int i = 0; i < kLookupPer; ++i) {
+            if (entry[i] < 0) continue;
+            uint32_t hh = mix64(key[i]) & mask;
+            for (int probe = 0; probe < c.table_size; ++probe) {
+                if (atomicCAS(&c.table[hh].entry, -1, entry[i]) == -1) {
+                    c.table[hh].key = key[i];
+                    break;
+                }
+                hh = (hh + 1) & mask;
+            }
+        }
         __threadfence_block();
-        __syncthreads();                    // insertions of this chunk are visible to the next probes
+        __syncthreads();                    // this round's insertions precede the next round's probes
     }
     if (threadIdx.x == 0) {
         const int stored = min(n_miss, max(c.capacity - base, 0));

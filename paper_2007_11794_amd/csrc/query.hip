@@ -16,47 +16,88 @@ namespace {
 
 constexpr int kQueryBatch = 8;
 
-template <typename T>
+// Word u of a batch is finished by the lanes whose bits (5, 4, 3) spell u.
+__device__ __forceinline__ int batch_slot_of_lane(int lane) {
+    return ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+}
+constexpr int lane_of_batch_slot(int u) { return 32 * ((u >> 2) & 1) + 16 * ((u >> 1) & 1) + 8 * (u & 1); }
+
+// Sums over the wave of eight per-lane values at once: the same xor butterfly (32, 16, ...,
+// 1) as wave_sum, but in the first three levels a lane passes on the half of the values it
+// will not finish, so 10 exchanges do the work of 48.  Returns the sum of value
+// batch_slot_of_lane(lane); bit-identical to wave_sum of that value.
+__device__ __forceinline__ float wave_sum8(const float (&acc)[kQueryBatch], int lane) {
+    float v4[4], v2[2];
+    const bool up5 = (lane & 32) != 0, up4 = (lane & 16) != 0, up3 = (lane & 8) != 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v4[i] = (up5 ? acc[4 + i] : acc[i]) + __shfl_xor(up5 ? acc[i] : acc[4 + i], 32, 64);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) v2[i] = (up4 ? v4[2 + i] : v4[i]) + __shfl_xor(up4 ? v4[i] : v4[2 + i], 16, 64);
+    float v = (up3 ? v2[1] : v2[0]) + __shfl_xor(up3 ? v2[0] : v2[1], 8, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 1, 64);
+    return v;
+}
+
+// A workgroup of four waves serves QPW raw queries (4, 2 or 1): with few words per query a
+// whole wave per query keeps the eight-row batches full; with many, the four waves share
+// one query's words.  Nothing branches on loaded values before the stores, so the loads of
+// a batch (row index, word ids, their bias and base score, the partials, eight weight rows,
+// the hidden row) are in flight together.
+template <typename T, int QPW>
 __global__ __launch_bounds__(256) void query_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K, SplitInfo si,
     const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
     const float *__restrict__ h_out, const float *__restrict__ lse_rows,
     const float *__restrict__ base_score, float *__restrict__ logprob) {
+    constexpr int kWavesPerQuery = 4 / QPW;
+    constexpr int kPartsPerLane = kMaxSplits / 64;
     const int B = B_dev ? *B_dev : rows;
-    const int n = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x * QPW + wave / kWavesPerQuery;
+    if (n >= N) return;                                  // wave-uniform; no barrier in this kernel
+    const int kwave = wave % kWavesPerQuery;             // this wave takes words kwave, kwave + 4/QPW, ...
     const int H = m.H, Hp = m.Hp;
-    const int r = row_of_query ? row_of_query[n] : n;
+    const int r_raw = row_of_query ? row_of_query[n] : n;
+    const bool r_ok = r_raw >= 0 && r_raw < B;
+    const int r = r_ok ? r_raw : 0;                      // a bad row is computed on row 0 and then dropped
     float *out = logprob + (size_t)n * K;
-    if (r < 0 || r >= B) {
-        if (threadIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_ROW);
-        for (int k = threadIdx.x; k < K; k += 256) out[k] = quiet_nan();
-        return;
-    }
-    // lse of row r: handed in, or assembled by every wave from the partials, lane l taking
-    // splits l, l+64, ...
-    float lse;
+    const int umine = batch_slot_of_lane(lane);
+    const bool writer = (lane & 7) == 0;
+
+    // lse of row r: handed in, or merged from the partials (lane l takes splits l, l+64, ...)
+    // once the first batch of dot products is done.
+    float2 parts[kPartsPerLane];
+    float lse = 0.f;
     if (lse_rows) {
         lse = lse_rows[r];
     } else {
         const int splits = si.fixed_splits > 0 ? si.fixed_splits : staged_plan(B, si.staged_wg_per_xcd).S;
-        lse = lse_from_partials(m.part + (size_t)r * kMaxSplits, splits, lane);
+#pragma unroll
+        for (int i = 0; i < kPartsPerLane; ++i) {
+            const int s = lane + 64 * i;
+            const float2 p = m.part[(size_t)r * kMaxSplits + (s < splits ? s : 0)];
+            parts[i] = (s < splits) ? p : make_float2(-INFINITY, 0.f);
+        }
     }
 
     const T *Ot = static_cast<const T *>(m.Ot);
     const float *hrow = h_out + (size_t)r * H;
     const bool vec_ok = (H % 4) == 0;
-    // A wave answers the queries k = wave, wave + 4, ...; kQueryBatch of them at a time so
-    // that their weight rows are all requested before the first is used.
-    for (int kb = wave; kb < K; kb += 4 * kQueryBatch) {
-        int q[kQueryBatch];
-        bool ok[kQueryBatch];
+    for (int kb = kwave; kb < K; kb += kWavesPerQuery * kQueryBatch) {
+        // this lane's word of the batch, its bias and base score
+        const int kmine = kb + kWavesPerQuery * umine;
+        const bool k_ok = kmine < K;
+        const int qmine = k_ok ? query_word[(size_t)n * K + kmine] : 0;
+        const bool q_ok = qmine >= 0 && qmine < m.V;
+        const int qsafe = q_ok ? qmine : 0;
+        const float bias_mine = m.bias[qsafe];
+        const float base_mine = (base_score && k_ok) ? base_score[(size_t)n * K + kmine] : 0.f;
+        int q[kQueryBatch];                              // wave-uniform word ids of the batch
 #pragma unroll
-        for (int u = 0; u < kQueryBatch; ++u) {
-            const int k = kb + 4 * u;
-            q[u] = (k < K) ? query_word[(size_t)n * K + k] : 0;
-            ok[u] = (k < K) && q[u] >= 0 && q[u] < m.V;
-        }
+        for (int u = 0; u < kQueryBatch; ++u) q[u] = __builtin_amdgcn_readlane(qsafe, lane_of_batch_slot(u));
+
         float acc[kQueryBatch];
 #pragma unroll
         for (int u = 0; u < kQueryBatch; ++u) acc[u] = 0.f;
@@ -65,28 +106,52 @@ __global__ __launch_bounds__(256) void query_kernel(
             load8_row(hrow, j0, H, vec_ok, 0.f, h8);
             float w8[kQueryBatch][8];
 #pragma unroll
-            for (int u = 0; u < kQueryBatch; ++u) load8_weights(Ot, (size_t)(ok[u] ? q[u] : 0) * Hp + j0, w8[u]);
+            for (int u = 0; u < kQueryBatch; ++u) load8_weights(Ot, (size_t)q[u] * Hp + j0, w8[u]);
 #pragma unroll
             for (int u = 0; u < kQueryBatch; ++u)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc[u] = fmaf(w8[u][i], h8[i], acc[u]);
         }
+        if (!lse_rows && kb == kwave) {                  // first batch: merge the partials now
+            float pm = -INFINITY, ps = 0.f;
 #pragma unroll
-        for (int u = 0; u < kQueryBatch; ++u) {
-            const int k = kb + 4 * u;
-            if (k >= K) continue;                        // wave-uniform
-            const float z = wave_sum(acc[u]);
-            if (lane == 0) {
-                if (ok[u]) {
-                    const float lp = (z + m.bias[q[u]]) - lse;
-                    out[k] = base_score ? lp - base_score[(size_t)n * K + k] : lp;
-                }
-                else { atomicOr(m.flag, RNNLM_FLAG_BAD_QUERY_WORD); out[k] = quiet_nan(); }
+            for (int i = 0; i < kPartsPerLane; ++i) lse2_merge(pm, ps, parts[i].x, parts[i].y);
+            const float mm = wave_max(pm);
+            const float ss = wave_sum(mm == -INFINITY ? 0.f : ps * fast_exp2(pm - mm));
+            lse = (mm + fast_log2(ss)) * kLn2;
+        }
+        const float z = wave_sum8(acc, lane);
+        if (writer && k_ok) {
+            if (r_ok && q_ok) {
+                float lp = (z + bias_mine) - lse;
+                if (base_score) lp -= base_mine;
+                out[kmine] = lp;
+            } else {
+                atomicOr(m.flag, r_ok ? RNNLM_FLAG_BAD_QUERY_WORD : RNNLM_FLAG_BAD_ROW);
+                out[kmine] = quiet_nan();
             }
         }
     }
 }
 
+}  // namespace
+
+namespace {
+template <typename T>
+void launch_query_typed(const ModelDev &m, int rows, const int *B_dev, int N, int K, SplitInfo splits,
+                               const int32_t *query_word, const int32_t *row_of_query, const float *h_out,
+                               const float *lse_rows, const float *base_score, float *logprob,
+                               hipStream_t stream) {
+    if (K <= kQueryBatch)
+        hipLaunchKernelGGL((query_kernel<T, 4>), dim3((N + 3) / 4), dim3(256), 0, stream, m, rows, B_dev, N, K,
+                           splits, query_word, row_of_query, h_out, lse_rows, base_score, logprob);
+    else if (K <= 2 * kQueryBatch)
+        hipLaunchKernelGGL((query_kernel<T, 2>), dim3((N + 1) / 2), dim3(256), 0, stream, m, rows, B_dev, N, K,
+                           splits, query_word, row_of_query, h_out, lse_rows, base_score, logprob);
+    else
+        hipLaunchKernelGGL((query_kernel<T, 1>), dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
+                           query_word, row_of_query, h_out, lse_rows, base_score, logprob);
+}
 }  // namespace
 
 hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, int K, SplitInfo splits,
@@ -95,11 +160,11 @@ hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, in
                         float *logprob, hipStream_t stream) {
     if (N <= 0 || K <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16)
-        hipLaunchKernelGGL(query_kernel<bf16_t>, dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
-                           query_word, row_of_query, h_out, lse_rows, base_score, logprob);
+        launch_query_typed<bf16_t>(m, rows, B_dev, N, K, splits, query_word, row_of_query, h_out, lse_rows,
+                                   base_score, logprob, stream);
     else
-        hipLaunchKernelGGL(query_kernel<float>, dim3(N), dim3(256), 0, stream, m, rows, B_dev, N, K, splits,
-                           query_word, row_of_query, h_out, lse_rows, base_score, logprob);
+        launch_query_typed<float>(m, rows, B_dev, N, K, splits, query_word, row_of_query, h_out, lse_rows,
+                                  base_score, logprob, stream);
     return hipGetLastError();
 }
 
