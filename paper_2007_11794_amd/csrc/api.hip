@@ -42,6 +42,7 @@ void free_dev(rnnlm_model *m) {
     (void)hipFree(const_cast<float *>(d.cvec2));
     (void)hipFree(const_cast<float *>(d.cvec2_fixed));
     (void)hipFree(d.d);
+    (void)hipFree(d.dfrag);
     (void)hipFree(d.part);
     (void)hipFree(d.flag);
     if (m->ev0) (void)hipEventDestroy(m->ev0);
@@ -119,6 +120,10 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     HIP_TRY(hipMalloc(&p, (size_t)max_Bp * kMaxSplits * sizeof(float2))); d.part = static_cast<float2 *>(p);
     HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
     HIP_TRY(hipMemset(d.d, 0, (size_t)max_Bp * Hp * es));
+    if (dtype == RNNLM_BF16) {
+        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.dfrag = p;
+        HIP_TRY(hipMemset(d.dfrag, 0, (size_t)max_Bp * Hp * es));
+    }
     HIP_TRY(hipMemset(d.part, 0, (size_t)max_Bp * kMaxSplits * sizeof(float2)));
     HIP_TRY(hipMemset(d.flag, 0, 4));
     HIP_TRY(hipEventCreate(&m->ev0));

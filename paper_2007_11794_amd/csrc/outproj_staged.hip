@@ -182,9 +182,11 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
                 loader.issue(Ot, cvec, (blk0 + i) * kStagedWords, lds0 + i * C::kStageBytes, cring0 + i * kCSlotBytes);
         bf16x8 dreg[KS];
         {
-            const bf16_t *drow = static_cast<const bf16_t *>(m.d) + (size_t)b * HP + 8 * g;
+            // fragment (row block, ks) of the fragment-ordered copy: 64 lanes x 16 bytes in a row
+            const bf16_t *dfr = static_cast<const bf16_t *>(m.dfrag) +
+                                ((size_t)(rg * (kStagedRows / 32) + wave) * KS * 64 + lane) * 8;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) dreg[ks] = *reinterpret_cast<const bf16x8 *>(drow + 16 * ks);
+            for (int ks = 0; ks < KS; ++ks) dreg[ks] = *reinterpret_cast<const bf16x8 *>(dfr + (size_t)ks * 512);
         }
         float mrun = FIXED ? m.m2_fixed : -INFINITY, srun = 0.f;
         // raw accumulators of the previous block, still to be exponentiated; -inf adds 2^-inf = 0

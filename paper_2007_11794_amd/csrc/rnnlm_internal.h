@@ -34,6 +34,10 @@ struct ModelDev {
     float m2_fixed;    // upper bound of every base-2 logit z*log2(e), valid because |h' - 0.5| <= 0.5
     // scratch
     void *d;           // [max_Bp][Hp]  h' - 0.5 in the weights' type
+    // bf16 models: the same block once more in the order the staged output projection reads
+    // it, [max_Bp / 32][Hp / 16][64 lanes][8]: lane 32 g + c of fragment (rb, ks) holds row
+    // 32 rb + c, units 16 ks + 8 g .. + 7, so one MFMA operand of a wave is 1 KB contiguous.
+    void *dfrag;
     float2 *part;      // [max_Bp][kMaxSplits]  (max, sum) partials of the base-2 log-sum-exp
     int *flag;         // sticky rnnlm_device_flag bits
 };
