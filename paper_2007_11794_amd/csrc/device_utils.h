@@ -113,6 +113,14 @@ __device__ __forceinline__ void lds_dma_16(const void *sbase, uint32_t voff, uin
                  : "memory");
 }
 
+// The same with a full 64-bit address per lane (rows gathered from anywhere in a buffer).
+__device__ __forceinline__ void lds_dma_16_ptr(const void *lane_ptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(lane_ptr)
+                 : "memory");
+}
+
 __device__ __forceinline__ uint32_t lds_address(const void *p) {
     return (uint32_t)reinterpret_cast<uintptr_t>(p);         // LDS offsets are the low 32 bits
 }

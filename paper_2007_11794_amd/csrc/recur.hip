@@ -130,6 +130,161 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
     }
 }
 
+// ----------------------------------------------------------------------------- bf16 / MFMA, LDS-tiled
+// The form used when the rows of h_in can be fetched in 16-byte pieces (H a multiple of 4,
+// 16-byte aligned buffer).  A workgroup of 2 x 2 waves computes 64 units x 64 rows; a wave
+// owns a 32 x 32 block over the whole reduction length (no cross-wave sum).  The reduction
+// length is cut in chunks of 64: 64 rows x 128 bytes of W and 64 rows x 256 bytes of h_in
+// (kept as two 128-byte half rows), in a ring of four LDS stages filled by direct global->LDS
+// loads, each of which covers whole 128-byte lines: the register-direct kernel above touches
+// 32 different lines per load instruction and re-reads every operand 2 x more often from L2.
+// LDS rows are 128 bytes; chunk c of row r sits at c ^ ((r >> 1) & 7) (as in the tiled
+// output projection).  h_in stays fp32 in LDS and is centred and split into hi + lo bf16 in
+// registers right before the two MFMAs of a k-step.
+constexpr int kRtTile = 64;                           // units and rows per workgroup
+constexpr int kRtWBytes = kRtTile * 128;              // W part of a stage
+constexpr int kRtStageBytes = kRtWBytes + 2 * kRtTile * 128;
+constexpr int kRtLoadsPerChunk = 6;                   // direct-to-LDS loads a thread issues per chunk
+// Stages of the ring (template parameter NS): a grid that gives a compute unit one workgroup
+// at most hides load latency by keeping three chunks in flight (4 stages, 96 KB); a larger
+// grid does better with 2 stages (48 KB), three workgroups per compute unit.
+
+template <int NS>
+__global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
+    float *__restrict__ h_out) {
+    const int B = B_dev ? *B_dev : rows;
+    const int b0 = blockIdx.y * kRtTile;
+    if (b0 >= B) return;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    __shared__ int srcs[kRtTile];
+    const int j0 = blockIdx.x * kRtTile;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
+    const int wj = wave & 1, wb = wave >> 1;
+    const int H = m.H, Hp = m.Hp;
+    const bf16_t *W = static_cast<const bf16_t *>(m.W);
+    const bf16_t *U = static_cast<const bf16_t *>(m.U);
+
+    if (tid < kRtTile) {                               // rows beyond B repeat the last one; dropped later
+        const int rv = min(b0 + tid, B - 1);
+        srcs[tid] = row_src ? row_src[rv] : rv;
+    }
+    __syncthreads();
+
+    // loader: thread fills the physical 16-byte pieces f = q * 256 + tid of an operand tile
+    // (row f / 8, position f % 8) with the logical piece c = position ^ swizzle(row)
+    uint32_t woff[2];
+    const float *hrow[2];
+    int hc[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int f = q * 256 + tid, r = f >> 3, c = (f & 7) ^ ((r >> 1) & 7);
+        woff[q] = (uint32_t)(r * Hp * 2 + c * 16);
+        hrow[q] = h_in + (size_t)srcs[r] * H;
+        hc[q] = 4 * c;
+    }
+    const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t lds0 = lds_address(lds);
+    auto issue = [&](int chunk, int stage) {
+        const int k0 = chunk * 64;
+        const uint32_t base = lds0 + stage * kRtStageBytes + wave_s * 1024;
+        const bf16_t *wsrc = W + (size_t)j0 * Hp + k0;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) lds_dma_16(wsrc, woff[q], base + q * 4096);
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                // pieces past the end of the row meet zero weights: fetch the row's first piece
+                const int k = k0 + 32 * half + hc[q];
+                lds_dma_16_ptr(hrow[q] + (k + 4 <= H ? k : 0), base + kRtWBytes + half * (kRtTile * 128) + q * 4096);
+            }
+    };
+
+    const int b = b0 + 32 * wb + col;
+    const bool row_ok = b < B;
+    const int src = srcs[32 * wb + col];
+    const int w = prev_word[src];
+    const bool w_ok = (w >= 0 && w < m.V);
+    const int jw = j0 + 32 * wj + 4 * g;                // this lane finishes units jw + 8 q .. + 3, q < 4
+    const int nk = Hp / 64;
+#pragma unroll
+    for (int c = 0; c < NS - 1; ++c)
+        if (c < nk) issue(c, c);
+    uint2 u4[4];
+    f32x4 rs[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        u4[q] = *reinterpret_cast<const uint2 *>(U + (size_t)(w_ok ? w : 0) * Hp + jw + 8 * q);
+        rs[q] = *reinterpret_cast<const f32x4 *>(m.half_rowsum_W + jw + 8 * q);
+    }
+
+    // LDS offsets of this lane's operands at k-step ks of a chunk
+    int aoff[4], boff[4];
+    {
+        const int ra = 32 * wj + col, rb = 32 * wb + col;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            aoff[ks] = ra * 128 + (((2 * ks + g) ^ ((ra >> 1) & 7)) * 16);
+            // h: k = 16 ks + 8 g .. + 7 -> half row ks / 2, pieces 4 (ks % 2) + 2 g and the next
+            boff[ks] = kRtWBytes + (ks >> 1) * (kRtTile * 128) + rb * 128;
+        }
+    }
+    const int bsw = ((32 * wb + col) >> 1) & 7;
+
+    f32x16 acc = {0};
+    for (int chunk = 0; chunk < nk; ++chunk) {
+        const int stage = chunk % NS;
+        // my loads of this chunk have landed once only those of the (at most two) later chunks
+        // already requested are outstanding
+        const int later = min(NS - 2, nk - 1 - chunk);
+        if (later >= 2) wait_vmcnt<2 * kRtLoadsPerChunk>();
+        else if (later == 1) wait_vmcnt<kRtLoadsPerChunk>();
+        else wait_vmcnt<0>();
+        __syncthreads();                                // everybody's; the stage of chunk - 1 is free
+        if (chunk + NS - 1 < nk) issue(chunk + NS - 1, (chunk + NS - 1) % NS);
+        const char *st = lds + stage * kRtStageBytes;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + aoff[ks]);
+            const int c0 = 4 * (ks & 1) + 2 * g;
+            const f32x4 h0 = *reinterpret_cast<const f32x4 *>(st + boff[ks] + ((c0 ^ bsw) * 16));
+            const f32x4 h1 = *reinterpret_cast<const f32x4 *>(st + boff[ks] + (((c0 + 1) ^ bsw) * 16));
+            const float h8[8] = {h0[0], h0[1], h0[2], h0[3], h1[0], h1[1], h1[2], h1[3]};
+            u32x4 hi, lo;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d0 = h8[2 * i] - 0.5f, d1 = h8[2 * i + 1] - 0.5f;
+                hi[i] = pack_bf16x2(d0, d1);
+                lo[i] = pack_bf16x2(d0 - __uint_as_float(hi[i] << 16), d1 - __uint_as_float(hi[i] & 0xFFFF0000u));
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, hi), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, lo), acc, 0, 0, 0);
+        }
+    }
+    if (!row_ok) return;
+    if (!w_ok && g == 0 && wj == 0 && blockIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
+    const int bo = row_dst ? row_dst[b] : b;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int je = jw + 8 * q;
+        const float u[4] = {__uint_as_float(u4[q].x << 16), __uint_as_float(u4[q].x & 0xFFFF0000u),
+                            __uint_as_float(u4[q].y << 16), __uint_as_float(u4[q].y & 0xFFFF0000u)};
+        float hp[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hp[i] = w_ok ? sigmoid_f32(acc[4 * q + i] + rs[q][i] + u[i]) : quiet_nan();
+        uint2 dpk;                                      // padded units come out as sigmoid(0) - 1/2 = 0
+        dpk.x = pack_bf16x2(hp[0] - 0.5f, hp[1] - 0.5f);
+        dpk.y = pack_bf16x2(hp[2] - 0.5f, hp[3] - 0.5f);
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
+        const size_t frag = (size_t)(b >> 5) * (Hp >> 4) + (je >> 4);
+        const size_t at = (frag * 64 + ((je >> 3) & 1) * 32 + (b & 31)) * 8 + (je & 7);
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dpk;
+        if (je + 4 <= H) *reinterpret_cast<f32x4 *>(h_out + (size_t)bo * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
+    }
+}
+
 // ----------------------------------------------------------------------------- fp32 / MFMA
 // Same shape as the bf16 kernel (32 x 32 block per workgroup, reduction length split over the
 // four waves, all loads of a wave in flight together), with the full-precision fp32 matrix
@@ -231,7 +386,23 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
                         const int32_t *row_dst, const int32_t *prev_word, const float *h_in,
                         float *h_out, hipStream_t stream) {
     if (rows <= 0) return hipSuccess;
-    if (m.dtype == RNNLM_BF16) {
+    if (m.dtype == RNNLM_BF16 && m.H % 4 == 0 && (reinterpret_cast<uintptr_t>(h_in) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(h_out) & 15) == 0) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kRtStageBytes);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        dim3 grid(m.Hp / kRtTile, (rows + kRtTile - 1) / kRtTile);
+        if (grid.x * grid.y <= 256)
+            hipLaunchKernelGGL(recur_bf16_tiled_kernel<4>, grid, dim3(256), 4 * kRtStageBytes, stream, m, rows,
+                               B_dev, row_src, row_dst, prev_word, h_in, h_out);
+        else
+            hipLaunchKernelGGL(recur_bf16_tiled_kernel<2>, grid, dim3(256), 2 * kRtStageBytes, stream, m, rows,
+                               B_dev, row_src, row_dst, prev_word, h_in, h_out);
+    } else if (m.dtype == RNNLM_BF16) {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);
         hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
                            row_dst, prev_word, h_in, h_out);
