@@ -155,11 +155,15 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
     float *__restrict__ h_out) {
     const int B = B_dev ? *B_dev : rows;
-    const int b0 = blockIdx.y * kRtTile;
+    // Workgroup id modulo 8 is the XCD (L2 domain).  Row block rb runs on XCD rb % 8 with all
+    // its unit blocks, so h_in (the larger operand) is fetched into one L2 only.
+    const int JB = m.Hp / kRtTile;
+    const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    const int b0 = (xcd + kXcds * (local / JB)) * kRtTile;
     if (b0 >= B) return;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     __shared__ int srcs[kRtTile];
-    const int j0 = blockIdx.x * kRtTile;
+    const int j0 = (local % JB) * kRtTile;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int wj = wave & 1, wb = wave >> 1;
     const int H = m.H, Hp = m.Hp;
@@ -264,7 +268,7 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
         }
     }
     if (!row_ok) return;
-    if (!w_ok && g == 0 && wj == 0 && blockIdx.x == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
+    if (!w_ok && g == 0 && wj == 0 && j0 == 0) atomicOr(m.flag, RNNLM_FLAG_BAD_PREV_WORD);
     const int bo = row_dst ? row_dst[b] : b;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -395,8 +399,9 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        dim3 grid(m.Hp / kRtTile, (rows + kRtTile - 1) / kRtTile);
-        if (grid.x * grid.y <= 256)
+        const int row_blocks = (rows + kRtTile - 1) / kRtTile;
+        dim3 grid(kXcds * ((row_blocks + kXcds - 1) / kXcds) * (m.Hp / kRtTile));
+        if (row_blocks * (m.Hp / kRtTile) <= 256)
             hipLaunchKernelGGL(recur_bf16_tiled_kernel<4>, grid, dim3(256), 4 * kRtStageBytes, stream, m, rows,
                                B_dev, row_src, row_dst, prev_word, h_in, h_out);
         else
