@@ -53,6 +53,18 @@ def _load():
         lib.oracle_step_cached.restype = I
         lib.oracle_pack_ids.argtypes = [P, P, I, P]
         lib.oracle_pack_ids.restype = None
+        lib.oracle_index_new.argtypes = [I, I]
+        lib.oracle_index_new.restype = P
+        lib.oracle_index_free.argtypes = [P]
+        lib.oracle_index_free.restype = None
+        lib.oracle_index_reset.argtypes = [P]
+        lib.oracle_index_reset.restype = None
+        lib.oracle_index_stats.argtypes = [P, P]
+        lib.oracle_index_stats.restype = None
+        lib.oracle_index_intern.argtypes = [P, I, P, P, P]
+        lib.oracle_index_intern.restype = None
+        lib.oracle_index_fetch.argtypes = [P, I, P, P, P]
+        lib.oracle_index_fetch.restype = I
         _lib = lib
     return _lib
 
@@ -186,3 +198,46 @@ def pack_ids(ctx, small_lm) -> np.ndarray:
     out = np.zeros(ctx.shape[0], dtype=np.uint64)
     _load().oracle_pack_ids(_ptr(ctx), _ptr(small_lm), ctx.shape[0], _ptr(out))
     return out
+
+
+class IndexTable:
+    """IndexTable and its inverse (Section 3.2; Table 1 steps 5, 7-12): contexts (word, hidden
+    vector) stored once, found again by content (all bits), numbered in order of storage."""
+    NOT_STORED = 0xFFFFFFFF
+
+    def __init__(self, H: int, capacity: int):
+        self._h = _load().oracle_index_new(int(H), int(capacity))
+        if not self._h:
+            raise MemoryError("oracle_index_new failed")
+        self.H, self.capacity = int(H), int(capacity)
+
+    def reset(self) -> None:
+        _load().oracle_index_reset(self._h)
+
+    def stats(self) -> dict:
+        out = np.zeros(4, dtype=np.int64)
+        _load().oracle_index_stats(self._h, _ptr(out))
+        return dict(zip(("entries", "lookups", "found", "unstored"), (int(x) for x in out)))
+
+    def intern(self, word, h) -> np.ndarray:
+        word = _c(word, np.int32)
+        h = _c(h, np.float32)
+        N = word.shape[0]
+        assert h.shape == (N, self.H)
+        out = np.zeros(N, dtype=np.uint32)
+        _load().oracle_index_intern(self._h, N, _ptr(word), _ptr(h), _ptr(out))
+        return out
+
+    def fetch(self, index):
+        index = _c(index, np.uint32)
+        N = index.shape[0]
+        word = np.zeros(N, dtype=np.int32)
+        h = np.zeros((N, self.H), dtype=np.float32)
+        if _load().oracle_index_fetch(self._h, N, _ptr(index), _ptr(word), _ptr(h)) != 0:
+            raise ValueError("oracle_index_fetch: index not held")
+        return word, h
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.oracle_index_free(self._h)
+            self._h = None

@@ -22,6 +22,8 @@
  *   cache      the same lookup kept between steps (Table 1 as a whole; Sections 4.2, 5.3),
  *              the score difference handed back after it, and the packed 8-byte index of
  *              Section 3.2: oracle_step_cached, oracle_pack_ids further down.
+ *   index      IndexTable and its inverse (Section 3.2, Table 1 steps 5, 7-12): contexts stored
+ *              by value, found again by content: oracle_index_* further down.
  *
  * Everything is summed left to right in double.  Weights arrive as float (bf16 models
  * pass values that are exact in float) and are widened exactly.  h' is never rounded
@@ -303,6 +305,98 @@ int oracle_step_cached(oracle_cache *c, int V, int H, int N, int K,
 void oracle_pack_ids(const uint32_t *ctx, const uint32_t *small_lm, int N, uint64_t *ids)
 {
     for (int n = 0; n < N; ++n) ids[n] = ((uint64_t)ctx[n] << 32) | (uint64_t)small_lm[n];
+}
+
+/* ------------------------------------------------------------------------------------
+ * IndexTable and its inverse (Section 3.2; Table 1 steps 5 and 7-12): a context -- the word it
+ * ends in and its hidden vector (Section 4.1) -- is stored once and stands for its index from
+ * then on.  Two contexts are the same when the word and every bit of the hidden vector agree.
+ * Indices are handed out in the order of first storage (step 10).  The table holds at most
+ * `capacity` contexts; one that does not fit gets the index 0xFFFFFFFF and is not stored.
+ */
+#include <string.h>
+
+typedef struct oracle_index {
+    int H, capacity, count;
+    int32_t *word;      /* [capacity] */
+    float *h;           /* [capacity][H] */
+    long long lookups, found, unstored;    /* running totals over the distinct contexts of each call */
+} oracle_index;
+
+oracle_index *oracle_index_new(int H, int capacity)
+{
+    if (H <= 0 || capacity < 0) return NULL;
+    oracle_index *t = (oracle_index *)calloc(1, sizeof(oracle_index));
+    if (!t) return NULL;
+    t->H = H;
+    t->capacity = capacity;
+    size_t cap = capacity > 0 ? (size_t)capacity : 1;
+    t->word = (int32_t *)malloc(cap * sizeof(int32_t));
+    t->h = (float *)malloc(cap * (size_t)H * sizeof(float));
+    if (!t->word || !t->h) { free(t->word); free(t->h); free(t); return NULL; }
+    return t;
+}
+
+void oracle_index_free(oracle_index *t)
+{
+    if (!t) return;
+    free(t->word); free(t->h); free(t);
+}
+
+void oracle_index_reset(oracle_index *t)
+{
+    t->count = 0;
+    t->lookups = t->found = t->unstored = 0;
+}
+
+void oracle_index_stats(const oracle_index *t, long long out[4])
+{
+    out[0] = t->count; out[1] = t->lookups; out[2] = t->found; out[3] = t->unstored;
+}
+
+static int same_context(int H, int32_t w1, const float *h1, int32_t w2, const float *h2)
+{
+    return w1 == w2 && memcmp(h1, h2, (size_t)H * sizeof(float)) == 0;
+}
+
+/* IndexTable^-1 for N contexts given by value, in order: the index of a context already in the
+ * table, else the next free index (and the context is stored).  A context that occurs several
+ * times in one call counts once in the totals. */
+void oracle_index_intern(oracle_index *t, int N, const int32_t *word, const float *h, uint32_t *index)
+{
+    int H = t->H;
+    for (int n = 0; n < N; ++n) {
+        const float *hn = h + (size_t)n * H;
+        int seen_in_call = 0;
+        for (int p = 0; p < n && !seen_in_call; ++p)
+            if (same_context(H, word[n], hn, word[p], h + (size_t)p * H)) { index[n] = index[p]; seen_in_call = 1; }
+        if (seen_in_call) continue;
+        ++t->lookups;
+        int e = -1;
+        for (int i = 0; i < t->count; ++i)
+            if (same_context(H, word[n], hn, t->word[i], t->h + (size_t)i * H)) { e = i; break; }
+        if (e >= 0) {
+            ++t->found;
+        } else if (t->count < t->capacity) {
+            e = t->count++;
+            t->word[e] = word[n];
+            memcpy(t->h + (size_t)e * H, hn, (size_t)H * sizeof(float));
+        } else {
+            ++t->unstored;
+        }
+        index[n] = e >= 0 ? (uint32_t)e : 0xFFFFFFFFu;
+    }
+}
+
+/* IndexTable[c]: the stored context of every index.  Returns -1 on an index that is not held. */
+int oracle_index_fetch(const oracle_index *t, int N, const uint32_t *index, int32_t *word, float *h)
+{
+    for (int n = 0; n < N; ++n) {
+        if (index[n] >= (uint32_t)t->count) return -1;
+        word[n] = t->word[index[n]];
+        memcpy(h + (size_t)n * t->H, t->h + (size_t)index[n] * t->H, (size_t)t->H * sizeof(float));
+    }
+    return 0;
 }
 
 int oracle_max_threads(void)
