@@ -12,11 +12,13 @@
  *   - Plain C ABI.  Every function returns an rnnlm_status (0 = OK, < 0 = error) except
  *     where stated; nothing throws or aborts.
  *   - rnnlm_load takes HOST pointers and copies; the caller keeps its buffers.
- *   - rnnlm_dedup / rnnlm_step / rnnlm_step_dedup / rnnlm_step_cached / rnnlm_pack_ids take
+ *   - rnnlm_dedup / rnnlm_step / rnnlm_step_dedup / rnnlm_step_cached / rnnlm_pack_ids /
+ *     rnnlm_index_intern / rnnlm_index_fetch take
  *     DEVICE pointers owned by the caller and are asynchronous on `hip_stream` (a
  *     hipStream_t passed as void*; NULL = the default stream).  No call here synchronises,
  *     allocates or frees device memory except rnnlm_load, rnnlm_free, rnnlm_last_error,
- *     rnnlm_cache_create, rnnlm_cache_free and rnnlm_cache_stats.
+ *     rnnlm_cache_create, rnnlm_cache_free, rnnlm_cache_stats, rnnlm_index_create,
+ *     rnnlm_index_free and rnnlm_index_stats.
  *   - float / int32 / uint64 arrays are dense, row-major, naturally aligned; `h_in` and
  *     `h_out` rows must start on 16-byte boundaries when H is a multiple of 4 (any
  *     allocator's base alignment gives this).
@@ -211,6 +213,58 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache_or_null, int 
                       int32_t *rep, int32_t *inverse, int32_t *n_unique,
                       float *h_out, float *score, int32_t *step_stats_or_null,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * ---- IndexTable and its inverse on the device (Section 3.2; Table 1 steps 5 and 7-12) -------
+ *
+ * A context -- the word it ends in and its hidden vector (Section 4.1) -- is stored once and
+ * stands for a 4-byte index from then on (Table 3), so a search that keeps only indices needs
+ * no host-side id management: rnnlm_index_intern turns contexts given by value into indices
+ * (the same context, compared word for word and bit for bit, always gets the same index; new
+ * ones are numbered in order of first appearance), rnnlm_index_fetch gives the stored contexts
+ * back.  Packed with the small-LM index by rnnlm_pack_ids, the indices are the history ids of
+ * rnnlm_step_dedup / rnnlm_step_cached.
+ */
+typedef struct rnnlm_index_table rnnlm_index_table;   /* opaque, owned by the library */
+
+enum {
+    RNNLM_INDEX_NOT_STORED = 0xFFFFFFFFu,  /* the table was full: the context was not stored */
+    RNNLM_INDEX_COLLISION  = 0xFFFFFFFEu   /* contents differ although the 64-bit hashes agree */
+};
+
+/* Create an empty table for hidden vectors of H floats, up to `capacity` contexts, calls of up
+ * to max_N contexts.  Device memory ~ capacity * (4 H + 20) + 40 max_N bytes.  Synchronous. */
+int rnnlm_index_create(int H, int capacity, int max_N, rnnlm_index_table **out);
+
+/* Release a table.  NULL is a no-op.  Synchronises the device. */
+int rnnlm_index_free(rnnlm_index_table *table);
+
+/* Forget every context and zero the counters.  Asynchronous on `hip_stream`. */
+int rnnlm_index_reset(rnnlm_index_table *table, void *hip_stream);
+
+/*
+ * Indices of N contexts given by value (inverse IndexTable, then IndexTable for the new ones).
+ *   word   dev i32[N]     the word each context ends in
+ *   h      dev f32[N][H]  its hidden vector
+ *   index  dev u32[N]     out: the index; RNNLM_INDEX_NOT_STORED when the table was full;
+ *                         RNNLM_INDEX_COLLISION when a different context with the same
+ *                         64-bit hash is held (probability about 2^-64 per pair of contexts;
+ *                         counted in rnnlm_index_stats)
+ * Asynchronous on `hip_stream`; calls on one table must be ordered on one stream.
+ */
+int rnnlm_index_intern(rnnlm_index_table *table, int N, const int32_t *word, const float *h,
+                       uint32_t *index, void *hip_stream);
+
+/* The stored context of each index (IndexTable[c], Table 1 step 5): word dev i32[N] and
+ * h dev f32[N][H], out.  An index the table does not hold gives word -1 and a NaN vector and is
+ * counted in rnnlm_index_stats.  Asynchronous on `hip_stream`. */
+int rnnlm_index_fetch(const rnnlm_index_table *table, int N, const uint32_t *index, int32_t *word,
+                      float *h, void *hip_stream);
+
+/* Wait for `hip_stream`, then write to the HOST array out[6]: contexts held, and running
+ * totals: distinct contexts looked up per call, found, not stored because full, hash
+ * collisions, bad indices passed to rnnlm_index_fetch. */
+int rnnlm_index_stats(rnnlm_index_table *table, void *hip_stream, int64_t out[6]);
 
 /*
  * The packed 8-byte index of Section 3.2: ids[n] = ctx_idx[n] << 32 | small_lm_idx[n]

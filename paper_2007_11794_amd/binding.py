@@ -24,7 +24,9 @@ _lib = None
 EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rnnlm_last_error",
            "rnnlm_dedup_workspace_bytes", "rnnlm_dedup", "rnnlm_step", "rnnlm_step_dedup",
            "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
-           "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids"]
+           "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
+           "rnnlm_index_free", "rnnlm_index_reset", "rnnlm_index_intern", "rnnlm_index_fetch",
+           "rnnlm_index_stats"]
 
 
 class RnnlmError(RuntimeError):
@@ -78,6 +80,18 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_step_cached.restype = I
         L.rnnlm_pack_ids.argtypes = [P, P, I, P, P]
         L.rnnlm_pack_ids.restype = I
+        L.rnnlm_index_create.argtypes = [I, I, I, ctypes.POINTER(P)]
+        L.rnnlm_index_create.restype = I
+        L.rnnlm_index_free.argtypes = [P]
+        L.rnnlm_index_free.restype = I
+        L.rnnlm_index_reset.argtypes = [P, P]
+        L.rnnlm_index_reset.restype = I
+        L.rnnlm_index_intern.argtypes = [P, I, P, P, P, P]
+        L.rnnlm_index_intern.restype = I
+        L.rnnlm_index_fetch.argtypes = [P, I, P, P, P, P]
+        L.rnnlm_index_fetch.restype = I
+        L.rnnlm_index_stats.argtypes = [P, P, ctypes.POINTER(ctypes.c_int64)]
+        L.rnnlm_index_stats.restype = I
         _lib = L
     return _lib
 
@@ -297,3 +311,65 @@ def rnnlm_pack_ids(ctx_idx, small_lm_idx, ids, stream=None):
         raise TypeError("shape mismatch")
     _check(lib().rnnlm_pack_ids(_dev(ctx_idx, torch.int32, "ctx_idx"), _dev(small_lm_idx, torch.int32, "small_lm_idx"),
                                 N, _dev(ids, torch.int64, "ids"), _stream(stream)), "rnnlm_pack_ids")
+
+
+INDEX_NOT_STORED, INDEX_COLLISION = 0xFFFFFFFF, 0xFFFFFFFE
+
+
+class RnnlmIndexTable:
+    """Handle returned by rnnlm_index_create."""
+
+    def __init__(self, handle: int, H: int, capacity: int, max_N: int):
+        self._h = handle
+        self.H, self.capacity, self.max_N = H, capacity, max_N
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("index table already freed")
+        return self._h
+
+    def reset(self, stream=None):
+        _check(lib().rnnlm_index_reset(self.handle, _stream(stream)), "rnnlm_index_reset")
+
+    def stats(self, stream=None) -> dict:
+        out = (ctypes.c_int64 * 6)()
+        _check(lib().rnnlm_index_stats(self.handle, _stream(stream), out), "rnnlm_index_stats")
+        return dict(zip(("entries", "lookups", "found", "unstored", "collisions", "bad_fetch"),
+                        (int(x) for x in out)))
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, None
+            _check(lib().rnnlm_index_free(h), "rnnlm_index_free")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def rnnlm_index_create(H: int, capacity: int, max_N: int) -> RnnlmIndexTable:
+    out = ctypes.c_void_p()
+    _check(lib().rnnlm_index_create(int(H), int(capacity), int(max_N), ctypes.byref(out)), "rnnlm_index_create")
+    return RnnlmIndexTable(out.value, int(H), int(capacity), int(max_N))
+
+
+def rnnlm_index_intern(table: RnnlmIndexTable, word, h, index, stream=None):
+    """word int32 [N], h float32 [N,H], index int32 [N] out (u32 bit patterns); device tensors."""
+    import torch
+    N = int(word.shape[0])
+    if h.shape != (N, table.H) or index.shape != (N,):
+        raise TypeError("shape mismatch")
+    _check(lib().rnnlm_index_intern(table.handle, N, _dev(word, torch.int32, "word"), _dev(h, torch.float32, "h"),
+                                    _dev(index, torch.int32, "index"), _stream(stream)), "rnnlm_index_intern")
+
+
+def rnnlm_index_fetch(table: RnnlmIndexTable, index, word, h, stream=None):
+    import torch
+    N = int(index.shape[0])
+    if h.shape != (N, table.H) or word.shape != (N,):
+        raise TypeError("shape mismatch")
+    _check(lib().rnnlm_index_fetch(table.handle, N, _dev(index, torch.int32, "index"), _dev(word, torch.int32, "word"),
+                                   _dev(h, torch.float32, "h"), _stream(stream)), "rnnlm_index_fetch")

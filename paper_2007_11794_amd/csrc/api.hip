@@ -300,7 +300,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
         return RNNLM_OK;
     }
     const CacheDev &c = cache->dev;
-    if (launch_cache_lookup(c, history_ids, rep, n_unique, step_stats, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_cache_lookup(c, N, history_ids, rep, n_unique, step_stats, s) != hipSuccess) return RNNLM_EDEVICE;
     if (N == 0) return RNNLM_OK;
     // Only the histories the cache does not hold are computed: *c.n_miss rows, row r taken
     // from raw query c.miss_src[r], its hidden vector written to row c.miss_dst[r] of h_out.
@@ -343,6 +343,7 @@ int rnnlm_cache_create(const rnnlm_model *model, int capacity, rnnlm_cache **out
     HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_dst = static_cast<int32_t *>(p);
     HIP_TRY(hipMalloc(&p, nb * 4)); d.lse_rows = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, 4)); d.n_miss = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, (nb / 1024 + 2) * 4)); d.block_total = static_cast<int *>(p);
     HIP_TRY(hipMemset(d.n_miss, 0, 4));
     HIP_TRY(launch_cache_reset(d, nullptr));
     HIP_TRY(hipDeviceSynchronize());
@@ -360,7 +361,7 @@ int rnnlm_cache_free(rnnlm_cache *cache) {
     CacheDev &d = cache->dev;
     (void)hipFree(d.table); (void)hipFree(d.store_h); (void)hipFree(d.store_lse); (void)hipFree(d.n_entries);
     (void)hipFree(d.totals); (void)hipFree(d.entry_of); (void)hipFree(d.miss_of); (void)hipFree(d.miss_src);
-    (void)hipFree(d.miss_dst); (void)hipFree(d.lse_rows); (void)hipFree(d.n_miss);
+    (void)hipFree(d.miss_dst); (void)hipFree(d.lse_rows); (void)hipFree(d.n_miss); (void)hipFree(d.block_total);
     delete cache;
     return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
 }
@@ -383,6 +384,112 @@ int rnnlm_cache_stats(rnnlm_cache *cache, void *hip_stream, int64_t out[5]) {
     if (hipStreamSynchronize(s) != hipSuccess) return RNNLM_EDEVICE;
     out[0] = entries;
     for (int i = 0; i < 4; ++i) out[1 + i] = totals[i];
+    return RNNLM_OK;
+}
+
+int rnnlm_index_create(int H, int capacity, int max_N, rnnlm_index_table **out) {
+    if (!out) return RNNLM_EINVAL;
+    *out = nullptr;
+    if (H <= 0 || capacity < 0 || max_N <= 0) return RNNLM_EINVAL;
+    if (capacity > (1 << 26) || max_N > (1 << 24) || H > (1 << 16)) return RNNLM_ERANGE;
+    rnnlm_index_table *t = new (std::nothrow) rnnlm_index_table();
+    if (!t) return RNNLM_ENOMEM;
+    memset(t, 0, sizeof(*t));
+    int status = RNNLM_OK;
+    IndexDev &d = t->dev;
+    CacheDev &c = d.c;
+    c.capacity = capacity;
+    c.table_size = 64;
+    while (c.table_size < 2 * capacity) c.table_size <<= 1;
+    c.H = H;
+    t->max_N = max_N;
+    const size_t nb = (size_t)max_N, cap1 = capacity > 0 ? (size_t)capacity : 1;
+    void *p;
+    HIP_TRY(hipMalloc(&p, (size_t)c.table_size * sizeof(CacheCell))); c.table = static_cast<CacheCell *>(p);
+    HIP_TRY(hipMalloc(&p, cap1 * H * 4)); c.store_h = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, cap1 * 4)); d.store_word = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); c.n_entries = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, 4 * sizeof(long long))); c.totals = static_cast<long long *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); c.entry_of = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); c.miss_of = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); c.miss_src = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); c.miss_dst = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); c.n_miss = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, (nb / 1024 + 2) * 4)); c.block_total = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 8)); d.keys = static_cast<uint64_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.rep = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.inverse = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); d.n_unique = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, dedup_workspace_bytes(max_N))); d.dedup_ws = p;
+    HIP_TRY(hipMalloc(&p, 2 * sizeof(long long))); d.errors = static_cast<long long *>(p);
+    HIP_TRY(hipMemset(c.n_miss, 0, 4));
+    HIP_TRY(launch_index_reset(d, nullptr));
+    HIP_TRY(hipDeviceSynchronize());
+    *out = t;
+    return RNNLM_OK;
+fail:
+    rnnlm_index_free(t);
+    (void)hipGetLastError();
+    return status;
+}
+
+int rnnlm_index_free(rnnlm_index_table *table) {
+    if (!table) return RNNLM_OK;
+    hipError_t e = hipDeviceSynchronize();
+    IndexDev &d = table->dev;
+    CacheDev &c = d.c;
+    (void)hipFree(c.table); (void)hipFree(c.store_h); (void)hipFree(d.store_word); (void)hipFree(c.n_entries);
+    (void)hipFree(c.totals); (void)hipFree(c.entry_of); (void)hipFree(c.miss_of); (void)hipFree(c.miss_src);
+    (void)hipFree(c.miss_dst); (void)hipFree(c.n_miss); (void)hipFree(c.block_total); (void)hipFree(d.keys); (void)hipFree(d.rep);
+    (void)hipFree(d.inverse); (void)hipFree(d.n_unique); (void)hipFree(d.dedup_ws); (void)hipFree(d.errors);
+    delete table;
+    return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
+}
+
+int rnnlm_index_reset(rnnlm_index_table *table, void *hip_stream) {
+    if (!table) return RNNLM_EINVAL;
+    return launch_index_reset(table->dev, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? RNNLM_OK
+                                                                                               : RNNLM_EDEVICE;
+}
+
+int rnnlm_index_intern(rnnlm_index_table *table, int N, const int32_t *word, const float *h, uint32_t *index,
+                       void *hip_stream) {
+    if (!table || N < 0) return RNNLM_EINVAL;
+    if (N > table->max_N) return RNNLM_ERANGE;
+    if (N > 0 && (!word || !h || !index)) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const IndexDev &d = table->dev;
+    if (launch_context_hash(word, h, N, d.c.H, d.keys, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_dedup(d.keys, N, d.rep, d.inverse, d.n_unique, d.dedup_ws, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_cache_lookup(d.c, N, d.keys, d.rep, d.n_unique, nullptr, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_index_commit(d, N, word, h, index, s) != hipSuccess) return RNNLM_EDEVICE;
+    return RNNLM_OK;
+}
+
+int rnnlm_index_fetch(const rnnlm_index_table *table, int N, const uint32_t *index, int32_t *word, float *h,
+                      void *hip_stream) {
+    if (!table || N < 0) return RNNLM_EINVAL;
+    if (N > 0 && (!index || !word || !h)) return RNNLM_EINVAL;
+    return launch_index_fetch(table->dev, N, index, word, h, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? RNNLM_OK
+               : RNNLM_EDEVICE;
+}
+
+int rnnlm_index_stats(rnnlm_index_table *table, void *hip_stream, int64_t out[6]) {
+    if (!table || !out) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int entries = 0;
+    long long totals[4] = {0, 0, 0, 0}, errors[2] = {0, 0};
+    const IndexDev &d = table->dev;
+    if (hipMemcpyAsync(&entries, d.c.n_entries, 4, hipMemcpyDeviceToHost, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (hipMemcpyAsync(totals, d.c.totals, sizeof(totals), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (hipMemcpyAsync(errors, d.errors, sizeof(errors), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return RNNLM_EDEVICE;
+    out[0] = entries;
+    out[1] = totals[0]; out[2] = totals[1]; out[3] = totals[3];
+    out[4] = errors[0]; out[5] = errors[1];
     return RNNLM_OK;
 }
 

@@ -136,6 +136,105 @@ __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
     }
 }
 
+// ---- the same lookup for many histories (more than one workgroup can number in one round):
+// probe + per-workgroup miss counts, a scan of the counts, then numbering + insertion.  The
+// launch boundaries put every probe before every insertion.
+__device__ __forceinline__ int probe_table(const CacheDev &c, uint64_t key) {
+    const uint32_t mask = (uint32_t)(c.table_size - 1);
+    uint32_t h = mix64(key) & mask;
+    for (int probe = 0; probe < c.table_size; ++probe) {
+        const CacheCell cell = c.table[h];
+        if (cell.entry < 0) return -1;
+        if (cell.key == key) return cell.entry;
+        h = (h + 1) & mask;
+    }
+    return -1;
+}
+
+__global__ __launch_bounds__(kLookupThreads) void lookup_probe_kernel(
+    CacheDev c, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
+    const int32_t *__restrict__ n_unique) {
+    __shared__ int wsum[kLookupThreads / 64 + 1];
+    const int U = *n_unique;
+    const int u = blockIdx.x * kLookupThreads + (int)threadIdx.x;
+    int miss = 0;
+    if (u < U) {
+        const int found = probe_table(c, ids[rep[u]]);
+        c.entry_of[u] = found;
+        miss = found < 0 ? 1 : 0;
+    }
+    int total;
+    (void)block_exclusive_scan(miss, wsum, total);
+    if (threadIdx.x == 0) c.block_total[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kLookupThreads) void lookup_scan_kernel(CacheDev c, int blocks,
+                                                                     const int32_t *__restrict__ n_unique,
+                                                                     int32_t *__restrict__ step_stats) {
+    __shared__ int wsum[kLookupThreads / 64 + 1];
+    int carry = 0;
+    for (int b0 = 0; b0 < blocks; b0 += kLookupThreads) {
+        const int b = b0 + (int)threadIdx.x;
+        const int v = (b < blocks) ? c.block_total[b] : 0;
+        int total;
+        const int excl = carry + block_exclusive_scan(v, wsum, total);
+        if (b < blocks) c.block_total[b] = excl;
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        const int U = *n_unique, n_miss = carry, base = *c.n_entries;
+        const int stored = min(n_miss, max(c.capacity - base, 0));
+        c.block_total[blocks] = base;               // entries before this call, for the numbering
+        *c.n_miss = n_miss;
+        *c.n_entries = base + stored;
+        c.totals[0] += U;
+        c.totals[1] += U - n_miss;
+        c.totals[2] += n_miss;
+        c.totals[3] += n_miss - stored;
+        if (step_stats) {
+            step_stats[0] = U;
+            step_stats[1] = U - n_miss;
+            step_stats[2] = n_miss;
+            step_stats[3] = base + stored;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kLookupThreads) void lookup_assign_kernel(
+    CacheDev c, int blocks, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
+    const int32_t *__restrict__ n_unique) {
+    __shared__ int wsum[kLookupThreads / 64 + 1];
+    const int U = *n_unique;
+    const int base = c.block_total[blocks];
+    const int u = blockIdx.x * kLookupThreads + (int)threadIdx.x;
+    const bool active = u < U;
+    const int miss = (active && c.entry_of[u] < 0) ? 1 : 0;
+    int total;
+    const int rank = c.block_total[blockIdx.x] + block_exclusive_scan(miss, wsum, total);
+    if (miss) {
+        const int raw = rep[u];
+        const uint64_t key = ids[raw];
+        const int entry = (base + rank < c.capacity) ? base + rank : -1;
+        c.miss_of[u] = rank;
+        c.miss_src[rank] = raw;
+        c.miss_dst[rank] = u;
+        c.entry_of[u] = entry;
+        if (entry >= 0) {
+            const uint32_t mask = (uint32_t)(c.table_size - 1);
+            uint32_t h = mix64(key) & mask;
+            for (int probe = 0; probe < c.table_size; ++probe) {
+                if (atomicCAS(&c.table[h].entry, -1, entry) == -1) {
+                    c.table[h].key = key;
+                    break;
+                }
+                h = (h + 1) & mask;
+            }
+        }
+    } else if (active) {
+        c.miss_of[u] = -1;
+    }
+}
+
 __global__ __launch_bounds__(256) void cache_commit_kernel(CacheDev c, ModelDev m,
                                                             const int32_t *__restrict__ n_unique,
                                                             SplitInfo si, float *__restrict__ h_out) {
@@ -182,10 +281,19 @@ hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_cache_lookup(const CacheDev &c, const uint64_t *ids, const int32_t *rep,
+hipError_t launch_cache_lookup(const CacheDev &c, int rows, const uint64_t *ids, const int32_t *rep,
                                const int32_t *n_unique, int32_t *step_stats, hipStream_t stream) {
-    hipLaunchKernelGGL(cache_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, rep, n_unique,
+    if (rows <= 2 * kLookupThreads) {                   // few histories: one workgroup, one launch
+        hipLaunchKernelGGL(cache_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, rep, n_unique,
+                           step_stats);
+        return hipGetLastError();
+    }
+    const int blocks = (rows + kLookupThreads - 1) / kLookupThreads;
+    hipLaunchKernelGGL(lookup_probe_kernel, dim3(blocks), dim3(kLookupThreads), 0, stream, c, ids, rep, n_unique);
+    hipLaunchKernelGGL(lookup_scan_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, blocks, n_unique,
                        step_stats);
+    hipLaunchKernelGGL(lookup_assign_kernel, dim3(blocks), dim3(kLookupThreads), 0, stream, c, blocks, ids, rep,
+                       n_unique);
     return hipGetLastError();
 }
 

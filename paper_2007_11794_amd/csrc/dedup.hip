@@ -10,7 +10,7 @@
 //
 // Two implementations with identical results:
 //   small  (N <= kSmallN): one workgroup, table and flags in LDS, one launch;
-//   large  : table in the caller's workspace, four launches.
+//   large  : table in the caller's workspace, six launches (the numbering is a grid-wide scan).
 #include "device_utils.h"
 #include "rnnlm_internal.h"
 
@@ -109,6 +109,7 @@ struct LargeWs {
     int *tfirst;       // [cap+1]
     int *tgroup;       // [cap+1]
     int *slot;         // [N]
+    int *block_total;  // [N / 1024 + 1]
 };
 
 __host__ inline LargeWs carve(void *ws, int N) {
@@ -118,7 +119,8 @@ __host__ inline LargeWs carve(void *ws, int N) {
     w.tkeys = reinterpret_cast<uint64_t *>(p); p += (size_t)(cap + 2) * 8;
     w.tfirst = reinterpret_cast<int *>(p);     p += (size_t)(cap + 2) * 4;
     w.tgroup = reinterpret_cast<int *>(p);     p += (size_t)(cap + 2) * 4;
-    w.slot = reinterpret_cast<int *>(p);
+    w.slot = reinterpret_cast<int *>(p);       p += (size_t)N * 4;
+    w.block_total = reinterpret_cast<int *>(p);
     return w;
 }
 
@@ -139,26 +141,57 @@ __global__ void dedup_insert_kernel(const uint64_t *__restrict__ keys, int N, ui
     atomicMin(&tfirst[s], n);
 }
 
-// One workgroup walks the queries in raw order, 1024 at a time, carrying the running count.
-__global__ __launch_bounds__(1024) void dedup_rank_kernel(int N, const int *__restrict__ slot,
-                                                          const int *__restrict__ tfirst,
-                                                          int *tgroup, int32_t *rep,
-                                                          int32_t *n_unique) {
-    __shared__ int wsum[1024 / 64 + 1];
+// Group numbers in raw order = exclusive prefix sum over the "first" flags, in three launches so
+// that every query is touched by a full grid: per-workgroup counts, a scan of those counts by
+// one workgroup, then the numbering proper.
+constexpr int kRankThreads = 1024;
+
+__device__ __forceinline__ int first_flag(int n, int N, const int *__restrict__ slot,
+                                          const int *__restrict__ tfirst, int &s) {
+    s = (n < N) ? slot[n] : 0;
+    return (n < N && tfirst[s] == n) ? 1 : 0;
+}
+
+__global__ __launch_bounds__(kRankThreads) void dedup_count_kernel(int N, const int *__restrict__ slot,
+                                                                   const int *__restrict__ tfirst,
+                                                                   int *__restrict__ block_total) {
+    __shared__ int wsum[kRankThreads / 64 + 1];
+    int s, total;
+    const int first = first_flag(blockIdx.x * kRankThreads + threadIdx.x, N, slot, tfirst, s);
+    (void)block_exclusive_scan(first, wsum, total);
+    if (threadIdx.x == 0) block_total[blockIdx.x] = total;
+}
+
+// In place: block_total[b] becomes the number of firsts before workgroup b; *n_unique the total.
+__global__ __launch_bounds__(kRankThreads) void dedup_scan_kernel(int blocks, int *__restrict__ block_total,
+                                                                  int32_t *__restrict__ n_unique) {
+    __shared__ int wsum[kRankThreads / 64 + 1];
     int carry = 0;
-    for (int base = 0; base < N; base += 1024) {
-        int n = base + threadIdx.x;
-        int s = (n < N) ? slot[n] : 0;
-        int first = (n < N && tfirst[s] == n) ? 1 : 0;
+    for (int base = 0; base < blocks; base += kRankThreads) {
+        const int b = base + threadIdx.x;
+        const int v = (b < blocks) ? block_total[b] : 0;
         int total;
-        int u = carry + block_exclusive_scan(first, wsum, total);
-        if (first) {
-            rep[u] = n;
-            tgroup[s] = u;
-        }
+        const int excl = carry + block_exclusive_scan(v, wsum, total);
+        if (b < blocks) block_total[b] = excl;
         carry += total;
     }
     if (threadIdx.x == 0) *n_unique = carry;
+}
+
+__global__ __launch_bounds__(kRankThreads) void dedup_number_kernel(int N, const int *__restrict__ slot,
+                                                                    const int *__restrict__ tfirst,
+                                                                    const int *__restrict__ block_total,
+                                                                    int *__restrict__ tgroup,
+                                                                    int32_t *__restrict__ rep) {
+    __shared__ int wsum[kRankThreads / 64 + 1];
+    const int n = blockIdx.x * kRankThreads + threadIdx.x;
+    int s, total;
+    const int first = first_flag(n, N, slot, tfirst, s);
+    const int u = block_total[blockIdx.x] + block_exclusive_scan(first, wsum, total);
+    if (first) {
+        rep[u] = n;
+        tgroup[s] = u;
+    }
 }
 
 __global__ void dedup_inverse_kernel(int N, const int *__restrict__ slot,
@@ -174,7 +207,7 @@ __global__ void dedup_empty_kernel(int32_t *n_unique) { *n_unique = 0; }
 size_t dedup_workspace_bytes(int N) {
     if (N <= 0) return 0;
     int cap = table_capacity(N);
-    size_t bytes = (size_t)(cap + 2) * 16 + (size_t)N * 4;
+    size_t bytes = (size_t)(cap + 2) * 16 + (size_t)N * 4 + ((size_t)N / kRankThreads + 2) * 4;
     return (bytes + 255) & ~(size_t)255;
 }
 
@@ -195,8 +228,12 @@ hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inve
                        w.tfirst, cap);
     hipLaunchKernelGGL(dedup_insert_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, keys, N,
                        w.tkeys, w.tfirst, w.slot, cap);
-    hipLaunchKernelGGL(dedup_rank_kernel, dim3(1), dim3(1024), 0, stream, N, w.slot, w.tfirst, w.tgroup,
-                       rep, n_unique);
+    const int blocks = (N + kRankThreads - 1) / kRankThreads;
+    hipLaunchKernelGGL(dedup_count_kernel, dim3(blocks), dim3(kRankThreads), 0, stream, N, w.slot, w.tfirst,
+                       w.block_total);
+    hipLaunchKernelGGL(dedup_scan_kernel, dim3(1), dim3(kRankThreads), 0, stream, blocks, w.block_total, n_unique);
+    hipLaunchKernelGGL(dedup_number_kernel, dim3(blocks), dim3(kRankThreads), 0, stream, N, w.slot, w.tfirst,
+                       w.block_total, w.tgroup, rep);
     hipLaunchKernelGGL(dedup_inverse_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, N, w.slot,
                        w.tgroup, inverse);
     return hipGetLastError();

@@ -142,6 +142,14 @@ __device__ __forceinline__ uint32_t mix64(uint64_t k) {
     return (uint32_t)k;
 }
 
+// The same finaliser with all 64 bits kept.
+__device__ __forceinline__ uint64_t mix64_full(uint64_t k) {
+    k ^= k >> 30; k *= 0xBF58476D1CE4E5B9ull;
+    k ^= k >> 27; k *= 0x94D049BB133111EBull;
+    k ^= k >> 31;
+    return k;
+}
+
 // Block-wide exclusive prefix sum of one int per thread; returns the exclusive prefix and,
 // through `total`, the block sum.  `wsum` is LDS scratch of blockDim.x/64 + 1 ints.
 __device__ __forceinline__ int block_exclusive_scan(int v, int *wsum, int &total) {

@@ -1,0 +1,171 @@
+// IndexTable and its inverse on the device (Section 3.2; Table 1 steps 5 and 7-12): a context
+// -- the word it ends in and its hidden vector (Section 4.1) -- is stored once and stands for a
+// 4-byte index from then on (Table 3), so that only indices have to travel.
+//
+// Inverse direction (context -> index), for N contexts given by value:
+//   hash     one wave per context: 64-bit hash of the word and of every bit of the vector;
+//   group    equal hashes of the call are grouped in order of first appearance (the grouping
+//            kernel of the step);
+//   lookup   the cache's lookup kernel on the hashes: found -> the stored index; new -> the next
+//            indices in order of first appearance (Table 1 step 10), keys inserted;
+//   commit   one wave per context: a new context is copied into the stores by its first
+//            occurrence; every other one is compared word for word and bit for bit with the
+//            context it was identified with (the stored one, or the first occurrence in this
+//            call), so that a hash collision cannot go unnoticed: it is counted and the
+//            context gets the index 0xFFFFFFFE instead of a wrong one.
+// Forward direction (index -> context): a gather.
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+constexpr uint32_t kNotStored = 0xFFFFFFFFu, kCollision = 0xFFFFFFFEu;
+
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, off, 64), hi = __shfl_xor((uint32_t)(v >> 32), off, 64);
+        v += ((uint64_t)hi << 32) | lo;
+    }
+    return v;
+}
+
+// Rows of H floats can be walked in 16-byte pieces when H is a multiple of 4 and the buffer is
+// 16-byte aligned (the stores of the table are).
+__device__ __forceinline__ bool vec_rows(const void *p, int H) {
+    return (H & 3) == 0 && (reinterpret_cast<uintptr_t>(p) & 15) == 0;
+}
+
+__device__ __forceinline__ void copy_row(uint32_t *dst, const uint32_t *src, int H, int lane, bool vec) {
+    if (vec) {
+        for (int j = 4 * lane; j < H; j += 256)
+            *reinterpret_cast<u32x4 *>(dst + j) = *reinterpret_cast<const u32x4 *>(src + j);
+    } else {
+        for (int j = lane; j < H; j += 64) dst[j] = src[j];
+    }
+}
+
+// The hash of a vector is the sum (mod 2^64) of a 64-bit mix of every (position, bit pattern)
+// pair: order-free, so lanes and their partial sums can be combined in any way.
+__global__ __launch_bounds__(256) void context_hash_kernel(const int32_t *__restrict__ word,
+                                                            const float *__restrict__ h, int N, int H,
+                                                            uint64_t *__restrict__ keys) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    const uint32_t *row = reinterpret_cast<const uint32_t *>(h) + (size_t)n * H;
+    uint64_t acc = 0;
+    if (vec_rows(h, H)) {                                // 16 bytes per lane and load
+        for (int j = 4 * lane; j < H; j += 256) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(row + j);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc += mix64_full(((uint64_t)v[i] << 32) | (uint32_t)(j + i));
+        }
+    } else {
+        for (int j = lane; j < H; j += 64) acc += mix64_full(((uint64_t)row[j] << 32) | (uint32_t)j);
+    }
+    acc = wave_sum_u64(acc);
+    if (lane == 0) keys[n] = mix64_full(acc ^ ((uint64_t)(uint32_t)word[n] * 0x9E3779B97F4A7C15ull));
+}
+
+__global__ __launch_bounds__(256) void index_commit_kernel(IndexDev t, int N, const int32_t *__restrict__ word,
+                                                            const float *__restrict__ h,
+                                                            uint32_t *__restrict__ index) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    const int H = t.c.H;
+    const int u = t.inverse[n];
+    const int e = t.c.entry_of[u];
+    const bool is_new = t.c.miss_of[u] >= 0;
+    const int first = t.rep[u];
+    const uint32_t *mine = reinterpret_cast<const uint32_t *>(h) + (size_t)n * H;
+    const bool vec = vec_rows(h, H);
+    bool differs = false;
+    if (is_new && n == first) {
+        if (e >= 0) {                                    // store the new context
+            copy_row(reinterpret_cast<uint32_t *>(t.c.store_h) + (size_t)e * H, mine, H, lane, vec);
+            if (lane == 0) t.store_word[e] = word[n];
+        }
+    } else {
+        // `first` never equals n here when the reference is this call's first occurrence, and a
+        // stored context is not written by this call: no read races a write
+        const uint32_t *ref = is_new ? reinterpret_cast<const uint32_t *>(h) + (size_t)first * H
+                                     : reinterpret_cast<const uint32_t *>(t.c.store_h) + (size_t)e * H;
+        const int ref_word = is_new ? word[first] : t.store_word[e];
+        bool d = word[n] != ref_word;
+        if (vec) {
+            for (int j = 4 * lane; j < H; j += 256) {
+                const u32x4 a = *reinterpret_cast<const u32x4 *>(mine + j), b = *reinterpret_cast<const u32x4 *>(ref + j);
+                d |= (a[0] != b[0]) | (a[1] != b[1]) | (a[2] != b[2]) | (a[3] != b[3]);
+            }
+        } else {
+            for (int j = lane; j < H; j += 64) d |= mine[j] != ref[j];
+        }
+        differs = __any(d);
+    }
+    if (lane == 0) {
+        if (differs) {
+            atomicAdd(reinterpret_cast<unsigned long long *>(&t.errors[0]), 1ull);
+            index[n] = kCollision;
+        } else {
+            index[n] = e >= 0 ? (uint32_t)e : kNotStored;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void index_fetch_kernel(IndexDev t, int N, const uint32_t *__restrict__ index,
+                                                           int32_t *__restrict__ word, float *__restrict__ h) {
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= N) return;
+    const int H = t.c.H;
+    const uint32_t i = index[n];
+    float *dst = h + (size_t)n * H;
+    if (i < (uint32_t)*t.c.n_entries) {
+        copy_row(reinterpret_cast<uint32_t *>(dst), reinterpret_cast<const uint32_t *>(t.c.store_h) + (size_t)i * H, H,
+                 lane, vec_rows(h, H));
+        if (lane == 0) word[n] = t.store_word[i];
+    } else {                                             // not an index this table holds
+        for (int j = lane; j < H; j += 64) dst[j] = quiet_nan();
+        if (lane == 0) {
+            word[n] = -1;
+            atomicAdd(reinterpret_cast<unsigned long long *>(&t.errors[1]), 1ull);
+        }
+    }
+}
+
+__global__ void index_clear_errors_kernel(IndexDev t) {
+    if (threadIdx.x < 2) t.errors[threadIdx.x] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_index_reset(const IndexDev &t, hipStream_t stream) {
+    hipError_t e = launch_cache_reset(t.c, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(index_clear_errors_kernel, dim3(1), dim3(64), 0, stream, t);
+    return hipGetLastError();
+}
+
+hipError_t launch_context_hash(const int32_t *word, const float *h, int N, int H, uint64_t *keys,
+                               hipStream_t stream) {
+    if (N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(context_hash_kernel, dim3((N + 3) / 4), dim3(256), 0, stream, word, h, N, H, keys);
+    return hipGetLastError();
+}
+
+hipError_t launch_index_commit(const IndexDev &t, int N, const int32_t *word, const float *h, uint32_t *index,
+                               hipStream_t stream) {
+    if (N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(index_commit_kernel, dim3((N + 3) / 4), dim3(256), 0, stream, t, N, word, h, index);
+    return hipGetLastError();
+}
+
+hipError_t launch_index_fetch(const IndexDev &t, int N, const uint32_t *index, int32_t *word, float *h,
+                              hipStream_t stream) {
+    if (N <= 0) return hipSuccess;
+    hipLaunchKernelGGL(index_fetch_kernel, dim3((N + 3) / 4), dim3(256), 0, stream, t, N, index, word, h);
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm

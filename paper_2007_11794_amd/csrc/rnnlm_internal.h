@@ -64,8 +64,26 @@ struct CacheDev {
     int32_t *miss_dst;      // computed row -> u
     float *lse_rows;        // [max_B] normaliser of every distinct history of the step
     int *n_miss;            // [1]
+    int *block_total;       // [max_B / 1024 + 2] scan scratch of the many-workgroup lookup; last = entries before
 };
+// Device-side view of an index table (index_table.hip): contexts stored by value, found again
+// by content.  The hash table, the counters and the per-call scratch are the cache's.
+struct IndexDev {
+    CacheDev c;             // c.store_h = hidden vectors [capacity][H]; c.store_lse, c.lse_rows unused
+    int32_t *store_word;    // [capacity]
+    uint64_t *keys;         // [max_N] content hashes of the call
+    int32_t *rep, *inverse; // [max_N] grouping of the call's hashes
+    int32_t *n_unique;      // [1]
+    void *dedup_ws;
+    long long *errors;      // [2] hash collisions caught by the full comparison, bad indices in fetch
+};
+
 }  // namespace rnnlm
+
+struct rnnlm_index_table {
+    rnnlm::IndexDev dev;
+    int max_N;
+};
 
 struct rnnlm_cache {
     rnnlm::CacheDev dev;
@@ -142,12 +160,23 @@ hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, in
 hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream);
 // Looks the distinct histories ids[rep[u]], u < *n_unique, up; numbers the ones not found
 // (in order of u), gives them entries while there is room and inserts their keys.
-hipError_t launch_cache_lookup(const CacheDev &c, const uint64_t *ids, const int32_t *rep,
+// rows = upper bound of *n_unique (sizes the grid).
+hipError_t launch_cache_lookup(const CacheDev &c, int rows, const uint64_t *ids, const int32_t *rep,
                                const int32_t *n_unique, int32_t *step_stats, hipStream_t stream);
 // After the computed block is done: normalisers of all distinct histories into c.lse_rows,
 // new entries into the stores, stored hidden vectors of found histories into h_out.
 hipError_t launch_cache_commit(const CacheDev &c, const ModelDev &m, int rows, const int32_t *n_unique,
                                SplitInfo splits, float *h_out, hipStream_t stream);
+// Index table: content hashes of N contexts; after grouping and lookup, storage of the new
+// contexts, full comparison of every context with the one it was identified with, and the
+// indices; gather of stored contexts.
+hipError_t launch_index_reset(const IndexDev &t, hipStream_t stream);
+hipError_t launch_context_hash(const int32_t *word, const float *h, int N, int H, uint64_t *keys,
+                               hipStream_t stream);
+hipError_t launch_index_commit(const IndexDev &t, int N, const int32_t *word, const float *h, uint32_t *index,
+                               hipStream_t stream);
+hipError_t launch_index_fetch(const IndexDev &t, int N, const uint32_t *index, int32_t *word, float *h,
+                              hipStream_t stream);
 hipError_t launch_pack_ids(const uint32_t *ctx, const uint32_t *small_lm, int N, uint64_t *ids,
                            hipStream_t stream);
 

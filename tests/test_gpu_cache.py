@@ -89,6 +89,27 @@ def test_steps_through_the_cache_match_the_oracle(dtype, V, H, kernel, capacity)
     m.close()
 
 
+def test_many_histories_take_the_grid_wide_lookup():
+    """More than 4096 raw queries: grouping and lookup run as grid-wide scans."""
+    rng = np.random.default_rng(77)
+    V, H, K = 2000, 64, 2
+    model = small_model(rng, V, H, "bf16", 0.1)
+    m = load_model(model, "bf16", 9000)
+    pool = rng.integers(0, 2 ** 64, 7000, dtype=np.uint64)
+    for capacity in (100000, 3000):
+        cache = rn.rnnlm_cache_create(m, capacity)
+        ocache = oracle.Cache(H, capacity)
+        st = CachedStepper(m, cache, 9000, K)
+        for step, N in enumerate([6000, 9000, 4097]):
+            ids, prev, h_in, query, base = draw_step(rng, V, H, N, K, pool)
+            out = st.step(ids, prev, h_in, query, base)
+            ref = oracle.step_cached(model, ocache, ids, prev, h_in, query, base_score=base)
+            compare(out, ref, "bf16", "grid-wide lookup cap=%d step %d" % (capacity, step))
+        assert cache.stats() == ocache.stats()
+        cache.close()
+    m.close()
+
+
 def test_answer_from_cache_is_bit_identical_and_ignores_new_inputs():
     rng = np.random.default_rng(5)
     V, H, N, K = 6000, 128, 400, 6
