@@ -29,6 +29,55 @@ PEAK_FP32_TFLOPS = 157.3         # MI355X fp32 vector (and fp32 matrix), publish
 OUTPROJ_TRAFFIC_BYTES = {"staged": 78.0e6}
 
 
+def bench_index_table(args, cfg, rn, torch, np) -> int:
+    """One "step" = the N*K contexts that follow a step (queried word, updated hidden vector of its
+    history) turned into indices; reported for new contexts and for contexts the table already
+    holds, plus the fetch of N contexts.  Prints one JSON line; HBM-bound (every call walks the
+    hidden vectors once)."""
+    dev = "cuda:0"
+    M, H = cfg.N * cfg.K, cfg.H
+    reps = max(4, min(args.steps, 40))
+    table = rn.rnnlm_index_create(H, M * (reps + 2), M)
+    g = torch.Generator(device=dev).manual_seed(cfg.seed)
+    word = torch.randint(0, cfg.V, (M,), generator=g, device=dev, dtype=torch.int32)
+    batches = [torch.rand((M, H), generator=g, device=dev) for _ in range(reps + 1)]
+    index = torch.zeros(M, dtype=torch.int32, device=dev)
+    rn.rnnlm_index_intern(table, word, batches[0], index)            # warm-up
+    torch.cuda.synchronize()
+
+    def timed(fn, n):
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    t_new = timed(lambda i: rn.rnnlm_index_intern(table, word, batches[1 + i], index), reps)
+    t_known = timed(lambda i: rn.rnnlm_index_intern(table, word, batches[1 + i], index), reps)
+    w2 = torch.zeros(cfg.N, dtype=torch.int32, device=dev)
+    h2 = torch.zeros((cfg.N, H), device=dev)
+    t_fetch = timed(lambda i: rn.rnnlm_index_fetch(table, index[: cfg.N], w2, h2), reps)
+    st = table.stats()
+    assert st["collisions"] == 0 and st["bad_fetch"] == 0 and st["unstored"] == 0
+    row_bytes = 4.0 * H
+    out = {"metric": "IndexTable contexts/sec (H=%d, %d contexts per call)" % (H, M),
+           "value": round(M / t_new, 1), "unit": "contexts/s", "n_gpus": 1, "steps": reps, "warmup": 1,
+           "ms_per_step": round(t_new * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "u32", "data": "synthetic",
+           "config": {"workload": "%s: contexts of the step's shape, N*K = %d x H = %d floats, all new" % (cfg.name, M, H)},
+           "roofline": {"kernel": "context_hash + index_commit", "bound": "hbm",
+                        "achieved": round(3 * M * row_bytes / t_new / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                        "frac": round(3 * M * row_bytes / t_new / 8e12, 4), "traffic": None,
+                        "note": "algorithmic bytes of a call with new contexts: rows read by the hash, read and "
+                                "written by the commit = 3 x %d x %d B" % (M, int(row_bytes))},
+           "cpu_baseline": None,
+           "index_table": {"intern_new_us": round(t_new * 1e6, 1), "intern_known_us": round(t_known * 1e6, 1),
+                           "fetch_%d_us" % cfg.N: round(t_fetch * 1e6, 1), "entries": st["entries"]}}
+    print(json.dumps(out))
+    table.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +93,9 @@ def main() -> int:
                     help="config 4 only: time a decode trace of --trace-steps steps through a cache of "
                          "CAPACITY histories kept between the steps (reset at the start of every pass)")
     ap.add_argument("--trace-steps", type=int, default=8)
+    ap.add_argument("--index-table", action="store_true",
+                    help="time the device-side IndexTable instead of the step: contexts of the chosen "
+                         "workload's shape (N x K contexts of H floats) turned into indices and fetched back")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy kernel, as the known-size "
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -64,6 +116,8 @@ def main() -> int:
     rn.lib()                                   # raises if librnnlm.so is not built
     dev = "cuda:0"
     cfg = CONFIGS[args.config]
+    if args.index_table:
+        return bench_index_table(args, cfg, rn, torch, np)
     bf16 = cfg.dtype == "bf16"
     model = make_model(cfg)
     if cfg.unique_frac is not None:

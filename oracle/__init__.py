@@ -53,6 +53,10 @@ def _load():
         lib.oracle_step_cached.restype = I
         lib.oracle_pack_ids.argtypes = [P, P, I, P]
         lib.oracle_pack_ids.restype = None
+        lib.oracle_huffman_build.argtypes = [I, P, P, P, ctypes.c_longlong]
+        lib.oracle_huffman_build.restype = ctypes.c_longlong
+        lib.oracle_hs_step.argtypes = [I, I, I, I, I] + [P] * 12 + [I]
+        lib.oracle_hs_step.restype = I
         lib.oracle_index_new.argtypes = [I, I]
         lib.oracle_index_new.restype = P
         lib.oracle_index_free.argtypes = [P]
@@ -241,3 +245,56 @@ class IndexTable:
         if getattr(self, "_h", None) and _lib is not None:
             _lib.oracle_index_free(self._h)
             self._h = None
+
+
+def huffman_build(freq):
+    """Huffman tree over the words (Section 2.1) from their frequencies: returns path_off i32[V+1]
+    and path_entry i32[total], the path of word v from the root down being
+    path_entry[path_off[v]:path_off[v+1]], each entry = inner node id | code bit << 31."""
+    freq = _c(freq, np.float64)
+    V = freq.shape[0]
+    off = np.zeros(V + 1, dtype=np.int32)
+    cap = 64 * V
+    entry = np.zeros(cap, dtype=np.int32)
+    total = _load().oracle_huffman_build(V, _ptr(freq), _ptr(off), _ptr(entry), cap)
+    if total < -1:
+        cap = -total - 1
+        entry = np.zeros(cap, dtype=np.int32)
+        total = _load().oracle_huffman_build(V, _ptr(freq), _ptr(off), _ptr(entry), cap)
+    if total < 0:
+        raise ValueError("oracle_huffman_build failed")
+    return off, entry[:total].copy()
+
+
+def hs_step(model: dict, prev, h_in, query, row_of_query=None, want_full: bool = False,
+            num_threads: int = 0) -> dict:
+    """One step with the hierarchical output layer.  model: float32 U[V,H], W[H,H], theta[V-1,H],
+    int32 path_off[V+1], path_entry[...].  Returns float64 h_out[B,H], logprob[N,K]."""
+    U = _c(model["U"], np.float32)
+    W = _c(model["W"], np.float32)
+    theta = _c(model["theta"], np.float32)
+    off = _c(model["path_off"], np.int32)
+    entry = _c(model["path_entry"], np.int32)
+    V, H = U.shape
+    assert W.shape == (H, H) and theta.shape == (V - 1, H) and off.shape == (V + 1,)
+    prev = _c(prev, np.int32)
+    h_in = _c(h_in, np.float32)
+    query = _c(query, np.int32)
+    B = prev.shape[0]
+    N, K = query.shape
+    if row_of_query is not None:
+        row_of_query = _c(row_of_query, np.int32)
+    else:
+        assert N == B
+    h_out = np.zeros((B, H), dtype=np.float64)
+    logprob = np.zeros((N, K), dtype=np.float64)
+    full = np.zeros((B, V), dtype=np.float64) if want_full else None
+    rc = _load().oracle_hs_step(V, H, B, K, N, _ptr(U), _ptr(W), _ptr(theta), _ptr(off), _ptr(entry),
+                                _ptr(prev), _ptr(h_in), _ptr(query), _ptr(row_of_query), _ptr(h_out),
+                                _ptr(logprob), _ptr(full), num_threads)
+    if rc != 0:
+        raise ValueError("oracle_hs_step: index out of range")
+    out = {"h_out": h_out, "logprob": logprob}
+    if want_full:
+        out["full_logp"] = full
+    return out

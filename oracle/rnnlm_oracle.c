@@ -22,6 +22,9 @@
  *   cache      the same lookup kept between steps (Table 1 as a whole; Sections 4.2, 5.3),
  *              the score difference handed back after it, and the packed 8-byte index of
  *              Section 3.2: oracle_step_cached, oracle_pack_ids further down.
+ *   tree       the hierarchical output layer of Section 2.1 (Huffman tree over the words,
+ *              probability = product of sigmoids along the path): oracle_huffman_build,
+ *              oracle_hs_step further down.
  *   index      IndexTable and its inverse (Section 3.2, Table 1 steps 5, 7-12): contexts stored
  *              by value, found again by content: oracle_index_* further down.
  *
@@ -395,6 +398,145 @@ int oracle_index_fetch(const oracle_index *t, int N, const uint32_t *index, int3
         if (index[n] >= (uint32_t)t->count) return -1;
         word[n] = t->word[index[n]];
         memcpy(h + (size_t)n * t->H, t->h + (size_t)index[n] * t->H, (size_t)t->H * sizeof(float));
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------
+ * Hierarchical softmax (Section 2.1): the output layer is a binary tree with the words at the
+ * leaves, built by Huffman's method from the word frequencies (frequent words get short
+ * codes); the probability of a word is normalised only over the nodes on the path from the
+ * root to the word.  The paper prints no formula; this is the standard form: every inner node
+ * i has a vector theta_i, and
+ *     p(w | h') = prod over the path nodes i of sigmoid(+-theta_i . h'),
+ * + for a step to the child with code bit 0, - for code bit 1, so that the two children of a
+ * node share its probability mass and the leaves sum to one.
+ *
+ * Huffman's method as two queues: the leaves sorted by (frequency, word id) ascending, and the
+ * inner nodes in order of creation (their weights never decrease).  Each merge takes the two
+ * lightest heads; on equal weight a leaf goes before an inner node.  The first taken becomes
+ * the child with code bit 0.  Inner nodes are numbered 0 .. V-2 in order of creation (the root
+ * is V-2).  Output per word: its path from the root down as entries node | code << 31.
+ * Returns the number of entries, or -1 (V < 2, a negative frequency, out of memory), or
+ * -(needed) - 1 when `capacity` is too small.
+ */
+typedef struct { double f; int32_t id; } hs_leaf;
+
+static int hs_leaf_cmp(const void *a, const void *b)
+{
+    const hs_leaf *x = (const hs_leaf *)a, *y = (const hs_leaf *)b;
+    if (x->f < y->f) return -1;
+    if (x->f > y->f) return 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+long long oracle_huffman_build(int V, const double *freq, int32_t *path_off, int32_t *path_entry,
+                               long long capacity)
+{
+    if (V < 2) return -1;
+    for (int v = 0; v < V; ++v)
+        if (!(freq[v] >= 0.0)) return -1;
+    hs_leaf *leaves = (hs_leaf *)malloc((size_t)V * sizeof(hs_leaf));
+    double *iw = (double *)malloc((size_t)(V - 1) * sizeof(double));       /* inner node weights */
+    int32_t *parent = (int32_t *)malloc((size_t)(2 * V - 1) * sizeof(int32_t));  /* leaves 0..V-1, inner V+i */
+    unsigned char *bit = (unsigned char *)malloc((size_t)(2 * V - 1));
+    if (!leaves || !iw || !parent || !bit) { free(leaves); free(iw); free(parent); free(bit); return -1; }
+    for (int v = 0; v < V; ++v) { leaves[v].f = freq[v]; leaves[v].id = v; }
+    qsort(leaves, (size_t)V, sizeof(hs_leaf), hs_leaf_cmp);
+    int li = 0, ii = 0;                       /* heads of the two queues */
+    for (int n = 0; n < V - 1; ++n) {         /* create inner node n */
+        double w = 0.0;
+        for (int c = 0; c < 2; ++c) {
+            int take_leaf;
+            if (li >= V) take_leaf = 0;
+            else if (ii >= n) take_leaf = 1;
+            else take_leaf = leaves[li].f <= iw[ii];
+            int child;
+            if (take_leaf) { child = leaves[li].id; w += leaves[li].f; ++li; }
+            else { child = V + ii; w += iw[ii]; ++ii; }
+            parent[child] = V + n;
+            bit[child] = (unsigned char)c;
+        }
+        iw[n] = w;
+    }
+    parent[V + V - 2] = -1;
+    long long total = 0;
+    for (int v = 0; v < V; ++v) {
+        int len = 0;
+        for (int x = v; parent[x] >= 0; x = parent[x]) ++len;
+        path_off[v] = (int32_t)total;
+        if (total + len <= capacity) {
+            int at = len;
+            for (int x = v; parent[x] >= 0; x = parent[x]) {
+                --at;
+                path_entry[total + at] = (int32_t)((uint32_t)(parent[x] - V) | ((uint32_t)bit[x] << 31));
+            }
+        }
+        total += len;
+    }
+    path_off[V] = (int32_t)total;
+    free(leaves); free(iw); free(parent); free(bit);
+    return total <= capacity ? total : -total - 1;
+}
+
+static double log_sigmoid(double z)
+{
+    return z >= 0.0 ? -log1p(exp(-z)) : z - log1p(exp(z));
+}
+
+/* log p(word | h) along its path; theta is [V-1][H]. */
+static double hs_logp(int H, const float *theta, const int32_t *path_off, const int32_t *path_entry,
+                      int word, const double *h)
+{
+    double lp = 0.0;
+    for (int e = path_off[word]; e < path_off[word + 1]; ++e) {
+        uint32_t entry = (uint32_t)path_entry[e];
+        const float *th = theta + (size_t)(entry & 0x7FFFFFFFu) * H;
+        double x = 0.0;
+        for (int j = 0; j < H; ++j) x += (double)th[j] * h[j];
+        lp += log_sigmoid((entry >> 31) ? -x : x);
+    }
+    return lp;
+}
+
+/*
+ * One step with the hierarchical output layer: arguments as oracle_step, with theta and the
+ * paths in place of O and bias.  full_logp (may be NULL): [B][V] log-probabilities of every
+ * word, for the sum-to-one pin.
+ */
+int oracle_hs_step(int V, int H, int B, int K, int N,
+                   const float *U, const float *W, const float *theta,
+                   const int32_t *path_off, const int32_t *path_entry,
+                   const int32_t *prev, const float *h_in,
+                   const int32_t *query, const int32_t *row_of_query,
+                   double *h_out, double *logprob, double *full_logp, int num_threads)
+{
+    for (int b = 0; b < B; ++b)
+        if (prev[b] < 0 || prev[b] >= V) return -1;
+    for (int n = 0; n < N; ++n) {
+        int r = row_of_query ? row_of_query[n] : n;
+        if (r < 0 || r >= B) return -1;
+        for (int k = 0; k < K; ++k)
+            if (query[(size_t)n * K + k] < 0 || query[(size_t)n * K + k] >= V) return -1;
+    }
+    (void)num_threads;
+#ifdef _OPENMP
+    if (num_threads > 0) omp_set_num_threads(num_threads);
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        double *h = h_out + (size_t)b * H;
+        hidden_row(H, U + (size_t)prev[b] * H, W, h_in + (size_t)b * H, h);
+        if (full_logp)
+            for (int v = 0; v < V; ++v)
+                full_logp[(size_t)b * V + v] = hs_logp(H, theta, path_off, path_entry, v, h);
+    }
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int n = 0; n < N; ++n) {
+        int r = row_of_query ? row_of_query[n] : n;
+        for (int k = 0; k < K; ++k)
+            logprob[(size_t)n * K + k] =
+                hs_logp(H, theta, path_off, path_entry, query[(size_t)n * K + k], h_out + (size_t)r * H);
     }
     return 0;
 }

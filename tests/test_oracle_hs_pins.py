@@ -1,0 +1,144 @@
+"""Pins for the oracle's hierarchical output layer (Section 2.1): Huffman tree and path
+probabilities.  Expected values: the textbook example of Huffman's method, the cost of an
+independent heap-based construction (heapq), exact Kraft sums, the closed form for zero node
+vectors, a pure-Python evaluation of the definition, and the sum over all leaves."""
+import heapq
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+
+
+def lengths(off):
+    return np.diff(off)
+
+
+def heap_cost(freq):
+    """Total weighted code length of an optimal prefix code = sum of all merged weights."""
+    h = [float(f) for f in freq]
+    heapq.heapify(h)
+    cost = 0.0
+    while len(h) > 1:
+        a, b = heapq.heappop(h), heapq.heappop(h)
+        cost += a + b
+        heapq.heappush(h, a + b)
+    return cost
+
+
+def check_tree(V, off, entry):
+    L = lengths(off)
+    assert off[0] == 0 and off[-1] == len(entry) and np.all(L >= 1)
+    # Kraft equality, exactly
+    assert sum(Fraction(1, 2 ** int(l)) for l in L) == 1
+    node = entry & 0x7FFFFFFF
+    assert node.min() == 0 and node.max() == V - 2
+    # every word starts at the root; paths are consistent: (node, bit) determines the next node
+    nxt = {}
+    leaf = {}
+    for v in range(V):
+        p = entry[off[v]:off[v + 1]]
+        assert (p[0] & 0x7FFFFFFF) == V - 2
+        for a, b in zip(p[:-1], p[1:]):
+            key = (int(a) & 0x7FFFFFFF, (int(a) >> 31) & 1)
+            assert nxt.setdefault(key, int(b) & 0x7FFFFFFF) == (int(b) & 0x7FFFFFFF)
+        key = (int(p[-1]) & 0x7FFFFFFF, (int(p[-1]) >> 31) & 1)
+        assert key not in leaf and key not in nxt
+        leaf[key] = v
+    # every inner node has exactly two children
+    assert len(nxt) + len(leaf) == 2 * (V - 1)
+    for n in range(V - 1):
+        assert ((n, 0) in nxt or (n, 0) in leaf) and ((n, 1) in nxt or (n, 1) in leaf)
+
+
+def test_textbook_example():
+    off, entry = oracle.huffman_build([5, 9, 12, 13, 16, 45])
+    assert lengths(off).tolist() == [4, 4, 3, 3, 3, 1]
+    check_tree(6, off, entry)
+    # the lighter of the first merge (5) is the child with code bit 0
+    assert (entry[off[0 + 1] - 1] >> 31) & 1 == 0 and (entry[off[1 + 1] - 1] >> 31) & 1 == 1
+
+
+@pytest.mark.parametrize("V,s", [(2, 0.0), (3, 1.0), (64, 0.0), (1000, 1.1), (5000, 1.0), (65536, 1.1)])
+def test_tree_is_valid_and_optimal(V, s):
+    freq = np.arange(1, V + 1, dtype=np.float64) ** -s * 1e6
+    off, entry = oracle.huffman_build(freq)
+    if V <= 5000:
+        check_tree(V, off, entry)
+    L = lengths(off)
+    assert float(np.dot(freq, L)) == pytest.approx(heap_cost(freq), rel=1e-12)
+    assert np.all(np.diff(L) >= 0) or s == 0.0             # rarer words never get shorter codes
+    if s == 0.0 and V == 64:
+        assert np.all(L == 6)
+
+
+def rand_model(rng, V, H, sigma=0.5, freq=None):
+    freq = rng.uniform(1, 100, V) if freq is None else freq
+    off, entry = oracle.huffman_build(freq)
+    return {"U": rng.normal(0, sigma, (V, H)).astype(np.float32), "W": rng.normal(0, sigma, (H, H)).astype(np.float32),
+            "theta": rng.normal(0, sigma, (V - 1, H)).astype(np.float32), "path_off": off, "path_entry": entry}
+
+
+@pytest.mark.parametrize("V,H", [(2, 1), (7, 3), (100, 8), (1000, 16)])
+def test_leaves_sum_to_one(V, H):
+    rng = np.random.default_rng(V)
+    m = rand_model(rng, V, H)
+    B = 3
+    out = oracle.hs_step(m, rng.integers(0, V, B), rng.uniform(0, 1, (B, H)).astype(np.float32),
+                         np.zeros((B, 1), np.int32), want_full=True)
+    assert np.exp(out["full_logp"]).sum(axis=1) == pytest.approx(np.ones(B), abs=1e-12)
+    assert np.all(out["full_logp"] < 0)
+
+
+def test_zero_node_vectors_give_two_to_minus_length():
+    rng = np.random.default_rng(2)
+    V, H = 50, 4
+    m = rand_model(rng, V, H)
+    m["theta"][:] = 0
+    out = oracle.hs_step(m, [0], rng.uniform(0, 1, (1, H)).astype(np.float32), np.arange(V, dtype=np.int32)[None, :])
+    assert out["logprob"][0] == pytest.approx(-math.log(2.0) * lengths(m["path_off"]), abs=1e-13)
+
+
+def test_two_words_is_one_sigmoid():
+    m = {"U": np.zeros((2, 2), np.float32), "W": np.zeros((2, 2), np.float32),
+         "theta": np.array([[1.5, -0.5]], np.float32)}
+    m["path_off"], m["path_entry"] = oracle.huffman_build([1.0, 3.0])      # word 0 lighter: code bit 0
+    out = oracle.hs_step(m, [0], [[0.2, 0.9]], [[0, 1]])
+    x = 0.5 * 1.5 - 0.5 * 0.5                                              # h' = sigmoid(0) = 1/2 each
+    assert out["logprob"][0] == pytest.approx([math.log(scipy.special.expit(x)), math.log(scipy.special.expit(-x))],
+                                              abs=1e-15)
+
+
+@pytest.mark.parametrize("V,H,B,K", [(5, 2, 2, 5), (33, 7, 4, 6)])
+def test_against_pure_python(V, H, B, K):
+    rng = np.random.default_rng(V + H)
+    m = rand_model(rng, V, H)
+    prev = rng.integers(0, V, B)
+    h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
+    N = B + 3
+    roq = rng.integers(0, B, N).astype(np.int32)
+    query = rng.integers(0, V, (N, K)).astype(np.int32)
+    out = oracle.hs_step(m, prev, h_in, query, row_of_query=roq)
+    for n in range(N):
+        b = int(roq[n])
+        hp = [1.0 / (1.0 + math.exp(-(float(m["U"][prev[b], j]) + sum(float(m["W"][j, i]) * float(h_in[b, i]) for i in range(H)))))
+              for j in range(H)]
+        for k in range(K):
+            w = int(query[n, k])
+            p = 1.0
+            for e in m["path_entry"][m["path_off"][w]:m["path_off"][w + 1]]:
+                node, bitv = int(e) & 0x7FFFFFFF, (int(e) >> 31) & 1
+                x = sum(float(m["theta"][node, j]) * hp[j] for j in range(H))
+                p *= 1.0 / (1.0 + math.exp(x if bitv else -x))
+            assert out["logprob"][n, k] == pytest.approx(math.log(p), abs=1e-12)
+
+
+def test_extreme_activations_stay_finite():
+    rng = np.random.default_rng(4)
+    m = rand_model(rng, 9, 3)
+    m["theta"] *= 400.0
+    out = oracle.hs_step(m, [1], [[0.3, 0.3, 0.3]], np.arange(9, dtype=np.int32)[None, :], want_full=True)
+    assert np.all(np.isfinite(out["logprob"])) and np.exp(out["full_logp"]).sum() == pytest.approx(1.0, abs=1e-12)
