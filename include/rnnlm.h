@@ -13,10 +13,10 @@
  *     where stated; nothing throws or aborts.
  *   - rnnlm_load takes HOST pointers and copies; the caller keeps its buffers.
  *   - rnnlm_dedup / rnnlm_step / rnnlm_step_dedup / rnnlm_step_cached / rnnlm_pack_ids /
- *     rnnlm_index_intern / rnnlm_index_fetch take
+ *     rnnlm_index_intern / rnnlm_index_fetch / rnnlm_hs_step take
  *     DEVICE pointers owned by the caller and are asynchronous on `hip_stream` (a
  *     hipStream_t passed as void*; NULL = the default stream).  No call here synchronises,
- *     allocates or frees device memory except rnnlm_load, rnnlm_free, rnnlm_last_error,
+ *     allocates or frees device memory except rnnlm_load, rnnlm_hs_load, rnnlm_free, rnnlm_last_error,
  *     rnnlm_cache_create, rnnlm_cache_free, rnnlm_cache_stats, rnnlm_index_create,
  *     rnnlm_index_free and rnnlm_index_stats.
  *   - float / int32 / uint64 arrays are dense, row-major, naturally aligned; `h_in` and
@@ -213,6 +213,43 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache_or_null, int 
                       int32_t *rep, int32_t *inverse, int32_t *n_unique,
                       float *h_out, float *score, int32_t *step_stats_or_null,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * ---- Hierarchical output layer (Section 2.1) ----------------------------------------------
+ *
+ * The paper's own output layer: the words are the leaves of a Huffman tree and the probability
+ * of a word is normalised only over the nodes on its path from the root,
+ *     log p(w | h') = sum over the path nodes i of log sigmoid(+-theta_i . h'),
+ * + for code bit 0, - for code bit 1: about log2 V dot products per queried word, no
+ * whole-vocabulary normalisation.  A model loaded with rnnlm_hs_load is stepped with
+ * rnnlm_hs_step (and refused by the full-softmax entry points, and the other way round).
+ */
+
+/* Huffman tree over V >= 2 words from their frequencies (HOST arrays, host code): the path of
+ * word v from the root down is path_entry[path_offset[v] .. path_offset[v+1]), each entry =
+ * inner node (0 .. V-2, numbered in order of creation, the root is V-2) | code bit << 31.
+ * Two-queue construction; of two equal weights a word goes before an inner node, words of
+ * equal frequency in order of their id; the first of a merged pair gets code bit 0.
+ *   path_offset  out i32[V+1]
+ *   path_entry   out i32[capacity], may be NULL to ask for the size only
+ *   needed       out, may be NULL: number of entries
+ * Returns RNNLM_ERANGE (offsets and *needed valid) when capacity is too small. */
+int rnnlm_huffman_build(int V, const double *frequency, int32_t *path_offset, int32_t *path_entry,
+                        size_t capacity, size_t *needed);
+
+/* Load a model with the hierarchical output layer.  U, W, dtype, max_B as rnnlm_load;
+ *   Theta        [V-1][H]  vector of every inner node, same element type as U and W
+ *   path_offset  i32[V+1], path_entry i32[path_offset[V]]  the tree, as rnnlm_huffman_build
+ *                writes it (checked: non-empty paths, node ids below V-1)
+ * All HOST pointers.  Synchronous. */
+int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const void *Theta,
+                  const int32_t *path_offset, const int32_t *path_entry, int max_B, rnnlm_model **out);
+
+/* rnnlm_step with the hierarchical output layer; arguments as rnnlm_step, plus base_score
+ * (dev f32[N][K] or NULL) as in rnnlm_step_cached. */
+int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word, const float *h_in,
+                  const int32_t *query_word, const int32_t *row_of_query_or_null, int N,
+                  const float *base_score_or_null, float *h_out, float *logprob, void *hip_stream);
 
 /*
  * ---- IndexTable and its inverse on the device (Section 3.2; Table 1 steps 5 and 7-12) -------

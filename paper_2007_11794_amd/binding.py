@@ -26,7 +26,7 @@ EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rn
            "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
            "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
            "rnnlm_index_free", "rnnlm_index_reset", "rnnlm_index_intern", "rnnlm_index_fetch",
-           "rnnlm_index_stats"]
+           "rnnlm_index_stats", "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step"]
 
 
 class RnnlmError(RuntimeError):
@@ -80,6 +80,12 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_step_cached.restype = I
         L.rnnlm_pack_ids.argtypes = [P, P, I, P, P]
         L.rnnlm_pack_ids.restype = I
+        L.rnnlm_huffman_build.argtypes = [I, P, P, P, Z, ctypes.POINTER(Z)]
+        L.rnnlm_huffman_build.restype = I
+        L.rnnlm_hs_load.argtypes = [I, I, I, P, P, P, P, P, I, ctypes.POINTER(P)]
+        L.rnnlm_hs_load.restype = I
+        L.rnnlm_hs_step.argtypes = [P, I, I, P, P, P, P, I, P, P, P, P]
+        L.rnnlm_hs_step.restype = I
         L.rnnlm_index_create.argtypes = [I, I, I, ctypes.POINTER(P)]
         L.rnnlm_index_create.restype = I
         L.rnnlm_index_free.argtypes = [P]
@@ -373,3 +379,53 @@ def rnnlm_index_fetch(table: RnnlmIndexTable, index, word, h, stream=None):
         raise TypeError("shape mismatch")
     _check(lib().rnnlm_index_fetch(table.handle, N, _dev(index, torch.int32, "index"), _dev(word, torch.int32, "word"),
                                    _dev(h, torch.float32, "h"), _stream(stream)), "rnnlm_index_fetch")
+
+
+def rnnlm_huffman_build(frequency: np.ndarray):
+    """Host-side Huffman tree over the words: returns (path_offset i32[V+1], path_entry i32[total])."""
+    f = np.ascontiguousarray(frequency, dtype=np.float64)
+    V = int(f.shape[0])
+    off = np.zeros(V + 1, dtype=np.int32)
+    need = ctypes.c_size_t(0)
+    st = lib().rnnlm_huffman_build(V, f.ctypes.data, off.ctypes.data, None, 0, ctypes.byref(need))
+    if st not in (0, -4):
+        _check(st, "rnnlm_huffman_build")
+    entry = np.zeros(max(need.value, 1), dtype=np.int32)
+    _check(lib().rnnlm_huffman_build(V, f.ctypes.data, off.ctypes.data, entry.ctypes.data, need.value,
+                                     ctypes.byref(need)), "rnnlm_huffman_build")
+    return off, entry[:need.value]
+
+
+def rnnlm_hs_load(V: int, H: int, dtype: int, U: np.ndarray, W: np.ndarray, Theta: np.ndarray,
+                  path_offset: np.ndarray, path_entry: np.ndarray, max_B: int) -> RnnlmModel:
+    want = np.float32 if dtype == RNNLM_F32 else np.uint16
+    arrs = []
+    for name, a, shape in (("U", U, (V, H)), ("W", W, (H, H)), ("Theta", Theta, (V - 1, H))):
+        a = np.ascontiguousarray(a)
+        if a.dtype != want or a.shape != shape:
+            raise TypeError("%s must be %s of shape %s" % (name, want.__name__, shape))
+        arrs.append(a)
+    off = np.ascontiguousarray(path_offset, dtype=np.int32)
+    ent = np.ascontiguousarray(path_entry, dtype=np.int32)
+    if off.shape != (V + 1,) or ent.shape != (int(off[-1]),):
+        raise TypeError("path arrays have the wrong size")
+    out = ctypes.c_void_p()
+    _check(lib().rnnlm_hs_load(V, H, dtype, arrs[0].ctypes.data, arrs[1].ctypes.data, arrs[2].ctypes.data,
+                               off.ctypes.data, ent.ctypes.data, int(max_B), ctypes.byref(out)), "rnnlm_hs_load")
+    return RnnlmModel(out.value, V, H, dtype, int(max_B))
+
+
+def rnnlm_hs_step(model: RnnlmModel, prev_word, h_in, query_word, h_out, logprob, row_of_query=None,
+                  base_score=None, stream=None):
+    import torch
+    B = int(prev_word.shape[0])
+    N = int(query_word.shape[0])
+    K = int(query_word.shape[1]) if query_word.dim() == 2 else 0
+    if h_in.shape != (B, model.H) or h_out.shape != (B, model.H) or logprob.shape != (N, K):
+        raise TypeError("shape mismatch")
+    _check(lib().rnnlm_hs_step(model.handle, B, K, _dev(prev_word, torch.int32, "prev_word"),
+                               _dev(h_in, torch.float32, "h_in"), _dev(query_word, torch.int32, "query_word"),
+                               _dev(row_of_query, torch.int32, "row_of_query"), N,
+                               _dev(base_score, torch.float32, "base_score"),
+                               _dev(h_out, torch.float32, "h_out"), _dev(logprob, torch.float32, "logprob"),
+                               _stream(stream)), "rnnlm_hs_step")

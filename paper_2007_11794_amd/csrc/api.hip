@@ -45,6 +45,9 @@ void free_dev(rnnlm_model *m) {
     (void)hipFree(d.dfrag);
     (void)hipFree(d.part);
     (void)hipFree(d.flag);
+    (void)hipFree(const_cast<void *>(d.Theta));
+    (void)hipFree(const_cast<int32_t *>(d.path_off));
+    (void)hipFree(const_cast<int32_t *>(d.path_entry));
     if (m->ev0) (void)hipEventDestroy(m->ev0);
     if (m->ev1) (void)hipEventDestroy(m->ev1);
 }
@@ -59,8 +62,47 @@ double widen_host(const void *p, size_t i, int dtype) {
     return (double)static_cast<const float *>(p)[i];
 }
 
-int check_step_args(const rnnlm_model *model, int B, int K, int N) {
+// Device copies of what the hidden update needs (U, W zero-padded to Hp, half row sums of W,
+// the scratch blocks, the flag, the events).  On failure the caller releases with free_dev.
+int upload_recurrent(rnnlm_model *m, int V, int H, int Hp, int dtype, const void *U, const void *W, int max_Bp) {
+    int status = RNNLM_OK;
+    const size_t es = elem_size(dtype);
+    ModelDev &d = m->dev;
+    std::vector<float> hrs;
+    void *p;
+    HIP_TRY(hipMalloc(&p, (size_t)V * Hp * es)); d.U = p;
+    HIP_TRY(hipMalloc(&p, (size_t)Hp * Hp * es)); d.W = p;
+    HIP_TRY(hipMalloc(&p, (size_t)Hp * 4)); d.half_rowsum_W = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.d = p;
+    HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
+    HIP_TRY(hipMemset(d.d, 0, (size_t)max_Bp * Hp * es));
+    if (dtype == RNNLM_BF16) {
+        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.dfrag = p;
+        HIP_TRY(hipMemset(d.dfrag, 0, (size_t)max_Bp * Hp * es));
+    }
+    HIP_TRY(hipMemset(d.flag, 0, 4));
+    HIP_TRY(hipEventCreate(&m->ev0));
+    HIP_TRY(hipEventCreate(&m->ev1));
+    HIP_TRY(hipMemset(const_cast<void *>(d.U), 0, (size_t)V * Hp * es));
+    HIP_TRY(hipMemset(const_cast<void *>(d.W), 0, (size_t)Hp * Hp * es));
+    HIP_TRY(hipMemcpy2D(const_cast<void *>(d.U), Hp * es, U, H * es, H * es, V, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy2D(const_cast<void *>(d.W), Hp * es, W, H * es, H * es, H, hipMemcpyHostToDevice));
+    // half row sums of W in fp64 on the host (H*H elements)
+    hrs.assign(Hp, 0.f);
+    for (int j = 0; j < H; ++j) {
+        double sum = 0.0;
+        for (int i = 0; i < H; ++i) sum += widen_host(W, (size_t)j * H + i, dtype);
+        hrs[j] = (float)(0.5 * sum);
+    }
+    HIP_TRY(hipMemcpy(const_cast<float *>(d.half_rowsum_W), hrs.data(), (size_t)Hp * 4, hipMemcpyHostToDevice));
+    return RNNLM_OK;
+fail:
+    return status;
+}
+
+int check_step_args(const rnnlm_model *model, int B, int K, int N, int hs = 0) {
     if (!model) return RNNLM_EINVAL;
+    if (model->dev.hs != hs) return RNNLM_EINVAL;       // full-softmax and hierarchical models have their own steps
     if (B < 0 || K < 0 || N < 0) return RNNLM_EINVAL;
     if (B > model->max_B || N > model->max_B) return RNNLM_ERANGE;
     return RNNLM_OK;
@@ -104,45 +146,19 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     m->max_B = max_B; m->max_Bp = max_Bp;
     void *O_stage = nullptr;
     float *bias_stage = nullptr, *upper = nullptr, *lower = nullptr;
-    std::vector<float> hu, hl, hrs;
+    std::vector<float> hu, hl;
     float max_upper = -INFINITY, min_lower = INFINITY;
 
     void *p;
-    HIP_TRY(hipMalloc(&p, (size_t)V * Hp * es)); d.U = p;
-    HIP_TRY(hipMalloc(&p, (size_t)Hp * Hp * es)); d.W = p;
+    status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp);
+    if (status != RNNLM_OK) goto fail;
     HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * es)); d.Ot = p;
-    HIP_TRY(hipMalloc(&p, (size_t)Hp * 4)); d.half_rowsum_W = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.bias = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.half_colsum_O = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec2 = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec2_fixed = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.d = p;
     HIP_TRY(hipMalloc(&p, (size_t)max_Bp * kMaxSplits * sizeof(float2))); d.part = static_cast<float2 *>(p);
-    HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
-    HIP_TRY(hipMemset(d.d, 0, (size_t)max_Bp * Hp * es));
-    if (dtype == RNNLM_BF16) {
-        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.dfrag = p;
-        HIP_TRY(hipMemset(d.dfrag, 0, (size_t)max_Bp * Hp * es));
-    }
     HIP_TRY(hipMemset(d.part, 0, (size_t)max_Bp * kMaxSplits * sizeof(float2)));
-    HIP_TRY(hipMemset(d.flag, 0, 4));
-    HIP_TRY(hipEventCreate(&m->ev0));
-    HIP_TRY(hipEventCreate(&m->ev1));
-
-    // U and W: zero-padded to Hp columns (and W to Hp rows)
-    HIP_TRY(hipMemset(const_cast<void *>(d.U), 0, (size_t)V * Hp * es));
-    HIP_TRY(hipMemset(const_cast<void *>(d.W), 0, (size_t)Hp * Hp * es));
-    HIP_TRY(hipMemcpy2D(const_cast<void *>(d.U), Hp * es, U, H * es, H * es, V, hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy2D(const_cast<void *>(d.W), Hp * es, W, H * es, H * es, H, hipMemcpyHostToDevice));
-
-    // half row sums of W in fp64 on the host (H*H elements)
-    hrs.assign(Hp, 0.f);
-    for (int j = 0; j < H; ++j) {
-        double s = 0.0;
-        for (int i = 0; i < H; ++i) s += widen_host(W, (size_t)j * H + i, dtype);
-        hrs[j] = (float)(0.5 * s);
-    }
-    HIP_TRY(hipMemcpy(const_cast<float *>(d.half_rowsum_W), hrs.data(), (size_t)Hp * 4, hipMemcpyHostToDevice));
 
     // O: upload as given, transpose + pad on the device, column statistics
     HIP_TRY(hipMalloc(&O_stage, (size_t)H * V * es));
@@ -200,11 +216,12 @@ int rnnlm_set_option(rnnlm_model *model, int option, int value) {
     switch (option) {
         case RNNLM_OPT_LSE_MODE:
             if (value < 0 || value > 2) return RNNLM_EINVAL;
-            if (value == 2 && !model->fixed_ok) return RNNLM_EINVAL;
+            if (model->dev.hs || (value == 2 && !model->fixed_ok)) return RNNLM_EINVAL;
             model->lse_mode = value;
             return RNNLM_OK;
         case RNNLM_OPT_OUTPROJ_KERNEL:
             if (value < 0 || value > 3) return RNNLM_EINVAL;
+            if (model->dev.hs) return RNNLM_EINVAL;
             if (value == 2 && !outproj_staged_supported(model->dev)) return RNNLM_EINVAL;
             model->outproj_kernel = value;
             return RNNLM_OK;
@@ -387,6 +404,71 @@ int rnnlm_cache_stats(rnnlm_cache *cache, void *hip_stream, int64_t out[5]) {
     return RNNLM_OK;
 }
 
+int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const void *Theta,
+                  const int32_t *path_offset, const int32_t *path_entry, int max_B, rnnlm_model **out) {
+    if (!out) return RNNLM_EINVAL;
+    *out = nullptr;
+    if (!U || !W || !Theta || !path_offset || !path_entry) return RNNLM_EINVAL;
+    if (V < 2 || H <= 0 || max_B <= 0) return RNNLM_EINVAL;
+    if (dtype != RNNLM_F32 && dtype != RNNLM_BF16) return RNNLM_EINVAL;
+    if ((long long)V > (1ll << 30) || H > (1 << 16) || max_B > (1 << 24)) return RNNLM_EINVAL;
+    // the tree is walked on the device without further checks: every path must be non-empty
+    // and name inner nodes only
+    if (path_offset[0] != 0) return RNNLM_EINVAL;
+    for (int v = 0; v < V; ++v)
+        if (path_offset[v + 1] <= path_offset[v]) return RNNLM_EINVAL;
+    const size_t entries = (size_t)path_offset[V];
+    for (size_t e = 0; e < entries; ++e)
+        if (((uint32_t)path_entry[e] & 0x7FFFFFFFu) >= (uint32_t)(V - 1)) return RNNLM_EINVAL;
+
+    rnnlm_model *m = new (std::nothrow) rnnlm_model();
+    if (!m) return RNNLM_ENOMEM;
+    memset(m, 0, sizeof(*m));
+    int status = RNNLM_OK;
+    const size_t es = elem_size(dtype);
+    const int Hp = (dtype == RNNLM_BF16 && H < 128) ? 128 : round_up(H, 64);
+    const int max_Bp = round_up(max_B, 256);
+    ModelDev &d = m->dev;
+    d.V = V; d.H = H; d.Hp = Hp; d.Vp = round_up(V, 256); d.dtype = dtype; d.hs = 1;
+    m->max_B = max_B; m->max_Bp = max_Bp;
+    void *p;
+    status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp);
+    if (status != RNNLM_OK) goto fail;
+    HIP_TRY(hipMalloc(&p, (size_t)(V - 1) * Hp * es)); d.Theta = p;
+    HIP_TRY(hipMemset(p, 0, (size_t)(V - 1) * Hp * es));
+    HIP_TRY(hipMemcpy2D(p, Hp * es, Theta, H * es, H * es, V - 1, hipMemcpyHostToDevice));
+    HIP_TRY(hipMalloc(&p, ((size_t)V + 1) * 4)); d.path_off = static_cast<int32_t *>(p);
+    HIP_TRY(hipMemcpy(p, path_offset, ((size_t)V + 1) * 4, hipMemcpyHostToDevice));
+    HIP_TRY(hipMalloc(&p, entries * 4)); d.path_entry = static_cast<int32_t *>(p);
+    HIP_TRY(hipMemcpy(p, path_entry, entries * 4, hipMemcpyHostToDevice));
+    HIP_TRY(hipDeviceSynchronize());
+    *out = m;
+    return RNNLM_OK;
+fail:
+    free_dev(m);
+    delete m;
+    (void)hipGetLastError();
+    return status;
+}
+
+int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word, const float *h_in,
+                  const int32_t *query_word, const int32_t *row_of_query_or_null, int N,
+                  const float *base_score_or_null, float *h_out, float *logprob, void *hip_stream) {
+    int rc = check_step_args(model, B, K, N, 1);
+    if (rc != RNNLM_OK) return rc;
+    if (B > 0 && (!prev_word || !h_in || !h_out)) return RNNLM_EINVAL;
+    if (N > 0 && K > 0 && (!query_word || !logprob)) return RNNLM_EINVAL;
+    if (!row_of_query_or_null && N != B) return RNNLM_EINVAL;
+    if (B > 0 && h_out == h_in) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const ModelDev &d = model->dev;
+    if (launch_recur(d, B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_hs_query(d, B, nullptr, N, K, query_word, row_of_query_or_null, h_out, base_score_or_null, logprob,
+                        s) != hipSuccess)
+        return RNNLM_EDEVICE;
+    return RNNLM_OK;
+}
+
 int rnnlm_index_create(int H, int capacity, int max_N, rnnlm_index_table **out) {
     if (!out) return RNNLM_EINVAL;
     *out = nullptr;
@@ -503,7 +585,7 @@ int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N,
 }
 
 int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream, float *ms_per_launch) {
-    if (!model || !ms_per_launch || repeats <= 0 || B <= 0) return RNNLM_EINVAL;
+    if (!model || !ms_per_launch || repeats <= 0 || B <= 0 || model->dev.hs) return RNNLM_EINVAL;
     if (B > model->max_B) return RNNLM_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     SplitInfo splits = {1, 0};

@@ -193,6 +193,31 @@ __device__ __forceinline__ float lse_from_partials(const float2 *part_row, int s
     return (mm + fast_log2(ss)) * 0.6931471805599453f;
 }
 
+// Batches of eight dot products per wave (query gather, hierarchical output layer): value u
+// of a batch is finished by the lanes whose bits (5, 4, 3) spell u.
+__device__ __forceinline__ int batch_slot_of_lane(int lane) {
+    return ((lane >> 5) & 1) * 4 + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+}
+constexpr int lane_of_batch_slot(int u) { return 32 * ((u >> 2) & 1) + 16 * ((u >> 1) & 1) + 8 * (u & 1); }
+
+// Sums over the wave of eight per-lane values at once: the same xor butterfly (32, 16, ...,
+// 1) as wave_sum, but in the first three levels a lane passes on the half of the values it
+// will not finish, so 10 exchanges do the work of 48.  Returns the sum of value
+// batch_slot_of_lane(lane); bit-identical to wave_sum of that value.
+__device__ __forceinline__ float wave_sum8(const float (&acc)[8], int lane) {
+    float v4[4], v2[2];
+    const bool up5 = (lane & 32) != 0, up4 = (lane & 16) != 0, up3 = (lane & 8) != 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v4[i] = (up5 ? acc[4 + i] : acc[i]) + __shfl_xor(up5 ? acc[i] : acc[4 + i], 32, 64);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) v2[i] = (up4 ? v4[2 + i] : v4[i]) + __shfl_xor(up4 ? v4[i] : v4[2 + i], 16, 64);
+    float v = (up3 ? v2[1] : v2[0]) + __shfl_xor(up3 ? v2[0] : v2[1], 8, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 1, 64);
+    return v;
+}
+
 __device__ __forceinline__ float quiet_nan() { return __uint_as_float(0x7FC00000u); }
 
 }  // namespace rnnlm

@@ -1,0 +1,171 @@
+// Hierarchical output layer (Section 2.1 of the paper): the words are the leaves of a Huffman
+// tree, and the probability of a word is normalised only over the nodes on its path from the
+// root: log p(w | h') = sum over the path nodes i of log sigmoid(+-theta_i . h'), + for code bit
+// 0, - for code bit 1.  About log2 V dot products per queried word instead of V per row: the
+// whole-vocabulary contraction of the full softmax disappears, what is left is a gather of node
+// vectors (one contiguous row each), bound by L2 / HBM traffic.
+//
+// One wave per (query, word) pair, eight path nodes at a time: the eight node rows are requested
+// together, the eight dot products are reduced over the wave at once, and the lane that ends up
+// with node u turns its dot product into log sigmoid.  The tree comes with the model
+// (rnnlm_hs_load); rnnlm_huffman_build below makes one from word frequencies on the host.
+#include <algorithm>
+#include <numeric>
+#include <vector>
+
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+namespace {
+
+constexpr int kHsBatch = 8;
+
+// log sigmoid(x) = min(x, 0) - log(1 + exp(-|x|))
+__device__ __forceinline__ float log_sigmoid_f32(float x) {
+    const float t = fast_exp2(-fabsf(x) * kLog2e);
+    return fminf(x, 0.f) - fast_log2(1.0f + t) * kLn2;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void hs_query_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K,
+    const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
+    const float *__restrict__ h_out, const float *__restrict__ base_score, float *__restrict__ logprob) {
+    const int B = B_dev ? *B_dev : rows;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long pair = (long long)blockIdx.x * 4 + wave;
+    if (pair >= (long long)N * K) return;                // wave-uniform; no barrier in this kernel
+    const int n = (int)(pair / K);
+    const int H = m.H, Hp = m.Hp;
+    const int r_raw = row_of_query ? row_of_query[n] : n;
+    const bool r_ok = r_raw >= 0 && r_raw < B;
+    const int r = r_ok ? r_raw : 0;
+    const int q_raw = query_word[pair];
+    const bool q_ok = q_raw >= 0 && q_raw < m.V;
+    const int q = q_ok ? q_raw : 0;
+    const int off0 = m.path_off[q], len = m.path_off[q + 1] - off0;      // wave-uniform
+    const T *Theta = static_cast<const T *>(m.Theta);
+    const float *hrow = h_out + (size_t)r * H;
+    const bool vec_ok = (H % 4) == 0;
+    const int umine = batch_slot_of_lane(lane);
+    float total = 0.f;
+    for (int i0 = 0; i0 < len; i0 += kHsBatch) {
+        const bool valid = i0 + umine < len;
+        const uint32_t entry = valid ? (uint32_t)m.path_entry[off0 + i0 + umine] : 0u;
+        const int node_mine = (int)(entry & 0x7FFFFFFFu);
+        int node[kHsBatch];
+#pragma unroll
+        for (int u = 0; u < kHsBatch; ++u) node[u] = __builtin_amdgcn_readlane(node_mine, lane_of_batch_slot(u));
+        float acc[kHsBatch];
+#pragma unroll
+        for (int u = 0; u < kHsBatch; ++u) acc[u] = 0.f;
+        for (int j0 = lane * 8; j0 < Hp; j0 += 512) {
+            float h8[8];
+            load8_row(hrow, j0, H, vec_ok, 0.f, h8);
+            float w8[kHsBatch][8];
+#pragma unroll
+            for (int u = 0; u < kHsBatch; ++u) load8_weights(Theta, (size_t)node[u] * Hp + j0, w8[u]);
+#pragma unroll
+            for (int u = 0; u < kHsBatch; ++u)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[u] = fmaf(w8[u][i], h8[i], acc[u]);
+        }
+        const float x = wave_sum8(acc, lane);
+        float term = valid ? log_sigmoid_f32((entry >> 31) ? -x : x) : 0.f;
+        term += __shfl_xor(term, 32, 64);                // the eight slots differ in lane bits 5, 4, 3
+        term += __shfl_xor(term, 16, 64);
+        term += __shfl_xor(term, 8, 64);
+        total += term;
+    }
+    if (lane == 0) {
+        if (r_ok && q_ok) {
+            logprob[pair] = base_score ? total - base_score[pair] : total;
+        } else {
+            atomicOr(m.flag, r_ok ? RNNLM_FLAG_BAD_QUERY_WORD : RNNLM_FLAG_BAD_ROW);
+            logprob[pair] = quiet_nan();
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_hs_query(const ModelDev &m, int rows, const int *B_dev, int N, int K,
+                           const int32_t *query_word, const int32_t *row_of_query, const float *h_out,
+                           const float *base_score, float *logprob, hipStream_t stream) {
+    if (N <= 0 || K <= 0) return hipSuccess;
+    const long long pairs = (long long)N * K;
+    const dim3 grid((unsigned)((pairs + 3) / 4));
+    if (m.dtype == RNNLM_BF16)
+        hipLaunchKernelGGL(hs_query_kernel<bf16_t>, grid, dim3(256), 0, stream, m, rows, B_dev, N, K, query_word,
+                           row_of_query, h_out, base_score, logprob);
+    else
+        hipLaunchKernelGGL(hs_query_kernel<float>, grid, dim3(256), 0, stream, m, rows, B_dev, N, K, query_word,
+                           row_of_query, h_out, base_score, logprob);
+    return hipGetLastError();
+}
+
+}  // namespace rnnlm
+
+// Huffman's method with two queues (host code): the words sorted by (frequency, id) ascending,
+// and the inner nodes in order of creation, whose weights never decrease.  Every merge takes
+// the two lightest queue heads, a word before an inner node of equal weight; the first taken is
+// the child with code bit 0.  Inner nodes are numbered in order of creation, the root is V - 2.
+extern "C" int rnnlm_huffman_build(int V, const double *frequency, int32_t *path_offset, int32_t *path_entry,
+                                   size_t capacity, size_t *needed) {
+    if (V < 2 || !frequency || !path_offset) return RNNLM_EINVAL;
+    if (V > (1 << 30)) return RNNLM_ERANGE;
+    for (int v = 0; v < V; ++v)
+        if (!(frequency[v] >= 0.0)) return RNNLM_EINVAL;
+    std::vector<int32_t> order, up;          // words by weight; parent of word v / of inner node V + i
+    std::vector<double> weight;              // of the inner nodes
+    std::vector<uint8_t> code;
+    try {
+        order.resize(V);
+        up.assign(2 * (size_t)V - 1, -1);
+        code.assign(2 * (size_t)V - 1, 0);
+        weight.resize(V - 1);
+    } catch (...) {
+        return RNNLM_ENOMEM;
+    }
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        return frequency[a] < frequency[b] || (frequency[a] == frequency[b] && a < b);
+    });
+    size_t next_word = 0, next_inner = 0;
+    for (int created = 0; created < V - 1; ++created) {
+        double sum = 0.0;
+        for (int side = 0; side < 2; ++side) {
+            const bool words_left = next_word < (size_t)V, inner_left = next_inner < (size_t)created;
+            const bool take_word = words_left && (!inner_left || frequency[order[next_word]] <= weight[next_inner]);
+            size_t child;
+            if (take_word) {
+                child = (size_t)order[next_word];
+                sum += frequency[order[next_word++]];
+            } else {
+                child = (size_t)V + next_inner;
+                sum += weight[next_inner++];
+            }
+            up[child] = V + created;
+            code[child] = (uint8_t)side;
+        }
+        weight[created] = sum;
+    }
+    size_t total = 0;
+    for (int v = 0; v < V; ++v) {
+        size_t depth = 0;
+        for (int32_t x = v; up[x] >= 0; x = up[x]) ++depth;
+        path_offset[v] = (int32_t)total;
+        if (path_entry && total + depth <= capacity) {
+            size_t at = total + depth;
+            for (int32_t x = v; up[x] >= 0; x = up[x])
+                path_entry[--at] = (int32_t)((uint32_t)(up[x] - V) | ((uint32_t)code[x] << 31));
+        }
+        total += depth;
+        if (total > 0x7FFFFFFFull) return RNNLM_ERANGE;
+    }
+    path_offset[V] = (int32_t)total;
+    if (needed) *needed = total;
+    return (path_entry && total <= capacity) ? RNNLM_OK : RNNLM_ERANGE;
+}

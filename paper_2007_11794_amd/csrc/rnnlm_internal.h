@@ -32,6 +32,11 @@ struct ModelDev {
     const float *cvec2;           // [Vp]
     const float *cvec2_fixed;     // [Vp]  cvec2 - m2_fixed
     float m2_fixed;    // upper bound of every base-2 logit z*log2(e), valid because |h' - 0.5| <= 0.5
+    // hierarchical output layer (models loaded with rnnlm_hs_load; Ot .. cvec2_fixed are null then)
+    int hs;                       // 1: hierarchical
+    const void *Theta;            // [V-1][Hp] node vectors, weights' type, zero-padded
+    const int32_t *path_off;      // [V+1]
+    const int32_t *path_entry;    // [path_off[V]] node | code bit << 31, root first
     // scratch
     void *d;           // [max_Bp][Hp]  h' - 0.5 in the weights' type
     // bf16 models: the same block once more in the order the staged output projection reads
@@ -177,6 +182,11 @@ hipError_t launch_index_commit(const IndexDev &t, int N, const int32_t *word, co
                                hipStream_t stream);
 hipError_t launch_index_fetch(const IndexDev &t, int N, const uint32_t *index, int32_t *word, float *h,
                               hipStream_t stream);
+// Hierarchical output layer: logprob[n][k] = sum over the path of query[n][k] of
+// log sigmoid(+-theta_node . h'[row(n)]) (- base_score[n][k]).
+hipError_t launch_hs_query(const ModelDev &m, int rows, const int *B_dev, int N, int K,
+                           const int32_t *query_word, const int32_t *row_of_query, const float *h_out,
+                           const float *base_score, float *logprob, hipStream_t stream);
 hipError_t launch_pack_ids(const uint32_t *ctx, const uint32_t *small_lm, int N, uint64_t *ids,
                            hipStream_t stream);
 

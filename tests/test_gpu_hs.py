@@ -1,0 +1,128 @@
+"""GPU tests of the hierarchical output layer (rnnlm_hs_load / rnnlm_hs_step) against the oracle,
+through the C ABI.  Bars as for the full softmax: bf16 |dlogprob| <= 2e-3, |dh| <= 1e-3; fp32
+1e-5."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2007_11794_amd as rn
+from workloads import CONFIGS, bf16_bits, bounded_zipf_ids, round_to_bf16
+
+from harness import DEV
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (2e-3, 1e-3)}
+
+
+def hs_model(rng, V, H, dtype, sigma, zipf_s=1.1):
+    freq = np.arange(1, V + 1, dtype=np.float64) ** -zipf_s
+    off, entry = oracle.huffman_build(freq)
+    m = {"U": rng.normal(0, sigma, (V, H)).astype(np.float32), "W": rng.normal(0, sigma, (H, H)).astype(np.float32),
+         "theta": rng.normal(0, 4 * sigma, (V - 1, H)).astype(np.float32), "path_off": off, "path_entry": entry}
+    if dtype == "bf16":
+        for k in ("U", "W", "theta"):
+            m[k] = round_to_bf16(m[k])
+    return m
+
+
+def load(m, dtype, max_B):
+    V, H = m["U"].shape
+    if dtype == "bf16":
+        return rn.rnnlm_hs_load(V, H, rn.RNNLM_BF16, bf16_bits(m["U"]), bf16_bits(m["W"]), bf16_bits(m["theta"]),
+                                m["path_off"], m["path_entry"], max_B)
+    return rn.rnnlm_hs_load(V, H, rn.RNNLM_F32, m["U"], m["W"], m["theta"], m["path_off"], m["path_entry"], max_B)
+
+
+def gpu_hs_step(mod, prev, h_in, query, row_of_query=None, base=None):
+    t = lambda a, d: None if a is None else torch.from_numpy(np.ascontiguousarray(a, d)).to(DEV)
+    prev_t, h_t, q_t = t(prev, np.int32), t(h_in, np.float32), t(query, np.int32)
+    B, (N, K) = prev_t.shape[0], q_t.shape
+    h_out = torch.full((B, mod.H), float("nan"), device=DEV)
+    lp = torch.full((N, K), float("nan"), device=DEV)
+    rn.rnnlm_hs_step(mod, prev_t, h_t, q_t, h_out, lp, row_of_query=t(row_of_query, np.int32), base_score=t(base, np.float32))
+    torch.cuda.synchronize()
+    return h_out.cpu().numpy(), lp.cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype,V,H,B,K,N", [
+    ("bf16", 5000, 512, 300, 8, 300),
+    ("bf16", 4099, 160, 77, 5, 200),         # padded hidden size, fan-out through row_of_query
+    ("bf16", 2, 64, 5, 2, 5),                # the smallest tree
+    ("f32", 3001, 96, 64, 9, 64),
+    ("f32", 20000, 256, 256, 16, 256),       # config 2's shape
+])
+def test_hs_step_matches_the_oracle(dtype, V, H, B, K, N):
+    rng = np.random.default_rng(V + H)
+    m = hs_model(rng, V, H, dtype, 0.05)
+    mod = load(m, dtype, max(B, N))
+    prev = rng.integers(0, V, B).astype(np.int32)
+    h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
+    query = bounded_zipf_ids(rng, V, 1.1, (N, K)).astype(np.int32) if V > 100 else rng.integers(0, V, (N, K)).astype(np.int32)
+    query[0, 0] = V - 1                                         # a rare word: one of the longest paths
+    roq = None if N == B else rng.integers(0, B, N).astype(np.int32)
+    base = rng.normal(-5, 2, (N, K)).astype(np.float32)
+    ref = oracle.hs_step(m, prev, h_in, query, row_of_query=roq)
+    for use_base in (False, True):
+        h, lp = gpu_hs_step(mod, prev, h_in, query, roq, base if use_base else None)
+        want = ref["logprob"] - (base.astype(np.float64) if use_base else 0.0)
+        dh, dlp = np.max(np.abs(h - ref["h_out"])), np.max(np.abs(lp - want))
+        print("hs %s V=%d H=%d max|dh|=%.3g max|dlogprob|=%.3g longest path %d" %
+              (dtype, V, H, dh, dlp, int(np.diff(m["path_off"]).max())), flush=True)
+        assert dh <= TOL[dtype][1] and dlp <= TOL[dtype][0]
+    assert mod.last_error() == 0
+    mod.close()
+
+
+def test_hs_bad_indices_and_wrong_entry_point():
+    rng = np.random.default_rng(3)
+    V, H, B, K = 300, 64, 6, 3
+    m = hs_model(rng, V, H, "f32", 0.1)
+    mod = load(m, "f32", 16)
+    prev = rng.integers(0, V, B).astype(np.int32)
+    h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
+    query = rng.integers(0, V, (B, K)).astype(np.int32)
+    query[1, 2] = V
+    query[4, 0] = -1
+    h, lp = gpu_hs_step(mod, prev, h_in, query)
+    bad = np.zeros((B, K), bool); bad[1, 2] = bad[4, 0] = True
+    assert np.all(np.isnan(lp[bad])) and np.all(np.isfinite(lp[~bad]))
+    assert mod.last_error() == rn.FLAG_BAD_QUERY_WORD
+    roq = np.array([0, 1, B, 2, -1, 3], np.int32)
+    query = rng.integers(0, V, (B, K)).astype(np.int32)
+    h, lp = gpu_hs_step(mod, prev, h_in, query, roq)
+    assert np.all(np.isnan(lp[[2, 4]])) and np.all(np.isfinite(lp[[0, 1, 3, 5]]))
+    assert mod.last_error() == rn.FLAG_BAD_ROW
+    # a hierarchical model is refused by the full-softmax step
+    with pytest.raises(rn.RnnlmError) as e:
+        rn.rnnlm_step(mod, torch.zeros(B, dtype=torch.int32, device=DEV), torch.zeros((B, H), device=DEV),
+                      torch.zeros((B, K), dtype=torch.int32, device=DEV), torch.zeros((B, H), device=DEV),
+                      torch.zeros((B, K), device=DEV))
+    assert e.value.status == -1
+    # a tree that names a node beyond V-2 is refused at load
+    bad_entry = m["path_entry"].copy(); bad_entry[5] = V - 1
+    with pytest.raises(rn.RnnlmError):
+        rn.rnnlm_hs_load(V, H, rn.RNNLM_F32, m["U"], m["W"], m["theta"], m["path_off"], bad_entry, 16)
+    mod.close()
+
+
+def test_hs_headline_shape_sampled():
+    """V = 65536, H = 512, B = 1024, K = 32 (the headline workload's shape): all hidden rows and
+    the queries of 64 sampled rows against the oracle."""
+    cfg = CONFIGS[3]
+    rng = np.random.default_rng(cfg.seed)
+    m = hs_model(rng, cfg.V, cfg.H, "bf16", cfg.sigma)
+    mod = load(m, "bf16", cfg.B)
+    prev = bounded_zipf_ids(rng, cfg.V, 1.1, cfg.B).astype(np.int32)
+    h_in = (1.0 / (1.0 + np.exp(-rng.normal(0, 1, (cfg.B, cfg.H))))).astype(np.float32)
+    query = bounded_zipf_ids(rng, cfg.V, 1.1, (cfg.B, cfg.K)).astype(np.int32)
+    h, lp = gpu_hs_step(mod, prev, h_in, query)
+    rows = np.sort(rng.choice(cfg.B, 64, replace=False))
+    ref = oracle.hs_step(m, prev[rows], h_in[rows], query[rows])
+    dh, dlp = np.max(np.abs(h[rows] - ref["h_out"])), np.max(np.abs(lp[rows] - ref["logprob"]))
+    print("hs headline shape: max|dh|=%.3g max|dlogprob|=%.3g mean path %.1f" %
+          (dh, dlp, float(np.diff(m["path_off"])[query].mean())), flush=True)
+    assert dh <= 1e-3 and dlp <= 2e-3 and np.all(np.isfinite(lp)) and np.all(lp < 0)
+    assert mod.last_error() == 0
+    mod.close()
