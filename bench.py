@@ -29,6 +29,83 @@ PEAK_FP32_TFLOPS = 157.3         # MI355X fp32 vector (and fp32 matrix), publish
 OUTPROJ_TRAFFIC_BYTES = {"staged": 78.0e6}
 
 
+def bench_hs(args, cfg, rn, torch, np) -> int:
+    """One step = hidden update + path evaluation of the N x K queried words (rnnlm_hs_step) on
+    the chosen workload's shape.  The tree is Huffman's over the workload's Zipf word frequencies,
+    node vectors N(0, (4 sigma)^2); inputs as the full-softmax bench."""
+    from workloads import bf16_bits, make_model, make_step_inputs
+    dev = "cuda:0"
+    bf16 = cfg.dtype == "bf16"
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    V, H, N, K = cfg.V, cfg.H, cfg.N, cfg.K
+    freq = np.arange(1, V + 1, dtype=np.float64) ** -(cfg.zipf_s or 0.0)
+    off, entry = rn.rnnlm_huffman_build(freq)
+    theta = np.random.default_rng(cfg.seed + 7).normal(0, 4 * cfg.sigma, (V - 1, H)).astype(np.float32)
+    if bf16:
+        theta = bf16_round(theta, np)
+        m = rn.rnnlm_hs_load(V, H, rn.RNNLM_BF16, bf16_bits(model["U"]), bf16_bits(model["W"]), bf16_bits(theta), off,
+                             entry, N)
+    else:
+        m = rn.rnnlm_hs_load(V, H, rn.RNNLM_F32, model["U"], model["W"], theta, off, entry, N)
+    prev = torch.from_numpy(x["prev"]).to(dev)
+    h_in = torch.from_numpy(x["h_in"]).to(dev)
+    query = torch.from_numpy(x["query"]).to(dev)
+    h_out = torch.zeros((N, H), device=dev)
+    lp = torch.zeros((N, K), device=dev)
+
+    def step():
+        rn.rnnlm_hs_step(m, prev, h_in, query, h_out, lp)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert m.last_error() == 0
+    k_ms = min(rn.rnnlm_hs_time_query(m, query, h_out, lp, 20), rn.rnnlm_hs_time_query(m, query, h_out, lp, 20))
+    nodes = int(np.diff(off)[x["query"]].sum())              # node vectors the step's queries touch
+    es = 2 if bf16 else 4
+    alg_bytes = nodes * H * es + N * H * 4 + N * K * 8.0
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        om = {"U": model["U"], "W": model["W"], "theta": theta,
+              "path_off": off, "path_entry": entry}
+        rows = N                                   # the whole step: the tree makes the oracle cheap too
+        t = time.perf_counter()
+        ref = oracle.hs_step(om, x["prev"][:rows], x["h_in"][:rows], x["query"][:rows])
+        cdt = time.perf_counter() - t
+        cpu = {"value": round(rows / cdt, 2), "unit": "hypothesis-steps/s", "cores": oracle.max_threads(), "kind": "oracle",
+               "sample": "all %d rows of the same step (hidden update + paths of their %d queried words), %.3f s wall"
+                         % (rows, rows * K, cdt),
+               "max_abs_dlogprob_vs_gpu": float(np.max(np.abs(lp.cpu().numpy()[:rows] - ref["logprob"])))}
+    out = {"metric": "RNNLM hypothesis-steps/sec, hierarchical output layer (V=%d,H=%d,B=%d)" % (V, H, N),
+           "value": round(N * args.steps / dt, 1), "unit": "hypothesis-steps/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+           "config": {"workload": "%s with the hierarchical output layer: V=%d H=%d B=N=%d K=%d, Huffman tree over "
+                                  "Zipf(%g) frequencies, mean path of a queried word %.1f nodes"
+                                  % (cfg.name, V, H, N, K, cfg.zipf_s or 0, nodes / float(N * K))},
+           "roofline": {"kernel": "hs_query", "bound": "hbm", "achieved": round(alg_bytes / (k_ms * 1e-3) / 1e9, 1),
+                        "peak": 8000.0, "unit": "GB/s", "frac": round(alg_bytes / (k_ms * 1e-3) / 8e12, 4),
+                        "traffic": None, "us_per_launch": round(k_ms * 1e3, 2), "bytes_per_launch": alg_bytes,
+                        "note": "algorithmic bytes: one node vector per path node of every queried word (repeats "
+                                "are served by L2, so the rate can exceed HBM's) + hidden rows + ids and outputs"},
+           "cpu_baseline": cpu}
+    print(json.dumps(out))
+    m.close()
+    return 0
+
+
+def bf16_round(a, np):
+    from workloads import round_to_bf16
+    return round_to_bf16(a)
+
+
 def bench_index_table(args, cfg, rn, torch, np) -> int:
     """One "step" = the N*K contexts that follow a step (queried word, updated hidden vector of its
     history) turned into indices; reported for new contexts and for contexts the table already
@@ -93,6 +170,9 @@ def main() -> int:
                     help="config 4 only: time a decode trace of --trace-steps steps through a cache of "
                          "CAPACITY histories kept between the steps (reset at the start of every pass)")
     ap.add_argument("--trace-steps", type=int, default=8)
+    ap.add_argument("--hs", action="store_true",
+                    help="the chosen workload with the hierarchical output layer (Huffman tree over the "
+                         "Zipf word frequencies) in place of the full softmax")
     ap.add_argument("--index-table", action="store_true",
                     help="time the device-side IndexTable instead of the step: contexts of the chosen "
                          "workload's shape (N x K contexts of H floats) turned into indices and fetched back")
@@ -118,6 +198,8 @@ def main() -> int:
     cfg = CONFIGS[args.config]
     if args.index_table:
         return bench_index_table(args, cfg, rn, torch, np)
+    if args.hs:
+        return bench_hs(args, cfg, rn, torch, np)
     bf16 = cfg.dtype == "bf16"
     model = make_model(cfg)
     if cfg.unique_frac is not None:

@@ -251,6 +251,13 @@ int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_wo
                   const int32_t *query_word, const int32_t *row_of_query_or_null, int N,
                   const float *base_score_or_null, float *h_out, float *logprob, void *hip_stream);
 
+/* Measurement aid: only the path-evaluation kernel of rnnlm_hs_step (no hidden update) on
+ * h_out as a step left it, `repeats` times back to back on `hip_stream` between HIP events on
+ * that stream; mean time of one launch in milliseconds.  Synchronises the stream. */
+int rnnlm_hs_time_query(const rnnlm_model *model, int B, int K, const int32_t *query_word,
+                        const int32_t *row_of_query_or_null, int N, const float *h_out, float *logprob,
+                        int repeats, void *hip_stream, float *ms_per_launch);
+
 /*
  * ---- IndexTable and its inverse on the device (Section 3.2; Table 1 steps 5 and 7-12) -------
  *

@@ -26,7 +26,7 @@ EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rn
            "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
            "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
            "rnnlm_index_free", "rnnlm_index_reset", "rnnlm_index_intern", "rnnlm_index_fetch",
-           "rnnlm_index_stats", "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step"]
+           "rnnlm_index_stats", "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step", "rnnlm_hs_time_query"]
 
 
 class RnnlmError(RuntimeError):
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_hs_load.restype = I
         L.rnnlm_hs_step.argtypes = [P, I, I, P, P, P, P, I, P, P, P, P]
         L.rnnlm_hs_step.restype = I
+        L.rnnlm_hs_time_query.argtypes = [P, I, I, P, P, I, P, P, I, P, ctypes.POINTER(ctypes.c_float)]
+        L.rnnlm_hs_time_query.restype = I
         L.rnnlm_index_create.argtypes = [I, I, I, ctypes.POINTER(P)]
         L.rnnlm_index_create.restype = I
         L.rnnlm_index_free.argtypes = [P]
@@ -429,3 +431,15 @@ def rnnlm_hs_step(model: RnnlmModel, prev_word, h_in, query_word, h_out, logprob
                                _dev(base_score, torch.float32, "base_score"),
                                _dev(h_out, torch.float32, "h_out"), _dev(logprob, torch.float32, "logprob"),
                                _stream(stream)), "rnnlm_hs_step")
+
+
+def rnnlm_hs_time_query(model: RnnlmModel, query_word, h_out, logprob, repeats: int, row_of_query=None,
+                        stream=None) -> float:
+    import torch
+    B, (N, K) = int(h_out.shape[0]), query_word.shape
+    ms = ctypes.c_float(0)
+    _check(lib().rnnlm_hs_time_query(model.handle, B, int(K), _dev(query_word, torch.int32, "query_word"),
+                                     _dev(row_of_query, torch.int32, "row_of_query"), int(N),
+                                     _dev(h_out, torch.float32, "h_out"), _dev(logprob, torch.float32, "logprob"),
+                                     int(repeats), _stream(stream), ctypes.byref(ms)), "rnnlm_hs_time_query")
+    return ms.value

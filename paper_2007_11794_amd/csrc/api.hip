@@ -469,6 +469,27 @@ int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_wo
     return RNNLM_OK;
 }
 
+int rnnlm_hs_time_query(const rnnlm_model *model, int B, int K, const int32_t *query_word,
+                        const int32_t *row_of_query_or_null, int N, const float *h_out, float *logprob,
+                        int repeats, void *hip_stream, float *ms_per_launch) {
+    int rc = check_step_args(model, B, K, N, 1);
+    if (rc != RNNLM_OK) return rc;
+    if (!ms_per_launch || repeats <= 0 || B <= 0 || N <= 0 || K <= 0) return RNNLM_EINVAL;
+    if (!query_word || !h_out || !logprob || (!row_of_query_or_null && N != B)) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (hipEventRecord(model->ev0, s) != hipSuccess) return RNNLM_EDEVICE;
+    for (int i = 0; i < repeats; ++i)
+        if (launch_hs_query(model->dev, B, nullptr, N, K, query_word, row_of_query_or_null, h_out, nullptr, logprob,
+                            s) != hipSuccess)
+            return RNNLM_EDEVICE;
+    if (hipEventRecord(model->ev1, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (hipEventSynchronize(model->ev1) != hipSuccess) return RNNLM_EDEVICE;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, model->ev0, model->ev1) != hipSuccess) return RNNLM_EDEVICE;
+    *ms_per_launch = ms / (float)repeats;
+    return RNNLM_OK;
+}
+
 int rnnlm_index_create(int H, int capacity, int max_N, rnnlm_index_table **out) {
     if (!out) return RNNLM_EINVAL;
     *out = nullptr;
