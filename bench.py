@@ -170,6 +170,9 @@ def main() -> int:
                     help="config 4 only: time a decode trace of --trace-steps steps through a cache of "
                          "CAPACITY histories kept between the steps (reset at the start of every pass)")
     ap.add_argument("--trace-steps", type=int, default=8)
+    ap.add_argument("--gemm-reference", action="store_true",
+                    help="also time the platform's GEMM (torch.matmul, bf16) on the output projection's "
+                         "contraction alone, logits written to HBM, no log-sum-exp: context for the roofline")
     ap.add_argument("--hs", action="store_true",
                     help="the chosen workload with the hierarchical output layer (Huffman tree over the "
                          "Zipf word frequencies) in place of the full softmax")
@@ -306,6 +309,25 @@ def main() -> int:
                 "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
                 "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
 
+    gemm_ref = None
+    if args.gemm_reference and bf16:
+        a = (torch.rand((B, H), device=dev) - 0.5).to(torch.bfloat16)
+        w = torch.from_numpy(model["O"].T.copy()).to(dev).to(torch.bfloat16)       # [V][H], as the library keeps it
+        logits = torch.empty((B, cfg.V), device=dev, dtype=torch.bfloat16)
+        for _ in range(5):
+            torch.matmul(a, w.t(), out=logits)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            torch.matmul(a, w.t(), out=logits)
+        e1.record()
+        torch.cuda.synchronize()
+        g_ms = e0.elapsed_time(e1) / 20
+        gemm_ref = {"what": "torch.matmul bf16 [B,H] x [H,V] -> bf16 logits in HBM (no log-sum-exp)",
+                    "us_per_launch": round(g_ms * 1e3, 2), "tflops": round(flops / (g_ms * 1e-3) / 1e12, 1),
+                    "logit_bytes_written": B * cfg.V * 2}
+        del a, w, logits
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -353,6 +375,8 @@ def main() -> int:
     }
     if cache_info is not None:
         out["cache"] = cache_info
+    if gemm_ref is not None:
+        out["gemm_reference"] = gemm_ref
     print(json.dumps(out))
     m.close()
     return 0
