@@ -317,7 +317,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
         return RNNLM_OK;
     }
     const CacheDev &c = cache->dev;
-    if (launch_cache_lookup(c, N, history_ids, rep, n_unique, step_stats, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_cache_lookup(c, N, 4096, history_ids, rep, n_unique, step_stats, s) != hipSuccess) return RNNLM_EDEVICE;
     if (N == 0) return RNNLM_OK;
     // Only the histories the cache does not hold are computed: *c.n_miss rows, row r taken
     // from raw query c.miss_src[r], its hidden vector written to row c.miss_dst[r] of h_out.
@@ -564,7 +564,7 @@ int rnnlm_index_intern(rnnlm_index_table *table, int N, const int32_t *word, con
     const IndexDev &d = table->dev;
     if (launch_context_hash(word, h, N, d.c.H, d.keys, s) != hipSuccess) return RNNLM_EDEVICE;
     if (launch_dedup(d.keys, N, d.rep, d.inverse, d.n_unique, d.dedup_ws, s) != hipSuccess) return RNNLM_EDEVICE;
-    if (launch_cache_lookup(d.c, N, d.keys, d.rep, d.n_unique, nullptr, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_cache_lookup(d.c, N, 1024, d.keys, d.rep, d.n_unique, nullptr, s) != hipSuccess) return RNNLM_EDEVICE;
     if (launch_index_commit(d, N, word, h, index, s) != hipSuccess) return RNNLM_EDEVICE;
     return RNNLM_OK;
 }

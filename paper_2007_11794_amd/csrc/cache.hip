@@ -281,9 +281,10 @@ hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_cache_lookup(const CacheDev &c, int rows, const uint64_t *ids, const int32_t *rep,
-                               const int32_t *n_unique, int32_t *step_stats, hipStream_t stream) {
-    if (rows <= 2 * kLookupThreads) {                   // few histories: one workgroup, one launch
+hipError_t launch_cache_lookup(const CacheDev &c, int rows, int one_group_rows, const uint64_t *ids,
+                               const int32_t *rep, const int32_t *n_unique, int32_t *step_stats,
+                               hipStream_t stream) {
+    if (rows <= one_group_rows) {                       // few histories: one workgroup, one launch
         hipLaunchKernelGGL(cache_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, rep, n_unique,
                            step_stats);
         return hipGetLastError();

@@ -165,9 +165,12 @@ hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, in
 hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream);
 // Looks the distinct histories ids[rep[u]], u < *n_unique, up; numbers the ones not found
 // (in order of u), gives them entries while there is room and inserts their keys.
-// rows = upper bound of *n_unique (sizes the grid).
-hipError_t launch_cache_lookup(const CacheDev &c, int rows, const uint64_t *ids, const int32_t *rep,
-                               const int32_t *n_unique, int32_t *step_stats, hipStream_t stream);
+// rows = upper bound of *n_unique (sizes the grid).  Up to one_group_rows the lookup is one launch
+// of one workgroup (best while the table sits in L2: the step's cache, up to 4096), beyond it
+// three launches of a full grid (best when the probes go to HBM: the index table, from 1024).
+hipError_t launch_cache_lookup(const CacheDev &c, int rows, int one_group_rows, const uint64_t *ids,
+                               const int32_t *rep, const int32_t *n_unique, int32_t *step_stats,
+                               hipStream_t stream);
 // After the computed block is done: normalisers of all distinct histories into c.lse_rows,
 // new entries into the stores, stored hidden vectors of found histories into h_out.
 hipError_t launch_cache_commit(const CacheDev &c, const ModelDev &m, int rows, const int32_t *n_unique,
