@@ -369,3 +369,25 @@ def test_running_maximum_fallback_when_logits_are_huge():
     scale = np.max(np.abs(ref["logprob"]))
     assert np.max(np.abs(lp - ref["logprob"])) <= 5e-6 * scale + 1e-5
     m.close()
+
+
+# ------------------------------------------------------------------------ a vocabulary of the paper's largest size
+def test_million_word_vocabulary():
+    """V = 1,000,003 (Section 5.1's in-house vocabulary is about a million words; odd on purpose:
+    ragged last tile), H = 128, bf16: full softmax on 130 rows through the staged kernel."""
+    rng = np.random.default_rng(99)
+    V, H, B, K = 1000003, 128, 130, 6
+    from workloads import bounded_zipf_ids, round_to_bf16
+    model = {"U": round_to_bf16(rng.normal(0, 0.05, (V, H)).astype(np.float32)),
+             "W": round_to_bf16(rng.normal(0, 0.05, (H, H)).astype(np.float32)),
+             "O": round_to_bf16(rng.normal(0, 0.05, (H, V)).astype(np.float32)), "bias": None}
+    m = load_model(model, "bf16", B)
+    prev = bounded_zipf_ids(rng, V, 1.1, B)
+    prev[0] = V - 1
+    h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
+    query = bounded_zipf_ids(rng, V, 1.1, (B, K))
+    query[:, 0] = V - 1 - np.arange(B)                  # words of the last, ragged tile
+    h, lp = gpu_step(m, prev, h_in, query)
+    check(h, lp, oracle.step(model, prev, h_in, query), "bf16", "V=1000003")
+    assert m.last_error() == 0
+    m.close()
