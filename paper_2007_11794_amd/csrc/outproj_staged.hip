@@ -86,13 +86,19 @@ struct Loader {
     }
 };
 
-// Base-2 logits of a finished block: x = acc * log2(e) + c2, c2 = the block's constants.
+// The hidden block arrives multiplied by log2(e) (fragment-ordered copy), so the accumulators
+// are base-2 already.  Fixed offset: the accumulators START at the block's constants, and a
+// finished accumulator IS the logit (one VALU instruction less per logit; |constant| < 100 there,
+// so accumulating on top of it costs nothing the tolerance would notice).  Running maximum
+// (constants of any size): the constants are added at the end, x = acc + c2.
+template <bool FIXED>
 __device__ __forceinline__ void finish_logits(const f32x16 &acc, const f32x4 *cn, int g, float (&x)[16]) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const f32x4 c = cn[2 * q + g];
+        f32x4 c = {0.f, 0.f, 0.f, 0.f};
+        if (!FIXED) c = cn[2 * q + g];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) x[4 * q + i] = fmaf(acc[4 * q + i], kLog2e, c[i]);
+        for (int i = 0; i < 4; ++i) x[4 * q + i] = FIXED ? acc[4 * q + i] : acc[4 * q + i] + c[i];
     }
 }
 
@@ -103,21 +109,29 @@ __device__ __forceinline__ void finish_logits(const f32x16 &acc, const f32x4 *cn
 //   stage      LDS stage of this block; a[] already holds its first kPrefetch A operands
 //   next_stage LDS stage of the following block (nullptr: none); on return a[] holds ITS first
 //              kPrefetch A operands -- that block was published one barrier earlier
+//   ccur       this block's constants (fixed offset: the accumulators start from them)
 //   pacc, pcn  the previous block's raw accumulators and its constants: its exp-and-add is
 //              spread over this block's k-steps (fixed offset) or done up front (running max)
 template <int HP, bool FIXED>
 __device__ __forceinline__ void staged_block(const char *stage, const char *next_stage, const int (&aoff)[8],
                                              bf16x8 (&a)[kPrefetch], const bf16x8 (&dreg)[HP / 16], int g,
-                                             f32x16 &pacc, const f32x4 *pcn, float &mrun, float &srun) {
+                                             const f32x4 *ccur, f32x16 &pacc, const f32x4 *pcn, float &mrun,
+                                             float &srun) {
     constexpr int KS = HP / 16;
     static_assert(KS >= 2 * kPrefetch, "");
     f32x16 acc = {0};
-    if (!FIXED) {
+    if (FIXED) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 c = ccur[2 * q + g];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[4 * q + i] = c[i];
+        }
+    } else {
         float x[16];
-        finish_logits(pacc, pcn, g, x);
+        finish_logits<false>(pacc, pcn, g, x);
         lse2_fold16<false>(x, mrun, srun);
     }
-    f32x4 c = pcn[g];                                         // constants of logits 0..3
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 cur = a[ks % kPrefetch];
@@ -125,14 +139,10 @@ __device__ __forceinline__ void staged_block(const char *stage, const char *next
         else if (next_stage) a[ks % kPrefetch] = RNNLM_A_FRAG(next_stage, ks + kPrefetch - KS);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[ks], acc, 0, 0, 0);
         if (FIXED) {
-            // sixteen logits of the previous block spread evenly over the KS steps; the
-            // constants of the next four are requested one step before they are needed
+            // sixteen logits of the previous block spread evenly over the KS steps
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                if ((e * KS) / 16 == ks) srun += fast_exp2(fmaf(pacc[e], kLog2e, c[e % 4]));
-#pragma unroll
-            for (int q = 1; q < 4; ++q)
-                if (ks == (4 * q * KS) / 16 - 1) c = pcn[2 * q + g];
+                if ((e * KS) / 16 == ks) srun += fast_exp2(pacc[e]);
         }
         // keep this order: the compiler's scheduler would otherwise sink every LDS read to
         // just before its MFMA and expose the LDS latency on each step
@@ -226,11 +236,12 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
             const char *next_stage = (bi + 1 < nblk) ? lds + ((bi + 1) & 3) * C::kStageBytes : nullptr;
             // constants of the previous block (for block 0 any landed slot: its pacc is -inf)
             const f32x4 *pcn = reinterpret_cast<const f32x4 *>(cring + ((bi ? bi - 1 : 0) & 7) * kCSlotBytes);
-            staged_block<HP, FIXED>(stage, next_stage, aoff, a, dreg, g, pacc, pcn, mrun, srun);
+            const f32x4 *ccur = reinterpret_cast<const f32x4 *>(cring + (bi & 7) * kCSlotBytes);
+            staged_block<HP, FIXED>(stage, next_stage, aoff, a, dreg, g, ccur, pacc, pcn, mrun, srun);
         }
         if (nblk > 0) {                                       // the last block's exp-and-add
             float x[16];
-            finish_logits(pacc, reinterpret_cast<const f32x4 *>(cring + ((nblk - 1) & 7) * kCSlotBytes), g, x);
+            finish_logits<FIXED>(pacc, reinterpret_cast<const f32x4 *>(cring + ((nblk - 1) & 7) * kCSlotBytes), g, x);
             lse2_fold16<FIXED>(x, mrun, srun);
         }
         // lanes l and l+32 hold the two halves of a row

@@ -119,7 +119,10 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
     {   // the same four values in the fragment order of the staged output projection
         const size_t frag = (size_t)(b >> 5) * (Hp >> 4) + (je >> 4);
         const size_t at = (frag * 64 + ((je >> 3) & 1) * 32 + (b & 31)) * 8 + (je & 7);
-        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dpk;
+        uint2 dsc;                                       // times log2(e): base-2 logits come out of the MFMAs
+        dsc.x = pack_bf16x2((hp[0] - 0.5f) * kLog2e, (hp[1] - 0.5f) * kLog2e);
+        dsc.y = pack_bf16x2((hp[2] - 0.5f) * kLog2e, (hp[3] - 0.5f) * kLog2e);
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dsc;
     }
     if (vec_ok && je + 4 <= H) {
         *reinterpret_cast<f32x4 *>(h_out + (size_t)bo * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
@@ -284,7 +287,10 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
         *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
         const size_t frag = (size_t)(b >> 5) * (Hp >> 4) + (je >> 4);
         const size_t at = (frag * 64 + ((je >> 3) & 1) * 32 + (b & 31)) * 8 + (je & 7);
-        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dpk;
+        uint2 dsc;                                       // times log2(e): base-2 logits come out of the MFMAs
+        dsc.x = pack_bf16x2((hp[0] - 0.5f) * kLog2e, (hp[1] - 0.5f) * kLog2e);
+        dsc.y = pack_bf16x2((hp[2] - 0.5f) * kLog2e, (hp[3] - 0.5f) * kLog2e);
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dsc;
         if (je + 4 <= H) *reinterpret_cast<f32x4 *>(h_out + (size_t)bo * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
     }
 }

@@ -39,7 +39,7 @@ struct ModelDev {
     const int32_t *path_entry;    // [path_off[V]] node | code bit << 31, root first
     // scratch
     void *d;           // [max_Bp][Hp]  h' - 0.5 in the weights' type
-    // bf16 models: the same block once more in the order the staged output projection reads
+    // bf16 models: the same block times log2(e), in the order the staged output projection reads
     // it, [max_Bp / 32][Hp / 16][64 lanes][8]: lane 32 g + c of fragment (rb, ks) holds row
     // 32 rb + c, units 16 ks + 8 g .. + 7, so one MFMA operand of a wave is 1 KB contiguous.
     void *dfrag;
