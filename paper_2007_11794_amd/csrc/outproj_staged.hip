@@ -107,8 +107,11 @@ __device__ __forceinline__ void finish_logits(const f32x16 &acc, const f32x4 *cn
 
 // One 32-word block for this wave's 32 rows.
 //   stage      LDS stage of this block; a[] already holds its first kPrefetch A operands
-//   next_stage LDS stage of the following block (nullptr: none); on return a[] holds ITS first
-//              kPrefetch A operands -- that block was published one barrier earlier
+//   next_stage LDS stage of the following block (after the last block: any stage, the operands
+//              read from it are not used); on return a[] holds ITS first kPrefetch A operands
+//              -- that block was published one barrier earlier.  Never a branch here: the
+//              unrolled body must stay ONE basic block, or the compiler sinks the exp-and-add
+//              of the previous block out of the MFMA sequence into the last block
 //   ccur       this block's constants (fixed offset: the accumulators start from them)
 //   pacc, pcn  the previous block's raw accumulators and its constants: its exp-and-add is
 //              spread over this block's k-steps (fixed offset) or done up front (running max)
@@ -136,7 +139,7 @@ __device__ __forceinline__ void staged_block(const char *stage, const char *next
     for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 cur = a[ks % kPrefetch];
         if (ks + kPrefetch < KS) a[ks % kPrefetch] = RNNLM_A_FRAG(stage, ks + kPrefetch);
-        else if (next_stage) a[ks % kPrefetch] = RNNLM_A_FRAG(next_stage, ks + kPrefetch - KS);
+        else a[ks % kPrefetch] = RNNLM_A_FRAG(next_stage, ks + kPrefetch - KS);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[ks], acc, 0, 0, 0);
         if (FIXED) {
             // sixteen logits of the previous block spread evenly over the KS steps
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
                                  cring0 + ((bi + 3) & 7) * kCSlotBytes);
             }
             const char *stage = lds + (bi & 3) * C::kStageBytes;
-            const char *next_stage = (bi + 1 < nblk) ? lds + ((bi + 1) & 3) * C::kStageBytes : nullptr;
+            const char *next_stage = lds + (((bi + 1 < nblk) ? bi + 1 : bi) & 3) * C::kStageBytes;
             // constants of the previous block (for block 0 any landed slot: its pacc is -inf)
             const f32x4 *pcn = reinterpret_cast<const f32x4 *>(cring + ((bi ? bi - 1 : 0) & 7) * kCSlotBytes);
             const f32x4 *ccur = reinterpret_cast<const f32x4 *>(cring + (bi & 7) * kCSlotBytes);
