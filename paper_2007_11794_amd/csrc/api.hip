@@ -100,6 +100,43 @@ fail:
     return status;
 }
 
+// Device memory of a CacheDev (hash table, stores, counters, per-call scratch for up to nb
+// histories); shared by the step's cache and the index table.  Null pointers are left for
+// release_cache_dev on failure.
+int alloc_cache_dev(CacheDev &d, int capacity, int H, size_t nb, bool with_lse) {
+    int status = RNNLM_OK;
+    d.capacity = capacity;
+    d.table_size = 64;
+    while (d.table_size < 2 * capacity) d.table_size <<= 1;
+    d.H = H;
+    const size_t cap1 = capacity > 0 ? (size_t)capacity : 1;
+    void *p;
+    HIP_TRY(hipMalloc(&p, (size_t)d.table_size * sizeof(CacheCell))); d.table = static_cast<CacheCell *>(p);
+    HIP_TRY(hipMalloc(&p, cap1 * H * 4)); d.store_h = static_cast<float *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); d.n_entries = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, 4 * sizeof(long long))); d.totals = static_cast<long long *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.entry_of = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_of = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_src = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_dst = static_cast<int32_t *>(p);
+    HIP_TRY(hipMalloc(&p, 4)); d.n_miss = static_cast<int *>(p);
+    HIP_TRY(hipMalloc(&p, (nb / 1024 + 2) * 4)); d.block_total = static_cast<int *>(p);
+    if (with_lse) {
+        HIP_TRY(hipMalloc(&p, cap1 * 4)); d.store_lse = static_cast<float *>(p);
+        HIP_TRY(hipMalloc(&p, nb * 4)); d.lse_rows = static_cast<float *>(p);
+    }
+    HIP_TRY(hipMemset(d.n_miss, 0, 4));
+    return RNNLM_OK;
+fail:
+    return status;
+}
+
+void release_cache_dev(CacheDev &d) {
+    (void)hipFree(d.table); (void)hipFree(d.store_h); (void)hipFree(d.store_lse); (void)hipFree(d.n_entries);
+    (void)hipFree(d.totals); (void)hipFree(d.entry_of); (void)hipFree(d.miss_of); (void)hipFree(d.miss_src);
+    (void)hipFree(d.miss_dst); (void)hipFree(d.lse_rows); (void)hipFree(d.n_miss); (void)hipFree(d.block_total);
+}
+
 int check_step_args(const rnnlm_model *model, int B, int K, int N, int hs = 0) {
     if (!model) return RNNLM_EINVAL;
     if (model->dev.hs != hs) return RNNLM_EINVAL;       // full-softmax and hierarchical models have their own steps
@@ -342,26 +379,9 @@ int rnnlm_cache_create(const rnnlm_model *model, int capacity, rnnlm_cache **out
     memset(c, 0, sizeof(*c));
     int status = RNNLM_OK;
     CacheDev &d = c->dev;
-    d.capacity = capacity;
-    d.table_size = 64;
-    while (d.table_size < 2 * capacity) d.table_size <<= 1;
-    d.H = model->dev.H;
     c->max_B = model->max_B;
-    const size_t nb = (size_t)model->max_B, cap1 = capacity > 0 ? (size_t)capacity : 1;
-    void *p;
-    HIP_TRY(hipMalloc(&p, (size_t)d.table_size * sizeof(CacheCell))); d.table = static_cast<CacheCell *>(p);
-    HIP_TRY(hipMalloc(&p, cap1 * d.H * 4)); d.store_h = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, cap1 * 4)); d.store_lse = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, 4)); d.n_entries = static_cast<int *>(p);
-    HIP_TRY(hipMalloc(&p, 4 * sizeof(long long))); d.totals = static_cast<long long *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); d.entry_of = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_of = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_src = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); d.miss_dst = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); d.lse_rows = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, 4)); d.n_miss = static_cast<int *>(p);
-    HIP_TRY(hipMalloc(&p, (nb / 1024 + 2) * 4)); d.block_total = static_cast<int *>(p);
-    HIP_TRY(hipMemset(d.n_miss, 0, 4));
+    status = alloc_cache_dev(d, capacity, model->dev.H, (size_t)model->max_B, true);
+    if (status != RNNLM_OK) goto fail;
     HIP_TRY(launch_cache_reset(d, nullptr));
     HIP_TRY(hipDeviceSynchronize());
     *out = c;
@@ -375,10 +395,7 @@ fail:
 int rnnlm_cache_free(rnnlm_cache *cache) {
     if (!cache) return RNNLM_OK;
     hipError_t e = hipDeviceSynchronize();
-    CacheDev &d = cache->dev;
-    (void)hipFree(d.table); (void)hipFree(d.store_h); (void)hipFree(d.store_lse); (void)hipFree(d.n_entries);
-    (void)hipFree(d.totals); (void)hipFree(d.entry_of); (void)hipFree(d.miss_of); (void)hipFree(d.miss_src);
-    (void)hipFree(d.miss_dst); (void)hipFree(d.lse_rows); (void)hipFree(d.n_miss); (void)hipFree(d.block_total);
+    release_cache_dev(cache->dev);
     delete cache;
     return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
 }
@@ -500,32 +517,18 @@ int rnnlm_index_create(int H, int capacity, int max_N, rnnlm_index_table **out) 
     memset(t, 0, sizeof(*t));
     int status = RNNLM_OK;
     IndexDev &d = t->dev;
-    CacheDev &c = d.c;
-    c.capacity = capacity;
-    c.table_size = 64;
-    while (c.table_size < 2 * capacity) c.table_size <<= 1;
-    c.H = H;
     t->max_N = max_N;
     const size_t nb = (size_t)max_N, cap1 = capacity > 0 ? (size_t)capacity : 1;
     void *p;
-    HIP_TRY(hipMalloc(&p, (size_t)c.table_size * sizeof(CacheCell))); c.table = static_cast<CacheCell *>(p);
-    HIP_TRY(hipMalloc(&p, cap1 * H * 4)); c.store_h = static_cast<float *>(p);
+    status = alloc_cache_dev(d.c, capacity, H, nb, false);
+    if (status != RNNLM_OK) goto fail;
     HIP_TRY(hipMalloc(&p, cap1 * 4)); d.store_word = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, 4)); c.n_entries = static_cast<int *>(p);
-    HIP_TRY(hipMalloc(&p, 4 * sizeof(long long))); c.totals = static_cast<long long *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); c.entry_of = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); c.miss_of = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); c.miss_src = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, nb * 4)); c.miss_dst = static_cast<int32_t *>(p);
-    HIP_TRY(hipMalloc(&p, 4)); c.n_miss = static_cast<int *>(p);
-    HIP_TRY(hipMalloc(&p, (nb / 1024 + 2) * 4)); c.block_total = static_cast<int *>(p);
     HIP_TRY(hipMalloc(&p, nb * 8)); d.keys = static_cast<uint64_t *>(p);
     HIP_TRY(hipMalloc(&p, nb * 4)); d.rep = static_cast<int32_t *>(p);
     HIP_TRY(hipMalloc(&p, nb * 4)); d.inverse = static_cast<int32_t *>(p);
     HIP_TRY(hipMalloc(&p, 4)); d.n_unique = static_cast<int32_t *>(p);
     HIP_TRY(hipMalloc(&p, dedup_workspace_bytes(max_N))); d.dedup_ws = p;
     HIP_TRY(hipMalloc(&p, 2 * sizeof(long long))); d.errors = static_cast<long long *>(p);
-    HIP_TRY(hipMemset(c.n_miss, 0, 4));
     HIP_TRY(launch_index_reset(d, nullptr));
     HIP_TRY(hipDeviceSynchronize());
     *out = t;
@@ -540,11 +543,9 @@ int rnnlm_index_free(rnnlm_index_table *table) {
     if (!table) return RNNLM_OK;
     hipError_t e = hipDeviceSynchronize();
     IndexDev &d = table->dev;
-    CacheDev &c = d.c;
-    (void)hipFree(c.table); (void)hipFree(c.store_h); (void)hipFree(d.store_word); (void)hipFree(c.n_entries);
-    (void)hipFree(c.totals); (void)hipFree(c.entry_of); (void)hipFree(c.miss_of); (void)hipFree(c.miss_src);
-    (void)hipFree(c.miss_dst); (void)hipFree(c.n_miss); (void)hipFree(c.block_total); (void)hipFree(d.keys); (void)hipFree(d.rep);
-    (void)hipFree(d.inverse); (void)hipFree(d.n_unique); (void)hipFree(d.dedup_ws); (void)hipFree(d.errors);
+    release_cache_dev(d.c);
+    (void)hipFree(d.store_word); (void)hipFree(d.keys); (void)hipFree(d.rep); (void)hipFree(d.inverse);
+    (void)hipFree(d.n_unique); (void)hipFree(d.dedup_ws); (void)hipFree(d.errors);
     delete table;
     return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
 }
