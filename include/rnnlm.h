@@ -67,8 +67,10 @@ enum rnnlm_option {
     RNNLM_OPT_LSE_MODE = 1,
     /* Which output-projection kernel: 0 = automatic (default), 1 = the plain any-shape
      * kernel, 2 = the LDS-staged kernel with the hidden block held in registers (bf16,
-     * H <= 512), 3 = the LDS-tiled kernel for any hidden size and both types.  EINVAL if the model
-     * does not allow the choice. */
+     * H <= 512), 3 = the LDS-tiled kernel for any hidden size and both types, 4 = (fp32 models)
+     * the bf16 LDS-tiled kernel on the three-term bf16 split of both operands, fp32 accuracy at
+     * matrix-core speed: the automatic choice for fp32 from 64 rows on.  EINVAL if the model does
+     * not allow the choice. */
     RNNLM_OPT_OUTPROJ_KERNEL = 2
 };
 

@@ -70,7 +70,27 @@ __global__ __launch_bounds__(256) void fill_cvec_kernel(const float *__restrict_
     }
 }
 
+// Three-way bf16 split of the fp32 [Vp][Hp] weights into the six segments of the long reduction.
+__global__ __launch_bounds__(256) void split3_weights_kernel(const float *__restrict__ Ot, size_t n, int Hp,
+                                                             bf16_t *__restrict__ Ot3) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const size_t v = i / Hp;
+    const int j = (int)(i % Hp);
+    uint16_t t[3];
+    split3_bf16(Ot[i], t[0], t[1], t[2]);
+#pragma unroll
+    for (int s = 0; s < 6; ++s) Ot3[v * 6 * Hp + (size_t)s * Hp + j] = t[RNNLM_SPLIT3_W(s)];
+}
+
 }  // namespace
+
+hipError_t launch_split3_weights(const float *Ot, int Vp, int Hp, void *Ot3, hipStream_t stream) {
+    const size_t n = (size_t)Vp * Hp;
+    hipLaunchKernelGGL(split3_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, Ot, n, Hp,
+                       static_cast<bf16_t *>(Ot3));
+    return hipGetLastError();
+}
 
 hipError_t launch_transpose_O(const void *O_dev, void *Ot, int dtype, int H, int V, int Hp, int Vp,
                               hipStream_t stream) {

@@ -243,8 +243,11 @@ hipError_t launch_tiled_shape(const ModelDev &m, int rows, const int *B_dev, boo
 hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                 SplitInfo *splits, hipStream_t stream) {
     if (m.dtype == RNNLM_BF16) {
-        // 256 x 256 tiles, one workgroup per compute unit, once the batch fills them
-        if (rows >= 256) return launch_tiled_shape<bf16_t, 4, 4>(m, rows, B_dev, fixed_offset, 256, splits, stream);
+        // 256 x 256 tiles, one workgroup per compute unit, once batch and vocabulary give every
+        // compute unit such a tile; smaller problems fill the chip better with 128 x 128
+        const long long big_tiles = (long long)((rows + 255) / 256) * (m.Vp / 256);
+        if (rows >= 256 && big_tiles >= 256)
+            return launch_tiled_shape<bf16_t, 4, 4>(m, rows, B_dev, fixed_offset, 256, splits, stream);
         return launch_tiled_shape<bf16_t, 2, 2>(m, rows, B_dev, fixed_offset, 512, splits, stream);
     }
     return launch_tiled_shape<float, 2, 2>(m, rows, B_dev, fixed_offset, 512, splits, stream);

@@ -32,6 +32,14 @@ struct ModelDev {
     const float *cvec2;           // [Vp]
     const float *cvec2_fixed;     // [Vp]  cvec2 - m2_fixed
     float m2_fixed;    // upper bound of every base-2 logit z*log2(e), valid because |h' - 0.5| <= 0.5
+    // fp32 models with the full softmax: the output projection on the bf16 matrix cores at fp32
+    // accuracy.  Every fp32 number is the exact sum of three bf16 numbers x1 + x2 + x3 (8 + 8 + 8
+    // mantissa bits); of the nine cross terms of a product the six with the largest weight are
+    // kept.  Both operands are laid out along a reduction length of 6 Hp so that the bf16 kernels
+    // add exactly those six terms: weights [x1 | x1 | x2 | x1 | x3 | x2], hidden block
+    // [d1 | d2 | d1 | d3 | d1 | d2].
+    const void *Ot3;   // [Vp][6 Hp] bf16, or null
+    void *d3;          // [max_Bp][6 Hp] bf16 scratch, or null
     // hierarchical output layer (models loaded with rnnlm_hs_load; Ot .. cvec2_fixed are null then)
     int hs;                       // 1: hierarchical
     const void *Theta;            // [V-1][Hp] node vectors, weights' type, zero-padded
@@ -199,6 +207,8 @@ hipError_t launch_transpose_O(const void *O_dev /*[H][V]*/, void *Ot /*[Vp][Hp]*
 hipError_t launch_col_stats(const void *O_dev, const float *bias_or_null, int dtype, int H, int V,
                             float *half_colsum /*[V]*/, float *upper /*[V]*/, float *lower /*[V]*/,
                             hipStream_t stream);
+hipError_t launch_split3_weights(const float *Ot /*[Vp][Hp]*/, int Vp, int Hp, void *Ot3 /*[Vp][6 Hp] bf16*/,
+                                 hipStream_t stream);
 hipError_t launch_fill_cvec(const float *bias_or_null, const float *half_colsum, int V, int Vp,
                             float m2_fixed, float *bias_out, float *cvec2, float *cvec2_fixed,
                             hipStream_t stream);

@@ -104,7 +104,7 @@ def test_f32_reduced_elementwise_both_lse_modes(V, H, B, K):
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
     m = load_model(model, "f32", B)
     ref = oracle.step(model, x["prev"], x["h_in"], x["query"])
-    for kernel in (1, 3):                       # plain FMA kernel, LDS-tiled fp32-MFMA kernel
+    for kernel in (1, 3, 4, 0):                 # plain FMA, LDS-tiled fp32-MFMA, bf16 three-term split, automatic
         m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
         for lse_mode in (1, 2):
             m.set_option(rn.OPT_LSE_MODE, lse_mode)
