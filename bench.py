@@ -161,7 +161,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--outproj-kernel", type=int, default=0, help="0 auto, 1 plain, 2 staged")
+    ap.add_argument("--outproj-kernel", type=int, default=0,
+                    help="0 auto, 1 plain, 2 staged, 3 tiled, 4 bf16 three-term split (fp32 models)")
     ap.add_argument("--lse-mode", type=int, default=0, help="0 auto, 1 running max, 2 fixed offset")
     ap.add_argument("--config", type=int, default=3,
                     help="workload number (default 3 = the headline one the metric is quoted on; "
@@ -301,9 +302,16 @@ def main() -> int:
     k3_ms = m.time_outproj(B, reps)
     k3_ms = min(k3_ms, m.time_outproj(B, reps))
     flops = 2.0 * B * cfg.H * cfg.V
+    # fp32 models run the contraction on the bf16 matrix cores from 64 rows on: six bf16 products
+    # per fp32 product (three-term split of both operands), so the launch does 6x the flops
+    split3 = (not bf16) and B >= 64 and args.outproj_kernel in (0, 4)
+    on_mfma = bf16 or split3
+    if split3:
+        flops *= 6.0
     achieved = flops / (k3_ms * 1e-3) / 1e12
-    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
-    roofline = {"kernel": "outproj_lse", "bound": "mfma" if bf16 else "alu", "achieved": round(achieved, 2), "peak": peak,
+    peak = PEAK_BF16_TFLOPS if on_mfma else PEAK_FP32_TFLOPS
+    roofline = {"kernel": "outproj_lse" + (" (fp32 as 6 bf16 products)" if split3 else ""),
+                "bound": "mfma" if on_mfma else "alu", "achieved": round(achieved, 2), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) and args.config == 3 else None,
                 "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
