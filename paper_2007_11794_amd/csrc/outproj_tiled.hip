@@ -219,10 +219,11 @@ hipError_t launch_tiled_shape(const ModelDev &m, int rows, const int *B_dev, boo
         attr_set[which] = true;
     }
     const int RG = (rows + C::kRows - 1) / C::kRows, ntiles = m.Vp / C::kWords;
-    // about wg_target workgroups, never more splits than tiles; splits in multiples of 8 so
-    // that the row groups streaming the same weights share an XCD
+    // about wg_target workgroups; splits in multiples of 8 so that the row groups streaming the
+    // same weights share an XCD; at most one split per tile, rounded UP to a multiple of 8 (a
+    // few splits stay empty) so that no split gets two tiles while the others have one
     int Sx = wg_target / (kXcds * RG);
-    if (Sx > ntiles / kXcds) Sx = ntiles / kXcds;
+    if (Sx > (ntiles + kXcds - 1) / kXcds) Sx = (ntiles + kXcds - 1) / kXcds;
     if (Sx < 1) Sx = 1;
     if (Sx > kMaxSplits / kXcds) Sx = kMaxSplits / kXcds;
     const int S = kXcds * Sx;
