@@ -77,3 +77,37 @@ def test_binding_refuses_cpu_tensors():
         rn.rnnlm_dedup(torch.zeros(4, dtype=torch.int64), torch.zeros(4, dtype=torch.int32),
                        torch.zeros(4, dtype=torch.int32), torch.zeros(1, dtype=torch.int32),
                        torch.zeros(1024, dtype=torch.uint8), stream=0)
+
+
+def test_host_checked_errors_of_the_cache_index_and_tree_entry_points():
+    L = rn.lib()
+    out = ctypes.c_void_p()
+    buf = (ctypes.c_float * 16)()
+    p = ctypes.cast(buf, ctypes.c_void_p)
+    EINVAL, ERANGE = -1, -4
+    assert L.rnnlm_cache_create(None, 10, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_cache_create(None, 10, None) == EINVAL
+    assert L.rnnlm_cache_free(None) == 0
+    assert L.rnnlm_cache_reset(None, None) == EINVAL
+    assert L.rnnlm_cache_stats(None, None, None) == EINVAL
+    assert L.rnnlm_index_create(0, 10, 10, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_index_create(8, -1, 10, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_index_create(8, 10, 0, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_index_create(8, 1 << 27, 10, ctypes.byref(out)) == ERANGE
+    assert L.rnnlm_index_free(None) == 0
+    assert L.rnnlm_index_intern(None, 1, p, p, p, None) == EINVAL
+    assert L.rnnlm_index_fetch(None, 1, p, p, p, None) == EINVAL
+    assert L.rnnlm_pack_ids(None, None, 1, None, None) == EINVAL
+    assert L.rnnlm_pack_ids(None, None, 0, None, None) == 0
+    assert L.rnnlm_pack_ids(None, None, -1, None, None) == EINVAL
+    off = (ctypes.c_int32 * 4)(0, 1, 2, 3)
+    ent = (ctypes.c_int32 * 3)(0, 0, 0)
+    assert L.rnnlm_hs_load(1, 4, 0, p, p, p, off, ent, 1, ctypes.byref(out)) == EINVAL      # V < 2
+    assert L.rnnlm_hs_load(3, 4, 0, p, p, p, None, ent, 1, ctypes.byref(out)) == EINVAL
+    bad_off = (ctypes.c_int32 * 4)(0, 1, 1, 2)                                              # an empty path
+    assert L.rnnlm_hs_load(3, 4, 0, p, p, p, bad_off, ent, 1, ctypes.byref(out)) == EINVAL
+    bad_ent = (ctypes.c_int32 * 3)(0, 2, 0)                                                 # node 2 of a 3-word tree
+    assert L.rnnlm_hs_load(3, 4, 0, p, p, p, off, bad_ent, 1, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_hs_step(None, 1, 1, p, p, p, None, 1, None, p, p, None) == EINVAL
+    assert L.rnnlm_step_cached(None, None, 1, 1, p, p, p, p, None, p, p, p, p, p, None, p, 64, None) == EINVAL
+    assert out.value is None
