@@ -185,8 +185,8 @@ def main() -> int:
                          "reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the step shards trivially over rows, "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (rows are independent, so the step would shard "
+              "by replicating the weights and splitting the rows); --gpus must be 1", file=sys.stderr)
         return 2
 
     import numpy as np
