@@ -7,7 +7,9 @@
 // 1024 x 512) and the output weights Ot[Vp][Hp] are large (64 MB at V = 65536), so the
 // weights are streamed exactly once per row group and the hidden block never moves:
 //   - a workgroup (8 waves) owns 256 rows; each wave keeps ITS 32 rows of d for the whole
-//     reduction length in registers (Hp/16 MFMA B-operands, 128 VGPRs at Hp = 512);
+//     reduction length in registers (Hp/16 MFMA B-operands, 128 VGPRs at Hp = 512), loaded from
+//     the fragment-ordered copy of the block (one operand = 1 KB contiguous), which holds
+//     d * log2(e): the accumulators are base-2 logits;
 //   - the weights of 32 words (32 x Hp bf16, 32 KB at Hp = 512) form one LDS stage; four
 //     stages are filled round-robin by direct global->LDS loads (no VGPR round trip), two to
 //     three blocks ahead of use;
@@ -15,7 +17,8 @@
 //     (read four steps ahead), B = 16 k x 32 rows from registers, so lane l holds 16 logits
 //     of ONE row and the sum over words stays inside the lane;
 //   - the exp-and-add of block i is interleaved, instruction by instruction, with the MFMAs
-//     of block i+1, so the vector ALU works in the shadow of the matrix core;
+//     of block i+1, so the vector ALU works in the shadow of the matrix core (the unrolled
+//     block body is kept free of branches for that: see staged_block);
 //   - one workgroup barrier per block.  It publishes the landing of block i+1 while block i
 //     is being computed, so no wave ever waits at a barrier for data it is about to use, and
 //     the first operands of block i+1 are already in registers when block i ends.
