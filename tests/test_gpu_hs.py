@@ -126,3 +126,34 @@ def test_hs_headline_shape_sampled():
     assert dh <= 1e-3 and dlp <= 2e-3 and np.all(np.isfinite(lp)) and np.all(lp < 0)
     assert mod.last_error() == 0
     mod.close()
+
+
+def hs_shapes():
+    rng = np.random.default_rng(314)
+    out = []
+    for i in range(16):
+        out.append((i, "bf16" if i % 2 else "f32", int(rng.choice([2, 3, 9, 33, 257, 1000, 4097])),
+                    int(rng.choice([1, 3, 64, 65, 130, 256, 516, 700])), int(rng.choice([1, 2, 33, 64, 129, 300])),
+                    int(rng.choice([1, 2, 7, 9, 17, 40]))))
+    return out
+
+
+@pytest.mark.parametrize("i,dtype,V,H,B,K", hs_shapes())
+def test_hs_awkward_shapes(i, dtype, V, H, B, K):
+    """Odd hidden sizes, trees of two or three words, single rows, many words per query, skewed and
+    flat frequencies (deep and shallow trees)."""
+    rng = np.random.default_rng(500 + i)
+    m = hs_model(rng, V, H, dtype, 0.4 / np.sqrt(H), zipf_s=(0.0, 1.0, 2.0)[i % 3])
+    N = B + int(rng.integers(0, B + 1))
+    mod = load(m, dtype, N)
+    prev = rng.integers(0, V, B).astype(np.int32)
+    h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
+    roq = np.concatenate([np.arange(B), rng.integers(0, B, N - B)]).astype(np.int32)
+    query = rng.integers(0, V, (N, K)).astype(np.int32)
+    query[0, 0] = V - 1
+    ref = oracle.hs_step(m, prev, h_in, query, row_of_query=roq)
+    h, lp = gpu_hs_step(mod, prev, h_in, query, roq)
+    dh, dlp = np.max(np.abs(h - ref["h_out"])), np.max(np.abs(lp - ref["logprob"]))
+    assert dh <= TOL[dtype][1] and dlp <= TOL[dtype][0], (i, dtype, V, H, B, K, dh, dlp, int(np.diff(m["path_off"]).max()))
+    assert mod.last_error() == 0
+    mod.close()
