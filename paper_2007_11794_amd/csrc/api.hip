@@ -441,8 +441,11 @@ int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const v
     // the tree is walked on the device without further checks: every path must be non-empty
     // and name inner nodes only
     if (path_offset[0] != 0) return RNNLM_EINVAL;
-    for (int v = 0; v < V; ++v)
+    int longest = 0;
+    for (int v = 0; v < V; ++v) {
         if (path_offset[v + 1] <= path_offset[v]) return RNNLM_EINVAL;
+        if (path_offset[v + 1] - path_offset[v] > longest) longest = path_offset[v + 1] - path_offset[v];
+    }
     const size_t entries = (size_t)path_offset[V];
     for (size_t e = 0; e < entries; ++e)
         if (((uint32_t)path_entry[e] & 0x7FFFFFFFu) >= (uint32_t)(V - 1)) return RNNLM_EINVAL;
@@ -455,7 +458,7 @@ int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const v
     const int Hp = (dtype == RNNLM_BF16 && H < 128) ? 128 : round_up(H, 64);
     const int max_Bp = round_up(max_B, 256);
     ModelDev &d = m->dev;
-    d.V = V; d.H = H; d.Hp = Hp; d.Vp = round_up(V, 256); d.dtype = dtype; d.hs = 1;
+    d.V = V; d.H = H; d.Hp = Hp; d.Vp = round_up(V, 256); d.dtype = dtype; d.hs = 1; d.hs_max_len = longest;
     m->max_B = max_B; m->max_Bp = max_Bp;
     void *p;
     status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp);

@@ -45,6 +45,7 @@ struct ModelDev {
     const void *Theta;            // [V-1][Hp] node vectors, weights' type, zero-padded
     const int32_t *path_off;      // [V+1]
     const int32_t *path_entry;    // [path_off[V]] node | code bit << 31, root first
+    int hs_max_len;               // longest path
     // scratch
     void *d;           // [max_Bp][Hp]  h' - 0.5 in the weights' type
     // bf16 models: the same block times log2(e), in the order the staged output projection reads
