@@ -9,9 +9,11 @@
 // addressing over 16-byte cells, at most half full.
 //
 // One step through the cache, after the grouping of the step's own ids:
-//   lookup   one workgroup: probe every distinct history; the ones not found are numbered in
-//            order of appearance by a prefix sum (row of the block that is computed now),
-//            get the next entries while there is room, and their keys are inserted;
+//   lookup   probe every distinct history; the ones not found are numbered in order of
+//            appearance by a prefix sum (row of the block that is computed now), get the next
+//            entries while there is room, and their keys are inserted.  One workgroup in one
+//            launch for few histories, three launches of a full grid (probe + counts, scan of
+//            the counts, numbering + insertion) for many;
 //   (hidden update and output projection run on the numbered rows only)
 //   commit   per distinct history: normaliser into lse_rows; new entries are written to the
 //            stores, found ones copy their stored h' to the caller's h_out.

@@ -10,7 +10,13 @@
 // percent of the step's flops) so that the hidden vector is accurate to fp32 level.
 //
 // Besides h_out (fp32, caller's buffer) the kernel leaves d' = h' - 1/2 in the model's
-// scratch block, in the weights' type, as the operand of the output projection.
+// scratch blocks as the operand of the output projection: row-major in the weights' type;
+// for bf16 models also times log2(e) in MFMA-fragment order (staged output projection); for
+// fp32 models also as three bf16 terms along a six times longer reduction (see ModelDev).
+//
+// Three kernels: the LDS-tiled bf16 kernel (the default), the register-direct bf16 kernel it
+// replaced (kept for hidden sizes that are not a multiple of 4 or unaligned buffers), and the
+// fp32 kernel on the full-precision matrix instruction.
 #include "device_utils.h"
 #include "rnnlm_internal.h"
 
@@ -23,7 +29,7 @@ __device__ __forceinline__ float sigmoid_f32(float a) {
     return __frcp_rn(1.0f + fast_exp2(-a * kLog2e));
 }
 
-// ----------------------------------------------------------------------------- bf16 / MFMA
+// ----------------------------------------------------------------------------- bf16 / MFMA, register-direct
 // A workgroup of 4 waves computes a 32 (units j) x 32 (rows b) block
 // D[j][b] = sum_i W[j][i] d[b][i]; wave w takes the quarter w of the reduction length and
 // issues all of its loads before the first MFMA (the kernel is bound by load latency, not
