@@ -3,7 +3,7 @@
 // 4-byte index from then on (Table 3), so that only indices have to travel.
 //
 // Inverse direction (context -> index), for N contexts given by value:
-//   hash     one wave per context: 64-bit hash of the word and of every bit of the vector;
+//   hash     a wave per eight contexts: 64-bit hash of the word and of every bit of the vector;
 //   group    equal hashes of the call are grouped in order of first appearance (the grouping
 //            kernel of the step);
 //   lookup   the cache's lookup kernel on the hashes: found -> the stored index; new -> the next
@@ -47,26 +47,54 @@ __device__ __forceinline__ void copy_row(uint32_t *dst, const uint32_t *src, int
     }
 }
 
-// The hash of a vector is the sum (mod 2^64) of a 64-bit mix of every (position, bit pattern)
-// pair: order-free, so lanes and their partial sums can be combined in any way.
+// The hash of a vector is multilinear: sum over the positions j of a_j * x_j (mod 2^64), x_j the bit
+// pattern of element j and a_j an odd 64-bit multiplier derived from j -- order-free, so lanes and
+// their partial sums combine freely, and two vectors that differ in one element never collide
+// (a_j odd).  A wave hashes kHashRows consecutive contexts at once: the multipliers of its positions
+// are computed once and the loads of all rows are in flight together.  The word is mixed in at
+// the end.
+constexpr int kHashRows = 8;
+
+__device__ __forceinline__ uint64_t position_multiplier(int j) {
+    return mix64_full((uint64_t)j + 0x632BE59BD9B4E019ull) | 1ull;
+}
+
 __global__ __launch_bounds__(256) void context_hash_kernel(const int32_t *__restrict__ word,
                                                             const float *__restrict__ h, int N, int H,
                                                             uint64_t *__restrict__ keys) {
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (n >= N) return;
-    const uint32_t *row = reinterpret_cast<const uint32_t *>(h) + (size_t)n * H;
-    uint64_t acc = 0;
+    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kHashRows, lane = threadIdx.x & 63;
+    if (n0 >= N) return;
+    const uint32_t *base = reinterpret_cast<const uint32_t *>(h);
+    uint64_t acc[kHashRows];
+#pragma unroll
+    for (int r = 0; r < kHashRows; ++r) acc[r] = 0;
     if (vec_rows(h, H)) {                                // 16 bytes per lane and load
         for (int j = 4 * lane; j < H; j += 256) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(row + j);
+            uint64_t a[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc += mix64_full(((uint64_t)v[i] << 32) | (uint32_t)(j + i));
+            for (int i = 0; i < 4; ++i) a[i] = position_multiplier(j + i);
+            u32x4 v[kHashRows];
+#pragma unroll
+            for (int r = 0; r < kHashRows; ++r)          // rows past N repeat the last one, unused
+                v[r] = *reinterpret_cast<const u32x4 *>(base + (size_t)min(n0 + r, N - 1) * H + j);
+#pragma unroll
+            for (int r = 0; r < kHashRows; ++r)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[r] += a[i] * (uint64_t)v[r][i];
         }
     } else {
-        for (int j = lane; j < H; j += 64) acc += mix64_full(((uint64_t)row[j] << 32) | (uint32_t)j);
+        for (int j = lane; j < H; j += 64) {
+            const uint64_t a = position_multiplier(j);
+#pragma unroll
+            for (int r = 0; r < kHashRows; ++r) acc[r] += a * (uint64_t)base[(size_t)min(n0 + r, N - 1) * H + j];
+        }
     }
-    acc = wave_sum_u64(acc);
-    if (lane == 0) keys[n] = mix64_full(acc ^ ((uint64_t)(uint32_t)word[n] * 0x9E3779B97F4A7C15ull));
+#pragma unroll
+    for (int r = 0; r < kHashRows; ++r) {
+        const uint64_t sum = wave_sum_u64(acc[r]);
+        if (lane == 0 && n0 + r < N)
+            keys[n0 + r] = mix64_full(sum ^ ((uint64_t)(uint32_t)word[n0 + r] * 0x9E3779B97F4A7C15ull));
+    }
 }
 
 __global__ __launch_bounds__(256) void index_commit_kernel(IndexDev t, int N, const int32_t *__restrict__ word,
@@ -150,7 +178,8 @@ hipError_t launch_index_reset(const IndexDev &t, hipStream_t stream) {
 hipError_t launch_context_hash(const int32_t *word, const float *h, int N, int H, uint64_t *keys,
                                hipStream_t stream) {
     if (N <= 0) return hipSuccess;
-    hipLaunchKernelGGL(context_hash_kernel, dim3((N + 3) / 4), dim3(256), 0, stream, word, h, N, H, keys);
+    hipLaunchKernelGGL(context_hash_kernel, dim3((N + 4 * kHashRows - 1) / (4 * kHashRows)), dim3(256), 0, stream, word, h,
+                       N, H, keys);
     return hipGetLastError();
 }
 
