@@ -150,36 +150,48 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
 // LDS rows are 128 bytes; chunk c of row r sits at c ^ ((r >> 1) & 7) (as in the tiled
 // output projection).  h_in stays fp32 in LDS and is centred and split into hi + lo bf16 in
 // registers right before the two MFMAs of a k-step.
-constexpr int kRtTile = 64;                           // units and rows per workgroup
+constexpr int kRtTile = 64;                           // units per workgroup (and rows, in the large shape)
 constexpr int kRtWBytes = kRtTile * 128;              // W part of a stage
-constexpr int kRtStageBytes = kRtWBytes + 2 * kRtTile * 128;
-constexpr int kRtLoadsPerChunk = 6;                   // direct-to-LDS loads a thread issues per chunk
-// Stages of the ring (template parameter NS): a grid that gives a compute unit one workgroup
-// at most hides load latency by keeping three chunks in flight (4 stages, 96 KB); a larger
-// grid does better with 2 stages (48 KB), three workgroups per compute unit.
+// Two shapes (template parameter TB = rows per workgroup):
+//   TB = 64: 2 x 2 waves, each a 32 x 32 block over the whole reduction length.  For grids that
+//            give every compute unit several workgroups (2 stages, 48 KB, three per unit).
+//   TB = 32: a compute unit pulls these direct-to-LDS loads in at 35-50 GB/s only, so a small
+//            problem must be spread over ALL compute units with as few bytes per workgroup as
+//            possible: 64 units x 32 rows (64 KB of W + 64 KB of h_in for H = 512, against
+//            64 + 128 KB), twice as many workgroups.  The four waves are 2 (unit halves) x 2
+//            (halves of every chunk's k-steps); the second pair hands its partial sums over
+//            through LDS at the end.  4 stages of 16 KB.
+template <int TB> struct RtCfg {
+    static constexpr int kHalfBytes = TB * 128;                       // one half row per row
+    static constexpr int kStageBytes = kRtWBytes + 2 * kHalfBytes;
+    static constexpr int kHLoads = TB * 8 / 256;                      // per thread and half
+    static constexpr int kLoads = 2 + 2 * kHLoads;                    // per thread and chunk
+};
 
-template <int NS>
+template <int NS, int TB>
 __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
     float *__restrict__ h_out) {
+    using C = RtCfg<TB>;
+    constexpr bool kSplitK = TB == 32;
     const int B = B_dev ? *B_dev : rows;
     // Workgroup id modulo 8 is the XCD (L2 domain).  Row block rb runs on XCD rb % 8 with all
     // its unit blocks, so h_in (the larger operand) is fetched into one L2 only.
     const int JB = m.Hp / kRtTile;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    const int b0 = (xcd + kXcds * (local / JB)) * kRtTile;
+    const int b0 = (xcd + kXcds * (local / JB)) * TB;
     if (b0 >= B) return;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    __shared__ int srcs[kRtTile];
+    __shared__ int srcs[TB];
     const int j0 = (local % JB) * kRtTile;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
-    const int wj = wave & 1, wb = wave >> 1;
+    const int wj = wave & 1, wb = kSplitK ? 0 : wave >> 1, wk = kSplitK ? wave >> 1 : 0;
     const int H = m.H, Hp = m.Hp;
     const bf16_t *W = static_cast<const bf16_t *>(m.W);
     const bf16_t *U = static_cast<const bf16_t *>(m.U);
 
-    if (tid < kRtTile) {                               // rows beyond B repeat the last one; dropped later
+    if (tid < TB) {                                    // rows beyond B repeat the last one; dropped later
         const int rv = min(b0 + tid, B - 1);
         srcs[tid] = row_src ? row_src[rv] : rv;
     }
@@ -188,12 +200,16 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     // loader: thread fills the physical 16-byte pieces f = q * 256 + tid of an operand tile
     // (row f / 8, position f % 8) with the logical piece c = position ^ swizzle(row)
     uint32_t woff[2];
-    const float *hrow[2];
-    int hc[2];
+    const float *hrow[C::kHLoads];
+    int hc[C::kHLoads];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const int f = q * 256 + tid, r = f >> 3, c = (f & 7) ^ ((r >> 1) & 7);
         woff[q] = (uint32_t)(r * Hp * 2 + c * 16);
+    }
+#pragma unroll
+    for (int q = 0; q < C::kHLoads; ++q) {
+        const int f = q * 256 + tid, r = f >> 3, c = (f & 7) ^ ((r >> 1) & 7);
         hrow[q] = h_in + (size_t)srcs[r] * H;
         hc[q] = 4 * c;
     }
@@ -201,17 +217,17 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     const uint32_t lds0 = lds_address(lds);
     auto issue = [&](int chunk, int stage) {
         const int k0 = chunk * 64;
-        const uint32_t base = lds0 + stage * kRtStageBytes + wave_s * 1024;
+        const uint32_t base = lds0 + stage * C::kStageBytes + wave_s * 1024;
         const bf16_t *wsrc = W + (size_t)j0 * Hp + k0;
 #pragma unroll
         for (int q = 0; q < 2; ++q) lds_dma_16(wsrc, woff[q], base + q * 4096);
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < C::kHLoads; ++q) {
                 // pieces past the end of the row meet zero weights: fetch the row's first piece
                 const int k = k0 + 32 * half + hc[q];
-                lds_dma_16_ptr(hrow[q] + (k + 4 <= H ? k : 0), base + kRtWBytes + half * (kRtTile * 128) + q * 4096);
+                lds_dma_16_ptr(hrow[q] + (k + 4 <= H ? k : 0), base + kRtWBytes + half * C::kHalfBytes + q * 4096);
             }
     };
 
@@ -241,7 +257,7 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
         for (int ks = 0; ks < 4; ++ks) {
             aoff[ks] = ra * 128 + (((2 * ks + g) ^ ((ra >> 1) & 7)) * 16);
             // h: k = 16 ks + 8 g .. + 7 -> half row ks / 2, pieces 4 (ks % 2) + 2 g and the next
-            boff[ks] = kRtWBytes + (ks >> 1) * (kRtTile * 128) + rb * 128;
+            boff[ks] = kRtWBytes + (ks >> 1) * C::kHalfBytes + rb * 128;
         }
     }
     const int bsw = ((32 * wb + col) >> 1) & 7;
@@ -252,14 +268,15 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
         // my loads of this chunk have landed once only those of the (at most two) later chunks
         // already requested are outstanding
         const int later = min(NS - 2, nk - 1 - chunk);
-        if (later >= 2) wait_vmcnt<2 * kRtLoadsPerChunk>();
-        else if (later == 1) wait_vmcnt<kRtLoadsPerChunk>();
+        if (later >= 2) wait_vmcnt<2 * C::kLoads>();
+        else if (later == 1) wait_vmcnt<C::kLoads>();
         else wait_vmcnt<0>();
         __syncthreads();                                // everybody's; the stage of chunk - 1 is free
         if (chunk + NS - 1 < nk) issue(chunk + NS - 1, (chunk + NS - 1) % NS);
-        const char *st = lds + stage * kRtStageBytes;
+        const char *st = lds + stage * C::kStageBytes;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
+            if (kSplitK && (ks >> 1) != wk) continue;   // wave-uniform: this wave's half of the chunk
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + aoff[ks]);
             const int c0 = 4 * (ks & 1) + 2 * g;
             const f32x4 h0 = *reinterpret_cast<const f32x4 *>(st + boff[ks] + ((c0 ^ bsw) * 16));
@@ -274,6 +291,23 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
             }
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, hi), acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, lo), acc, 0, 0, 0);
+        }
+    }
+    if (kSplitK) {
+        // the waves with the second halves hand their sums to their partners (the stages are free now)
+        f32x4 *red = reinterpret_cast<f32x4 *>(lds) + (size_t)wj * 4 * 64;
+        __syncthreads();
+        if (wk == 1) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) red[q * 64 + lane] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        }
+        __syncthreads();
+        if (wk == 1) return;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 t = red[q * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[4 * q + i] += t[i];
         }
     }
     if (!row_ok) return;
@@ -418,21 +452,25 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16 && m.H % 4 == 0 && (reinterpret_cast<uintptr_t>(h_in) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(h_out) & 15) == 0) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kRtStageBytes);
-            if (e != hipSuccess) return e;
-            attr_set = true;
+        const int big_blocks = (rows + 63) / 64, units = m.Hp / kRtTile;
+        if (big_blocks * units > 256) {                 // several 64 x 64 workgroups per compute unit
+            dim3 grid(kXcds * ((big_blocks + kXcds - 1) / kXcds) * units);
+            hipLaunchKernelGGL((recur_bf16_tiled_kernel<2, 64>), grid, dim3(256), 2 * RtCfg<64>::kStageBytes, stream, m,
+                               rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
+        } else {                                        // small problem: 64 x 32, all compute units
+            static bool attr_set = false;               // 64 KB of stages + the static row map: above the default limit
+            if (!attr_set) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   4 * RtCfg<32>::kStageBytes);
+                if (e != hipSuccess) return e;
+                attr_set = true;
+            }
+            const int small_blocks = (rows + 31) / 32;
+            dim3 grid(kXcds * ((small_blocks + kXcds - 1) / kXcds) * units);
+            hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32>), grid, dim3(256), 4 * RtCfg<32>::kStageBytes, stream, m,
+                               rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
         }
-        const int row_blocks = (rows + kRtTile - 1) / kRtTile;
-        dim3 grid(kXcds * ((row_blocks + kXcds - 1) / kXcds) * (m.Hp / kRtTile));
-        if (row_blocks * (m.Hp / kRtTile) <= 256)
-            hipLaunchKernelGGL(recur_bf16_tiled_kernel<4>, grid, dim3(256), 4 * kRtStageBytes, stream, m, rows,
-                               B_dev, row_src, row_dst, prev_word, h_in, h_out);
-        else
-            hipLaunchKernelGGL(recur_bf16_tiled_kernel<2>, grid, dim3(256), 2 * kRtStageBytes, stream, m, rows,
-                               B_dev, row_src, row_dst, prev_word, h_in, h_out);
     } else if (m.dtype == RNNLM_BF16) {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);
         hipLaunchKernelGGL(recur_bf16_kernel, grid, dim3(256), 0, stream, m, rows, B_dev, row_src,
