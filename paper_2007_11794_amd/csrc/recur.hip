@@ -168,7 +168,11 @@ template <int TB> struct RtCfg {
     static constexpr int kLoads = 2 + 2 * kHLoads;                    // per thread and chunk
 };
 
-template <int NS, int TB>
+// SUB = chunks per stage and barrier.  With SUB = 2 (small shape, Hp a multiple of 128) a wave
+// pair takes one whole chunk of the two: four k-steps of independent loads and conversions
+// between two barriers instead of two, which is what the single wave per SIMD needs to hide
+// the LDS and matrix latencies.
+template <int NS, int TB, int SUB>
 __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
@@ -215,20 +219,24 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     }
     const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = lds_address(lds);
-    auto issue = [&](int chunk, int stage) {
-        const int k0 = chunk * 64;
-        const uint32_t base = lds0 + stage * C::kStageBytes + wave_s * 1024;
-        const bf16_t *wsrc = W + (size_t)j0 * Hp + k0;
+    auto issue = [&](int sc, int stage) {            // the SUB chunks of stage-chunk sc
 #pragma unroll
-        for (int q = 0; q < 2; ++q) lds_dma_16(wsrc, woff[q], base + q * 4096);
+        for (int sub = 0; sub < SUB; ++sub) {
+            const int k0 = (sc * SUB + sub) * 64;
+            const uint32_t base = lds0 + (stage * SUB + sub) * C::kStageBytes + wave_s * 1024;
+            const bf16_t *wsrc = W + (size_t)j0 * Hp + k0;
 #pragma unroll
-        for (int half = 0; half < 2; ++half)
+            for (int q = 0; q < 2; ++q) lds_dma_16(wsrc, woff[q], base + q * 4096);
 #pragma unroll
-            for (int q = 0; q < C::kHLoads; ++q) {
-                // pieces past the end of the row meet zero weights: fetch the row's first piece
-                const int k = k0 + 32 * half + hc[q];
-                lds_dma_16_ptr(hrow[q] + (k + 4 <= H ? k : 0), base + kRtWBytes + half * C::kHalfBytes + q * 4096);
-            }
+            for (int half = 0; half < 2; ++half)
+#pragma unroll
+                for (int q = 0; q < C::kHLoads; ++q) {
+                    // pieces past the end of the row meet zero weights: fetch the row's first piece
+                    const int k = k0 + 32 * half + hc[q];
+                    lds_dma_16_ptr(hrow[q] + (k + 4 <= H ? k : 0),
+                                   base + kRtWBytes + half * C::kHalfBytes + q * 4096);
+                }
+        }
     };
 
     const int b = b0 + 32 * wb + col;
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     const int w = prev_word[src];
     const bool w_ok = (w >= 0 && w < m.V);
     const int jw = j0 + 32 * wj + 4 * g;                // this lane finishes units jw + 8 q .. + 3, q < 4
-    const int nk = Hp / 64;
+    const int nk = Hp / (64 * SUB);                     // stage-chunks (the launcher checks divisibility)
 #pragma unroll
     for (int c = 0; c < NS - 1; ++c)
         if (c < nk) issue(c, c);
@@ -268,15 +276,17 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
         // my loads of this chunk have landed once only those of the (at most two) later chunks
         // already requested are outstanding
         const int later = min(NS - 2, nk - 1 - chunk);
-        if (later >= 2) wait_vmcnt<2 * C::kLoads>();
-        else if (later == 1) wait_vmcnt<C::kLoads>();
+        if (later >= 2) wait_vmcnt<2 * SUB * C::kLoads>();
+        else if (later == 1) wait_vmcnt<SUB * C::kLoads>();
         else wait_vmcnt<0>();
         __syncthreads();                                // everybody's; the stage of chunk - 1 is free
         if (chunk + NS - 1 < nk) issue(chunk + NS - 1, (chunk + NS - 1) % NS);
-        const char *st = lds + stage * C::kStageBytes;
+        // split reduction: with two chunks per stage a wave pair takes one of them, else half of
+        // the k-steps of the one chunk
+        const char *st = lds + (stage * SUB + (SUB == 2 ? wk : 0)) * C::kStageBytes;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            if (kSplitK && (ks >> 1) != wk) continue;   // wave-uniform: this wave's half of the chunk
+            if (kSplitK && SUB == 1 && (ks >> 1) != wk) continue;   // wave-uniform
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(st + aoff[ks]);
             const int c0 = 4 * (ks & 1) + 2 * g;
             const f32x4 h0 = *reinterpret_cast<const f32x4 *>(st + boff[ks] + ((c0 ^ bsw) * 16));
@@ -455,21 +465,28 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
         const int big_blocks = (rows + 63) / 64, units = m.Hp / kRtTile;
         if (big_blocks * units > 256) {                 // several 64 x 64 workgroups per compute unit
             dim3 grid(kXcds * ((big_blocks + kXcds - 1) / kXcds) * units);
-            hipLaunchKernelGGL((recur_bf16_tiled_kernel<2, 64>), grid, dim3(256), 2 * RtCfg<64>::kStageBytes, stream, m,
-                               rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
+            hipLaunchKernelGGL((recur_bf16_tiled_kernel<2, 64, 1>), grid, dim3(256), 2 * RtCfg<64>::kStageBytes, stream,
+                               m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
         } else {                                        // small problem: 64 x 32, all compute units
-            static bool attr_set = false;               // 64 KB of stages + the static row map: above the default limit
+            static bool attr_set = false;               // more than the default 64 KB of dynamic LDS
             if (!attr_set) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32>),
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 1>),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                                    4 * RtCfg<32>::kStageBytes);
+                if (e == hipSuccess)
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 2>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 8 * RtCfg<32>::kStageBytes);
                 if (e != hipSuccess) return e;
                 attr_set = true;
             }
             const int small_blocks = (rows + 31) / 32;
             dim3 grid(kXcds * ((small_blocks + kXcds - 1) / kXcds) * units);
-            hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32>), grid, dim3(256), 4 * RtCfg<32>::kStageBytes, stream, m,
-                               rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
+            if (m.Hp % 128 == 0)
+                hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32, 2>), grid, dim3(256), 8 * RtCfg<32>::kStageBytes,
+                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
+            else
+                hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32, 1>), grid, dim3(256), 4 * RtCfg<32>::kStageBytes,
+                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
         }
     } else if (m.dtype == RNNLM_BF16) {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);
