@@ -55,21 +55,29 @@ __global__ __launch_bounds__(kSmallThreads) void dedup_small_kernel(
     __shared__ int wsum[kSmallThreads / 64 + 1];
     constexpr int kPer = kSmallN / kSmallThreads;      // queries per thread
 
-    for (int i = threadIdx.x; i <= kSmallCap; i += kSmallThreads) {
+    // Thread t owns the `per` contiguous queries from t * per on (per = ceil(N / threads), so all
+    // threads take part whatever N is); contiguous ownership makes the scan below run over
+    // raw-index order.  The keys are fetched first, all at once: an insertion is a loop around an
+    // LDS atomic, and a load behind it would wait for it.
+    const int per = (N + kSmallThreads - 1) / kSmallThreads;
+    uint64_t key[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int n = threadIdx.x * per + i;
+        key[i] = (i < per && n < N) ? keys[n] : 0;
+    }
+    for (int i = threadIdx.x; i <= kSmallCap; i += kSmallThreads) {     // while the keys are on their way
         tkeys[i] = kEmpty;
         tfirst[i] = 0x7FFFFFFF;
     }
     __syncthreads();
-
-    // Thread t owns the contiguous queries t*kPer .. t*kPer+kPer-1, so that the scan below
-    // runs over raw-index order.
     int slot[kPer];
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-        int n = threadIdx.x * kPer + i;
+        const int n = threadIdx.x * per + i;
         slot[i] = -1;
-        if (n < N) {
-            slot[i] = find_or_insert(tkeys, kSmallCap, keys[n]);
+        if (i < per && n < N) {
+            slot[i] = find_or_insert(tkeys, kSmallCap, key[i]);
             atomicMin(&tfirst[slot[i]], n);
         }
     }
@@ -79,8 +87,8 @@ __global__ __launch_bounds__(kSmallThreads) void dedup_small_kernel(
     int mine = 0;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-        int n = threadIdx.x * kPer + i;
-        is_first[i] = (n < N && tfirst[slot[i]] == n) ? 1 : 0;
+        int n = threadIdx.x * per + i;
+        is_first[i] = (slot[i] >= 0 && tfirst[slot[i]] == n) ? 1 : 0;
         mine += is_first[i];
     }
     int total;
@@ -88,7 +96,7 @@ __global__ __launch_bounds__(kSmallThreads) void dedup_small_kernel(
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
         if (is_first[i]) {
-            int n = threadIdx.x * kPer + i;
+            int n = threadIdx.x * per + i;
             rep[u] = n;
             tfirst[slot[i]] = u;                       // the slot now carries its group number
             ++u;
@@ -97,8 +105,8 @@ __global__ __launch_bounds__(kSmallThreads) void dedup_small_kernel(
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
-        int n = threadIdx.x * kPer + i;
-        if (n < N) inverse[n] = tfirst[slot[i]];
+        int n = threadIdx.x * per + i;
+        if (slot[i] >= 0) inverse[n] = tfirst[slot[i]];
     }
     if (threadIdx.x == 0) *n_unique = total;
 }
