@@ -35,11 +35,15 @@ __global__ __launch_bounds__(256) void query_kernel(
     if (n >= N) return;                                  // wave-uniform; no barrier in this kernel
     const int kwave = wave % kWavesPerQuery;             // this wave takes words kwave, kwave + 4/QPW, ...
     const int H = m.H, Hp = m.Hp;
+    // The word ids of the first batch depend on n only: requested before anything that hangs on the
+    // row index, so that the weight rows can follow one memory latency after the start, not three.
+    const int umine = batch_slot_of_lane(lane);
+    const int k_first = kwave + kWavesPerQuery * umine;
+    const int q_first = (k_first < K) ? query_word[(size_t)n * K + k_first] : 0;
     const int r_raw = row_of_query ? row_of_query[n] : n;
     const bool r_ok = r_raw >= 0 && r_raw < B;
     const int r = r_ok ? r_raw : 0;                      // a bad row is computed on row 0 and then dropped
     float *out = logprob + (size_t)n * K;
-    const int umine = batch_slot_of_lane(lane);
     const bool writer = (lane & 7) == 0;
 
     // lse of row r: handed in, or merged from the partials (lane l takes splits l, l+64, ...)
@@ -65,7 +69,7 @@ __global__ __launch_bounds__(256) void query_kernel(
         // this lane's word of the batch, its bias and base score
         const int kmine = kb + kWavesPerQuery * umine;
         const bool k_ok = kmine < K;
-        const int qmine = k_ok ? query_word[(size_t)n * K + kmine] : 0;
+        const int qmine = (kb == kwave) ? q_first : (k_ok ? query_word[(size_t)n * K + kmine] : 0);
         const bool q_ok = qmine >= 0 && qmine < m.V;
         const int qsafe = q_ok ? qmine : 0;
         const float bias_mine = m.bias[qsafe];
