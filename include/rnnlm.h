@@ -69,8 +69,11 @@ enum rnnlm_option {
      * kernel, 2 = the LDS-staged kernel with the hidden block held in registers (bf16,
      * H <= 512), 3 = the LDS-tiled kernel for any hidden size and both types, 4 = (fp32 models)
      * the bf16 LDS-tiled kernel on the three-term bf16 split of both operands, fp32 accuracy at
-     * matrix-core speed: the automatic choice for fp32 from 64 rows on.  EINVAL if the model does
-     * not allow the choice. */
+     * matrix-core speed: the automatic choice for fp32 from 64 rows on, 5 = (bf16 models) the
+     * weight-streaming kernel for few rows, which reads a second, operand-ordered copy of the
+     * output weights once at memory speed: the automatic choice up to 64 rows; it serves as many
+     * rows as fit its LDS (128 up to H = 512, 64 up to H = 1024, 32 up to H = 2048) and larger
+     * batches go the automatic way.  EINVAL if the model does not allow the choice. */
     RNNLM_OPT_OUTPROJ_KERNEL = 2
 };
 

@@ -46,6 +46,7 @@ void free_dev(rnnlm_model *m) {
     (void)hipFree(d.part);
     (void)hipFree(d.flag);
     (void)hipFree(const_cast<void *>(d.Ot3));
+    (void)hipFree(const_cast<void *>(d.Ofrag));
     (void)hipFree(d.d3);
     (void)hipFree(const_cast<void *>(d.Theta));
     (void)hipFree(const_cast<int32_t *>(d.path_off));
@@ -229,6 +230,10 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     }
     HIP_TRY(launch_fill_cvec(bias_stage, d.half_colsum_O, V, Vp, d.m2_fixed, const_cast<float *>(d.bias),
                              const_cast<float *>(d.cvec2), const_cast<float *>(d.cvec2_fixed), nullptr));
+    if (dtype == RNNLM_BF16) {      // operand-ordered copy for the weight-streaming kernel (few rows)
+        HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * 2)); d.Ofrag = p;
+        HIP_TRY(launch_frag_weights(d.Ot, Vp, Hp, const_cast<void *>(d.Ofrag), nullptr));
+    }
     if (dtype == RNNLM_F32) {       // three-term bf16 split of the weights, scratch for that of the hidden block
         HIP_TRY(hipMalloc(&p, (size_t)Vp * 6 * Hp * 2)); d.Ot3 = p;
         HIP_TRY(hipMalloc(&p, (size_t)max_Bp * 6 * Hp * 2)); d.d3 = p;
@@ -265,8 +270,9 @@ int rnnlm_set_option(rnnlm_model *model, int option, int value) {
             model->lse_mode = value;
             return RNNLM_OK;
         case RNNLM_OPT_OUTPROJ_KERNEL:
-            if (value < 0 || value > 4) return RNNLM_EINVAL;
+            if (value < 0 || value > 5) return RNNLM_EINVAL;
             if (model->dev.hs) return RNNLM_EINVAL;
+            if (value == 5 && outproj_stream_max_rows(model->dev) == 0) return RNNLM_EINVAL;
             if (value == 4 && !model->dev.Ot3) return RNNLM_EINVAL;
             if (value == 2 && !outproj_staged_supported(model->dev)) return RNNLM_EINVAL;
             model->outproj_kernel = value;

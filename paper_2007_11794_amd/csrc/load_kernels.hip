@@ -83,7 +83,26 @@ __global__ __launch_bounds__(256) void split3_weights_kernel(const float *__rest
     for (int s = 0; s < 6; ++s) Ot3[v * 6 * Hp + (size_t)s * Hp + j] = t[RNNLM_SPLIT3_W(s)];
 }
 
+// bf16 [Vp][Hp] weights re-laid in MFMA-operand order: 16 bytes per thread.
+__global__ __launch_bounds__(256) void frag_weights_kernel(const u32x4 *__restrict__ Ot, size_t n, int KS,
+                                                           u32x4 *__restrict__ Ofrag) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;       // (blk, ks, lane)
+    if (i >= n) return;
+    const int lane = (int)(i & 63);
+    const size_t frag = i >> 6, blk = frag / KS;
+    const int ks = (int)(frag % KS);
+    const size_t word = blk * 32 + (lane & 31);
+    Ofrag[i] = Ot[word * (2 * KS) + 2 * ks + (lane >> 5)];           // 2 KS chunks of 8 units per word
+}
+
 }  // namespace
+
+hipError_t launch_frag_weights(const void *Ot, int Vp, int Hp, void *Ofrag, hipStream_t stream) {
+    const size_t n = (size_t)Vp * Hp / 8;
+    hipLaunchKernelGGL(frag_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const u32x4 *>(Ot), n, Hp / 16, static_cast<u32x4 *>(Ofrag));
+    return hipGetLastError();
+}
 
 hipError_t launch_split3_weights(const float *Ot, int Vp, int Hp, void *Ot3, hipStream_t stream) {
     const size_t n = (size_t)Vp * Hp;

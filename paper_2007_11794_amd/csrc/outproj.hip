@@ -197,12 +197,20 @@ hipError_t launch_outproj_staged(const ModelDev &m, int rows, const int *B_dev, 
 hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                 SplitInfo *splits, hipStream_t stream);
 
+// defined in outproj_stream.hip
+hipError_t launch_outproj_stream(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                                 SplitInfo *splits, hipStream_t stream);
+
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream) {
     splits->fixed_splits = 1;
     splits->staged_wg_per_xcd = 0;
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16) {
+        const int stream_rows = outproj_stream_max_rows(m);
+        // few rows: the time is the time to read the weights once
+        const bool streamed = rows <= stream_rows && (kernel_choice == 5 || (kernel_choice == 0 && rows <= 64));
+        if (streamed) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
         const bool staged = kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128);
         if (staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
         const bool tiled = kernel_choice == 3 || (kernel_choice == 0 && rows >= 64);

@@ -39,6 +39,10 @@ struct ModelDev {
     // add exactly those six terms: weights [x1 | x1 | x2 | x1 | x3 | x2], hidden block
     // [d1 | d2 | d1 | d3 | d1 | d2].
     const void *Ot3;   // [Vp][6 Hp] bf16, or null
+    // bf16 models: a second copy of the output weights in MFMA-operand order for the kernel that
+    // streams them for few rows, [Vp / 32][Hp / 16][64 lanes][8]: lane 32 g + c of fragment
+    // (blk, ks) holds word 32 blk + c, units 16 ks + 8 g .. + 7 (one operand = 1 KB contiguous).
+    const void *Ofrag;
     void *d3;          // [max_Bp][6 Hp] bf16 scratch, or null
     // hierarchical output layer (models loaded with rnnlm_hs_load; Ot .. cvec2_fixed are null then)
     int hs;                       // 1: hierarchical
@@ -161,6 +165,7 @@ __host__ __device__ inline StagedPlan staged_plan(int B, int wg_per_xcd) {
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream);
 bool outproj_staged_supported(const ModelDev &m);
+int outproj_stream_max_rows(const ModelDev &m);   // 0: the weight-streaming kernel cannot serve this model
 
 // Query gather: logprob[n][k] = z[row(n)][query[n][k]] - lse[row(n)] - base_score[n][k].
 // lse comes from lse_rows[row] when that is given, else from the partials in m.part;
@@ -208,6 +213,7 @@ hipError_t launch_transpose_O(const void *O_dev /*[H][V]*/, void *Ot /*[Vp][Hp]*
 hipError_t launch_col_stats(const void *O_dev, const float *bias_or_null, int dtype, int H, int V,
                             float *half_colsum /*[V]*/, float *upper /*[V]*/, float *lower /*[V]*/,
                             hipStream_t stream);
+hipError_t launch_frag_weights(const void *Ot /*[Vp][Hp] bf16*/, int Vp, int Hp, void *Ofrag, hipStream_t stream);
 hipError_t launch_split3_weights(const float *Ot /*[Vp][Hp]*/, int Vp, int Hp, void *Ot3 /*[Vp][6 Hp] bf16*/,
                                  hipStream_t stream);
 hipError_t launch_fill_cvec(const float *bias_or_null, const float *half_colsum, int V, int Vp,

@@ -76,8 +76,12 @@ def test_config2_chained_steps_full():
     (300, 64, 33, 2),
     (2000, 1024, 200, 4),     # hidden size beyond the staged kernel: tiled kernel (128-row tiles) by default
     (1500, 640, 300, 4),      # tiled kernel with 256-row tiles, hidden size not a power of two
+    (4000, 512, 29, 4),       # few rows: the weight-streaming kernel by default (one row block)
+    (2100, 320, 64, 3),       # two row blocks in the streaming kernel, five groups per word block
+    (900, 1024, 50, 2),       # the longest reduction the streaming kernel takes two row blocks of
+    (3000, 256, 127, 2),      # four row blocks (on request only)
 ])
-@pytest.mark.parametrize("kernel", [1, 2, 3])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 5])
 @pytest.mark.parametrize("lse_mode", [1, 2])
 def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
     cfg = CONFIGS[3].scaled(V=V, H=H, B=B, K=K)
@@ -85,10 +89,12 @@ def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
     m = load_model(model, "bf16", B)
     m.set_option(rn.OPT_LSE_MODE, lse_mode)
-    if kernel == 2 and H > 512:
+    if kernel == 2 and max(128, -(-H // 64) * 64) not in (128, 256, 512):   # no staged kernel for this hidden size
         with pytest.raises(rn.RnnlmError):
             m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
         kernel = 0                      # automatic choice instead (the tiled kernel at this size)
+    # kernel 5 (weight streaming) serves up to 128 rows at these hidden sizes and hands larger
+    # batches to the automatic choice
     m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
     h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
     check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), "bf16",
@@ -137,6 +143,27 @@ def test_config3_headline_full_size_sampled():
     assert np.max(np.abs(outs[0][1] - outs[1][1])) <= 1e-4
     # properties that hold at any size: finite, log-probabilities negative
     assert np.all(np.isfinite(outs[0][1])) and np.all(outs[0][1] < 0)
+    assert m.last_error() == 0
+    m.close()
+
+
+def test_config3_model_few_rows_full_vocabulary():
+    """The headline model with the few distinct histories a well-cached search leaves per step
+    (Section 5.2): every row against the oracle, in the configuration the library picks by itself
+    (the weight-streaming kernel), and against the plain kernel."""
+    cfg = CONFIGS[3]
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    m = load_model(model, cfg.dtype, 64)
+    for B in (1, 7, 32, 33, 64):
+        prev, h_in, query = x["prev"][:B], x["h_in"][:B], x["query"][:B]
+        ref = oracle.step(model, prev, h_in, query)
+        m.set_option(rn.OPT_OUTPROJ_KERNEL, 0)
+        h, lp = gpu_step(m, prev, h_in, query)
+        check(h, lp, ref, "bf16", "cfg3 model, %d rows" % B)
+        m.set_option(rn.OPT_OUTPROJ_KERNEL, 1)
+        h1, lp1 = gpu_step(m, prev, h_in, query)
+        assert np.array_equal(h1, h) and np.max(np.abs(lp1 - lp)) <= 1e-4
     assert m.last_error() == 0
     m.close()
 
