@@ -23,10 +23,14 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3         # MI355X fp32 vector (and fp32 matrix), published
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 # HBM bytes per launch of the output-projection kernel on this workload, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain copy of known size; cannot be measured live.
 # Source and commands: profiles/step_kernels_cfg3_large_vocab_hbm_traffic.md
 OUTPROJ_TRAFFIC_BYTES = {"staged": 78.0e6}
+# The same for the weight-streaming kernel (few rows), by workload number (FETCH_SIZE only: it
+# writes 8 KB).  Source and commands: profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md
+STREAM_TRAFFIC_BYTES = {3: 67.8e6, 5: 411.5e6}
 
 
 def bench_hs(args, cfg, rn, torch, np) -> int:
@@ -167,7 +171,13 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--outproj-kernel", type=int, default=0,
-                    help="0 auto, 1 plain, 2 staged, 3 tiled, 4 bf16 three-term split (fp32 models)")
+                    help="0 auto, 1 plain, 2 staged, 3 tiled, 4 bf16 three-term split (fp32 models), "
+                         "5 weight streaming (bf16 models, few rows)")
+    ap.add_argument("--rows", type=int, default=None, metavar="B",
+                    help="the chosen workload with only B rows per step (full-softmax workloads 1, 2, 3, 5): "
+                         "the few distinct histories a well-cached search leaves; up to 64 rows of a bf16 "
+                         "model the output projection is then bound by reading the weights once, and the "
+                         "roofline is reported against HBM bandwidth")
     ap.add_argument("--lse-mode", type=int, default=0, help="0 auto, 1 running max, 2 fixed offset")
     ap.add_argument("--config", type=int, default=3,
                     help="workload number (default 3 = the headline one the metric is quoted on; "
@@ -205,6 +215,12 @@ def main() -> int:
     rn.lib()                                   # raises if librnnlm.so is not built
     dev = "cuda:0"
     cfg = CONFIGS[args.config]
+    if args.rows is not None:
+        if cfg.unique_frac is not None or args.rows < 1 or args.rows > cfg.B:
+            print("bench.py: --rows needs a workload without a decode trace and 1 <= B <= its row count",
+                  file=sys.stderr)
+            return 2
+        cfg = cfg.scaled(B=args.rows)
     if args.index_table:
         return bench_index_table(args, cfg, rn, torch, np)
     if args.hs:
@@ -315,12 +331,25 @@ def main() -> int:
         flops *= 6.0
     achieved = flops / (k3_ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if on_mfma else PEAK_FP32_TFLOPS
-    roofline = {"kernel": "outproj_lse" + (" (fp32 as 6 bf16 products)" if split3 else ""),
-                "bound": "mfma" if on_mfma else "alu", "achieved": round(achieved, 2), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) and args.config == 3 else None,
-                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
-                "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
+    streamed = bf16 and B <= 64 and args.outproj_kernel in (0, 5)
+    if streamed:
+        # few rows: the launch reads the (padded) output weights once, nothing else of size
+        Hp, Vp = -(-cfg.H // 64) * 64, -(-cfg.V // 256) * 256
+        wbytes = float(Hp) * Vp * 2
+        gbs = wbytes / (k3_ms * 1e-3) / 1e9
+        roofline = {"kernel": "outproj_lse (weight streaming, %d rows)" % B, "bound": "hbm",
+                    "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": STREAM_TRAFFIC_BYTES.get(args.config),
+                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE, copy-calibrated)",
+                    "us_per_launch": round(k3_ms * 1e3, 2), "bytes_per_launch": wbytes,
+                    "flop_per_launch": flops}
+    else:
+        roofline = {"kernel": "outproj_lse" + (" (fp32 as 6 bf16 products)" if split3 else ""),
+                    "bound": "mfma" if on_mfma else "alu", "achieved": round(achieved, 2), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                    "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) and args.config == 3 and args.rows is None else None,
+                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
+                    "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
 
     gemm_ref = None
     if args.gemm_reference and bf16:
@@ -380,7 +409,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "%s%s: V=%d H=%d N=%d raw queries (%d distinct histories) K=%d, %s weights "
                                "N(0,%g), Zipf(%g) word ids (0 = uniform), one step incl. history-id grouping"
-                               % (cfg.name, " (headline)" if args.config == 3 else "", cfg.V, cfg.H, cfg.N, B, cfg.K,
+                               % (cfg.name, (" (headline)" if args.config == 3 else "") if args.rows is None
+                                  else " cut to %d rows" % args.rows, cfg.V, cfg.H, cfg.N, B, cfg.K,
                                   cfg.dtype, cfg.sigma, cfg.zipf_s or 0),
                    "V": cfg.V, "H": cfg.H, "B": B, "N": cfg.N, "K": cfg.K},
         "roofline": roofline,
