@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 OUTPROJ_TRAFFIC_BYTES = {"staged": 78.0e6}
 # The same for the weight-streaming kernel (few rows), by workload number (FETCH_SIZE only: it
 # writes 8 KB).  Source and commands: profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md
-STREAM_TRAFFIC_BYTES = {3: 67.8e6, 5: 411.5e6}
+STREAM_TRAFFIC_BYTES = {2: 21.2e6, 3: 67.8e6, 5: 411.5e6}
 
 
 def bench_hs(args, cfg, rn, torch, np) -> int:
@@ -323,19 +323,23 @@ def main() -> int:
     k3_ms = m.time_outproj(B, reps)
     k3_ms = min(k3_ms, m.time_outproj(B, reps))
     flops = 2.0 * B * cfg.H * cfg.V
-    # fp32 models run the contraction on the bf16 matrix cores from 64 rows on: six bf16 products
-    # per fp32 product (three-term split of both operands), so the launch does 6x the flops
-    split3 = (not bf16) and B >= 64 and args.outproj_kernel in (0, 4)
+    # fp32 models run the contraction on the bf16 matrix cores (from 64 rows on the tiled kernel,
+    # below that the weight-streaming one when H <= 768): six bf16 products per fp32 product
+    # (three-term split of both operands), so the launch does 6x the flops
+    split3 = (not bf16) and args.outproj_kernel in (0, 4, 5) and (B >= 64 or cfg.H <= 768 or args.outproj_kernel == 4)
     on_mfma = bf16 or split3
     if split3:
         flops *= 6.0
     achieved = flops / (k3_ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if on_mfma else PEAK_FP32_TFLOPS
-    streamed = bf16 and B <= 64 and args.outproj_kernel in (0, 5)
+    # few rows (one launch of the weight-streaming kernel: up to 64 rows of a bf16 model with
+    # H <= 1216, up to 32 rows of an fp32 model with H <= 768): the launch reads the (padded) output
+    # weights once, nothing else of size
+    streamed = args.outproj_kernel in (0, 5) and ((bf16 and B <= 64 and cfg.H <= 1216) or
+                                                  (not bf16 and B <= 32 and cfg.H <= 768))
     if streamed:
-        # few rows: the launch reads the (padded) output weights once, nothing else of size
-        Hp, Vp = -(-cfg.H // 64) * 64, -(-cfg.V // 256) * 256
-        wbytes = float(Hp) * Vp * 2
+        Hp, Vp = max(128 if bf16 else 64, -(-cfg.H // 64) * 64), -(-cfg.V // 256) * 256
+        wbytes = float(Hp) * Vp * (2 if bf16 else 4)
         gbs = wbytes / (k3_ms * 1e-3) / 1e9
         roofline = {"kernel": "outproj_lse (weight streaming, %d rows)" % B, "bound": "hbm",
                     "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",

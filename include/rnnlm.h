@@ -69,11 +69,14 @@ enum rnnlm_option {
      * kernel, 2 = the LDS-staged kernel with the hidden block held in registers (bf16,
      * H <= 512), 3 = the LDS-tiled kernel for any hidden size and both types, 4 = (fp32 models)
      * the bf16 LDS-tiled kernel on the three-term bf16 split of both operands, fp32 accuracy at
-     * matrix-core speed: the automatic choice for fp32 from 64 rows on, 5 = (bf16 models) the
-     * weight-streaming kernel for few rows, which reads a second, operand-ordered copy of the
-     * output weights once at memory speed: the automatic choice up to 64 rows; it serves as many
-     * rows as fit its LDS (128 up to H = 512, 64 up to H = 1024, 32 up to H = 2048) and larger
-     * batches go the automatic way.  EINVAL if the model does not allow the choice. */
+     * matrix-core speed: the automatic choice for fp32 from 64 rows on, 5 = the weight-
+     * streaming kernel for few rows, which reads a second, operand-ordered copy of the output
+     * weights once per launch at memory speed (fp32 models: cut into three bf16 terms in registers,
+     * fp32 accuracy): the automatic choice up to 64 rows when two launches suffice.  One launch
+     * serves as many rows as fit its LDS (bf16: 128 up to H = 576, 64 up to H = 1216, 32 up to
+     * H = 2432; fp32: 128 up to H = 192, 64 up to H = 384, 32 up to H = 768); on request it takes
+     * up to 128 rows in at most four launches, and larger batches go the automatic way.
+     * EINVAL if the model does not allow the choice. */
     RNNLM_OPT_OUTPROJ_KERNEL = 2
 };
 

@@ -230,10 +230,9 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     }
     HIP_TRY(launch_fill_cvec(bias_stage, d.half_colsum_O, V, Vp, d.m2_fixed, const_cast<float *>(d.bias),
                              const_cast<float *>(d.cvec2), const_cast<float *>(d.cvec2_fixed), nullptr));
-    if (dtype == RNNLM_BF16) {      // operand-ordered copy for the weight-streaming kernel (few rows)
-        HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * 2)); d.Ofrag = p;
-        HIP_TRY(launch_frag_weights(d.Ot, Vp, Hp, const_cast<void *>(d.Ofrag), nullptr));
-    }
+    // operand-ordered copy for the weight-streaming kernels (few rows)
+    HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * es)); d.Ofrag = p;
+    HIP_TRY(launch_frag_weights(d.Ot, dtype, Vp, Hp, const_cast<void *>(d.Ofrag), nullptr));
     if (dtype == RNNLM_F32) {       // three-term bf16 split of the weights, scratch for that of the hidden block
         HIP_TRY(hipMalloc(&p, (size_t)Vp * 6 * Hp * 2)); d.Ot3 = p;
         HIP_TRY(hipMalloc(&p, (size_t)max_Bp * 6 * Hp * 2)); d.d3 = p;

@@ -95,12 +95,31 @@ __global__ __launch_bounds__(256) void frag_weights_kernel(const u32x4 *__restri
     Ofrag[i] = Ot[word * (2 * KS) + 2 * ks + (lane >> 5)];           // 2 KS chunks of 8 units per word
 }
 
+// fp32 [Vp][Hp] weights in the same operand order, 32 bytes per lane as two 16-byte halves:
+// [blk][ks][half][64 lanes][4 floats], lane 32 g + c: word 32 blk + c, units 16 ks + 8 g + 4 half .. + 3.
+__global__ __launch_bounds__(256) void frag_weights_f32_kernel(const u32x4 *__restrict__ Ot, size_t n, int KS,
+                                                               u32x4 *__restrict__ Ofrag) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;       // (blk, ks, half, lane)
+    if (i >= n) return;
+    const int lane = (int)(i & 63), half = (int)((i >> 6) & 1);
+    const size_t frag = i >> 7, blk = frag / KS;
+    const int ks = (int)(frag % KS);
+    const size_t word = blk * 32 + (lane & 31);
+    Ofrag[i] = Ot[word * (4 * KS) + 4 * ks + 2 * (lane >> 5) + half];   // 4 KS chunks of 4 units per word
+}
+
 }  // namespace
 
-hipError_t launch_frag_weights(const void *Ot, int Vp, int Hp, void *Ofrag, hipStream_t stream) {
-    const size_t n = (size_t)Vp * Hp / 8;
-    hipLaunchKernelGGL(frag_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
-                       static_cast<const u32x4 *>(Ot), n, Hp / 16, static_cast<u32x4 *>(Ofrag));
+hipError_t launch_frag_weights(const void *Ot, int dtype, int Vp, int Hp, void *Ofrag, hipStream_t stream) {
+    if (dtype == RNNLM_BF16) {
+        const size_t n = (size_t)Vp * Hp / 8;
+        hipLaunchKernelGGL(frag_weights_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                           static_cast<const u32x4 *>(Ot), n, Hp / 16, static_cast<u32x4 *>(Ofrag));
+    } else {
+        const size_t n = (size_t)Vp * Hp / 4;
+        hipLaunchKernelGGL(frag_weights_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                           static_cast<const u32x4 *>(Ot), n, Hp / 16, static_cast<u32x4 *>(Ofrag));
+    }
     return hipGetLastError();
 }
 

@@ -201,16 +201,24 @@ hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, b
 hipError_t launch_outproj_stream(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                  SplitInfo *splits, hipStream_t stream);
 
+// Few rows: the time is the time to read the weights once (per launch: the streaming kernel holds
+// 32 to 128 rows in LDS, depending on the model).  By itself up to 64 rows in at most two launches;
+// on request up to 128 rows in at most four.
+static bool stream_choice(const ModelDev &m, int rows, int kernel_choice) {
+    const int per = outproj_stream_max_rows(m);
+    if (per == 0) return false;
+    const int launches = (rows + per - 1) / per;
+    if (kernel_choice == 5) return rows <= 128 && launches <= 4;
+    return kernel_choice == 0 && rows <= 64 && launches <= 2;
+}
+
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream) {
     splits->fixed_splits = 1;
     splits->staged_wg_per_xcd = 0;
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16) {
-        const int stream_rows = outproj_stream_max_rows(m);
-        // few rows: the time is the time to read the weights once
-        const bool streamed = rows <= stream_rows && (kernel_choice == 5 || (kernel_choice == 0 && rows <= 64));
-        if (streamed) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
+        if (stream_choice(m, rows, kernel_choice)) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
         const bool staged = kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128);
         if (staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
         const bool tiled = kernel_choice == 3 || (kernel_choice == 0 && rows >= 64);
@@ -230,6 +238,7 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
         // bf16 products per fp32 product at sixteen times the fp32 matrix rate, same accuracy).
         // The tiled fp32-MFMA kernel only on request; at the WSJ-sized workload it is no faster
         // than the FMA kernel below.
+        if (stream_choice(m, rows, kernel_choice)) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
         if (kernel_choice == 3) return launch_outproj_tiled(m, rows, B_dev, fixed_offset, splits, stream);
         if (m.Ot3 && (kernel_choice == 4 || (kernel_choice == 0 && rows >= 64))) {
             ModelDev v = m;

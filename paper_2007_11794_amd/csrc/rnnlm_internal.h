@@ -39,9 +39,10 @@ struct ModelDev {
     // add exactly those six terms: weights [x1 | x1 | x2 | x1 | x3 | x2], hidden block
     // [d1 | d2 | d1 | d3 | d1 | d2].
     const void *Ot3;   // [Vp][6 Hp] bf16, or null
-    // bf16 models: a second copy of the output weights in MFMA-operand order for the kernel that
-    // streams them for few rows, [Vp / 32][Hp / 16][64 lanes][8]: lane 32 g + c of fragment
-    // (blk, ks) holds word 32 blk + c, units 16 ks + 8 g .. + 7 (one operand = 1 KB contiguous).
+    // A second copy of the output weights in MFMA-operand order for the kernels that stream them
+    // for few rows.  bf16: [Vp / 32][Hp / 16][64 lanes][8], lane 32 g + c of fragment (blk, ks)
+    // holds word 32 blk + c, units 16 ks + 8 g .. + 7 (one operand = 1 KB contiguous).  fp32: the
+    // same operand as two halves of four floats, [Vp / 32][Hp / 16][2][64 lanes][4].
     const void *Ofrag;
     void *d3;          // [max_Bp][6 Hp] bf16 scratch, or null
     // hierarchical output layer (models loaded with rnnlm_hs_load; Ot .. cvec2_fixed are null then)
@@ -213,7 +214,7 @@ hipError_t launch_transpose_O(const void *O_dev /*[H][V]*/, void *Ot /*[Vp][Hp]*
 hipError_t launch_col_stats(const void *O_dev, const float *bias_or_null, int dtype, int H, int V,
                             float *half_colsum /*[V]*/, float *upper /*[V]*/, float *lower /*[V]*/,
                             hipStream_t stream);
-hipError_t launch_frag_weights(const void *Ot /*[Vp][Hp] bf16*/, int Vp, int Hp, void *Ofrag, hipStream_t stream);
+hipError_t launch_frag_weights(const void *Ot /*[Vp][Hp]*/, int dtype, int Vp, int Hp, void *Ofrag, hipStream_t stream);
 hipError_t launch_split3_weights(const float *Ot /*[Vp][Hp]*/, int Vp, int Hp, void *Ot3 /*[Vp][6 Hp] bf16*/,
                                  hipStream_t stream);
 hipError_t launch_fill_cvec(const float *bias_or_null, const float *half_colsum, int V, int Vp,

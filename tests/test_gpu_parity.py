@@ -103,14 +103,19 @@ def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
     m.close()
 
 
-@pytest.mark.parametrize("V,H,B,K", [(3000, 200, 150, 6), (1000, 64, 8, 4)])
+@pytest.mark.parametrize("V,H,B,K", [(3000, 200, 150, 6), (1000, 64, 8, 4),
+                                     (2500, 512, 61, 3),      # few rows: weight streaming, two launches of 32 rows
+                                     (1200, 256, 64, 2),      # one launch, two row blocks
+                                     (700, 768, 17, 2),       # the longest reduction whose three terms fit in LDS
+                                     (900, 100, 97, 2)])      # on request only: four row blocks
 def test_f32_reduced_elementwise_both_lse_modes(V, H, B, K):
     cfg = CONFIGS[2].scaled(V=V, H=H, B=B, K=K)
     model = make_model(cfg)
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + V))
     m = load_model(model, "f32", B)
     ref = oracle.step(model, x["prev"], x["h_in"], x["query"])
-    for kernel in (1, 3, 4, 0):                 # plain FMA, LDS-tiled fp32-MFMA, bf16 three-term split, automatic
+    # plain FMA, LDS-tiled fp32-MFMA, bf16 three-term split, weight streaming (where it applies), automatic
+    for kernel in (1, 3, 4, 5, 0):
         m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
         for lse_mode in (1, 2):
             m.set_option(rn.OPT_LSE_MODE, lse_mode)
