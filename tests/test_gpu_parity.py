@@ -76,6 +76,7 @@ def test_config2_chained_steps_full():
     (300, 64, 33, 2),
     (2000, 1024, 200, 4),     # hidden size beyond the staged kernel: tiled kernel (128-row tiles) by default
     (1500, 640, 300, 4),      # tiled kernel with 256-row tiles, hidden size not a power of two
+    (2600, 640, 250, 3),      # tiled kernel, 128 words x 256 rows per workgroup with three stages
     (4000, 512, 29, 4),       # few rows: the weight-streaming kernel by default (one row block)
     (2100, 320, 64, 3),       # two row blocks in the streaming kernel, five groups per word block
     (900, 1024, 50, 2),       # the longest reduction the streaming kernel takes two row blocks of
