@@ -68,8 +68,8 @@ enum rnnlm_option {
     /* Which output-projection kernel: 0 = automatic (default), 1 = the plain any-shape
      * kernel, 2 = the LDS-staged kernel with the hidden block held in registers (bf16,
      * H <= 512), 3 = the LDS-tiled kernel for any hidden size and both types, 4 = (fp32 models)
-     * the bf16 LDS-tiled kernel on the three-term bf16 split of both operands, fp32 accuracy at
-     * matrix-core speed: the automatic choice for fp32 from 64 rows on, 5 = the weight-
+     * the LDS-tiled kernel on the three-term bf16 split of both operands, fp32 accuracy at
+     * bf16 matrix-core speed: the automatic choice for fp32 from 64 rows on, 5 = the weight-
      * streaming kernel for few rows, which reads a second, operand-ordered copy of the output
      * weights once per launch at memory speed (fp32 models: cut into three bf16 terms in registers,
      * fp32 accuracy): the automatic choice up to 64 rows when two launches suffice.  One launch

@@ -234,9 +234,9 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * es)); d.Ofrag = p;
     HIP_TRY(launch_frag_weights(d.Ot, dtype, Vp, Hp, const_cast<void *>(d.Ofrag), nullptr));
     if (dtype == RNNLM_F32) {       // three-term bf16 split of the weights, scratch for that of the hidden block
-        HIP_TRY(hipMalloc(&p, (size_t)Vp * 6 * Hp * 2)); d.Ot3 = p;
-        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * 6 * Hp * 2)); d.d3 = p;
-        HIP_TRY(hipMemset(d.d3, 0, (size_t)max_Bp * 6 * Hp * 2));
+        HIP_TRY(hipMalloc(&p, (size_t)Vp * 3 * Hp * 2)); d.Ot3 = p;
+        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * 3 * Hp * 2)); d.d3 = p;
+        HIP_TRY(hipMemset(d.d3, 0, (size_t)max_Bp * 3 * Hp * 2));
         HIP_TRY(launch_split3_weights(static_cast<const float *>(d.Ot), Vp, Hp, const_cast<void *>(d.Ot3), nullptr));
     }
     HIP_TRY(hipDeviceSynchronize());

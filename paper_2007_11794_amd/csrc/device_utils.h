@@ -34,10 +34,6 @@ __device__ __forceinline__ void split3_bf16(float x, uint16_t &x1, uint16_t &x2,
     const uint32_t p3 = pack_bf16x2(r2, 0.f);
     x1 = (uint16_t)p1; x2 = (uint16_t)p2; x3 = (uint16_t)p3;
 }
-// Segment s = 0..5 of the 6 Hp long reduction pairs weight term kSplit3W[s] with hidden term
-// kSplit3D[s]: (1,1) (1,2) (2,1) (1,3) (3,1) (2,2), written 0-based.
-#define RNNLM_SPLIT3_W(s) ((s) == 2 ? 1 : (s) == 4 ? 2 : (s) == 5 ? 1 : 0)
-#define RNNLM_SPLIT3_D(s) ((s) == 1 ? 1 : (s) == 3 ? 2 : (s) == 5 ? 1 : 0)
 
 // Eight consecutive weights starting at element index `at` (a multiple of 8) as floats.
 __device__ __forceinline__ void load8_weights(const uint16_t *p, size_t at, float (&out)[8]) {

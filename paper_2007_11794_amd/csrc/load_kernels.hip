@@ -70,7 +70,8 @@ __global__ __launch_bounds__(256) void fill_cvec_kernel(const float *__restrict_
     }
 }
 
-// Three-way bf16 split of the fp32 [Vp][Hp] weights into the six segments of the long reduction.
+// Three-way bf16 split of the fp32 [Vp][Hp] weights, term-interleaved in chunks of 32 units:
+// Ot3[v][j / 32][term][j % 32].
 __global__ __launch_bounds__(256) void split3_weights_kernel(const float *__restrict__ Ot, size_t n, int Hp,
                                                              bf16_t *__restrict__ Ot3) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -79,8 +80,9 @@ __global__ __launch_bounds__(256) void split3_weights_kernel(const float *__rest
     const int j = (int)(i % Hp);
     uint16_t t[3];
     split3_bf16(Ot[i], t[0], t[1], t[2]);
+    bf16_t *dst = Ot3 + v * 3 * Hp + (size_t)(j >> 5) * 96 + (j & 31);
 #pragma unroll
-    for (int s = 0; s < 6; ++s) Ot3[v * 6 * Hp + (size_t)s * Hp + j] = t[RNNLM_SPLIT3_W(s)];
+    for (int s = 0; s < 3; ++s) dst[s * 32] = t[s];
 }
 
 // bf16 [Vp][Hp] weights re-laid in MFMA-operand order: 16 bytes per thread.

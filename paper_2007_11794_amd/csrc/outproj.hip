@@ -197,6 +197,9 @@ hipError_t launch_outproj_staged(const ModelDev &m, int rows, const int *B_dev, 
 hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                 SplitInfo *splits, hipStream_t stream);
 
+// defined in outproj_split3.hip
+hipError_t launch_outproj_split3(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
+                                 SplitInfo *splits, hipStream_t stream);
 // defined in outproj_stream.hip
 hipError_t launch_outproj_stream(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                  SplitInfo *splits, hipStream_t stream);
@@ -234,20 +237,15 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
             hipLaunchKernelGGL(outproj_plain_bf16_kernel<false>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
         splits->fixed_splits = S;
     } else {
-        // fp32 from 64 rows on: the bf16 tiled kernel on the three-term split of both operands (six
-        // bf16 products per fp32 product at sixteen times the fp32 matrix rate, same accuracy).
-        // The tiled fp32-MFMA kernel only on request; at the WSJ-sized workload it is no faster
-        // than the FMA kernel below.
+        // fp32 on the bf16 matrix cores through the three-term split of both operands (six bf16
+        // products per fp32 product at sixteen times the fp32 matrix rate, same accuracy): weight
+        // streaming for few rows, the tiled three-term kernel from 64 rows on.  The tiled
+        // fp32-MFMA kernel only on request; at the WSJ-sized workload it is no faster than the
+        // FMA kernel below.
         if (stream_choice(m, rows, kernel_choice)) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
         if (kernel_choice == 3) return launch_outproj_tiled(m, rows, B_dev, fixed_offset, splits, stream);
-        if (m.Ot3 && (kernel_choice == 4 || (kernel_choice == 0 && rows >= 64))) {
-            ModelDev v = m;
-            v.dtype = RNNLM_BF16;
-            v.Hp = 6 * m.Hp;
-            v.Ot = m.Ot3;
-            v.d = m.d3;
-            return launch_outproj_tiled(v, rows, B_dev, fixed_offset, splits, stream);
-        }
+        if (m.Ot3 && (kernel_choice == 4 || (kernel_choice == 0 && rows >= 64)))
+            return launch_outproj_split3(m, rows, B_dev, fixed_offset, splits, stream);
         const int row_groups = (rows + kFM - 1) / kFM, col_blocks = m.Vp / kFN;
         int S = choose_splits(row_groups, col_blocks, 1024);
         int per = (col_blocks + S - 1) / S;

@@ -431,18 +431,17 @@ __global__ __launch_bounds__(256) void recur_f32_kernel(
         dv[i] = hp[i] - 0.5f;                        // padded units: sigmoid(0) - 1/2 = 0
     }
     *reinterpret_cast<f32x4 *>(static_cast<float *>(m.d) + (size_t)b * Hp + je) = dv;
-    if (m.d3) {     // the same values as three bf16 terms, in the six segments of the long reduction
+    if (m.d3) {     // the same values as three bf16 terms, term-interleaved in chunks of 32 units
         uint16_t t[4][3];
 #pragma unroll
         for (int i = 0; i < 4; ++i) split3_bf16(dv[i], t[i][0], t[i][1], t[i][2]);
-        bf16_t *row3 = static_cast<bf16_t *>(m.d3) + (size_t)b * 6 * Hp + je;
+        bf16_t *row3 = static_cast<bf16_t *>(m.d3) + (size_t)b * 3 * Hp + (size_t)(je >> 5) * 96 + (je & 31);
 #pragma unroll
-        for (int s = 0; s < 6; ++s) {
-            const int k = RNNLM_SPLIT3_D(s);
+        for (int k = 0; k < 3; ++k) {
             uint2 pk;
             pk.x = (uint32_t)t[0][k] | ((uint32_t)t[1][k] << 16);
             pk.y = (uint32_t)t[2][k] | ((uint32_t)t[3][k] << 16);
-            *reinterpret_cast<uint2 *>(row3 + (size_t)s * Hp) = pk;
+            *reinterpret_cast<uint2 *>(row3 + k * 32) = pk;
         }
     }
     if (vec_ok && je + 4 <= H) {

@@ -35,16 +35,15 @@ struct ModelDev {
     // fp32 models with the full softmax: the output projection on the bf16 matrix cores at fp32
     // accuracy.  Every fp32 number is the exact sum of three bf16 numbers x1 + x2 + x3 (8 + 8 + 8
     // mantissa bits); of the nine cross terms of a product the six with the largest weight are
-    // kept.  Both operands are laid out along a reduction length of 6 Hp so that the bf16 kernels
-    // add exactly those six terms: weights [x1 | x1 | x2 | x1 | x3 | x2], hidden block
-    // [d1 | d2 | d1 | d3 | d1 | d2].
-    const void *Ot3;   // [Vp][6 Hp] bf16, or null
+    // kept.  Both operands are kept term-interleaved in chunks of 32 units,
+    // [row][unit / 32][term][unit % 32], so a chunk of the reduction is 192 contiguous bytes per row.
+    const void *Ot3;   // [Vp][3 Hp] bf16, or null
     // A second copy of the output weights in MFMA-operand order for the kernels that stream them
     // for few rows.  bf16: [Vp / 32][Hp / 16][64 lanes][8], lane 32 g + c of fragment (blk, ks)
     // holds word 32 blk + c, units 16 ks + 8 g .. + 7 (one operand = 1 KB contiguous).  fp32: the
     // same operand as two halves of four floats, [Vp / 32][Hp / 16][2][64 lanes][4].
     const void *Ofrag;
-    void *d3;          // [max_Bp][6 Hp] bf16 scratch, or null
+    void *d3;          // [max_Bp][3 Hp] bf16 scratch, or null
     // hierarchical output layer (models loaded with rnnlm_hs_load; Ot .. cvec2_fixed are null then)
     int hs;                       // 1: hierarchical
     const void *Theta;            // [V-1][Hp] node vectors, weights' type, zero-padded
@@ -215,7 +214,7 @@ hipError_t launch_col_stats(const void *O_dev, const float *bias_or_null, int dt
                             float *half_colsum /*[V]*/, float *upper /*[V]*/, float *lower /*[V]*/,
                             hipStream_t stream);
 hipError_t launch_frag_weights(const void *Ot /*[Vp][Hp]*/, int dtype, int Vp, int Hp, void *Ofrag, hipStream_t stream);
-hipError_t launch_split3_weights(const float *Ot /*[Vp][Hp]*/, int Vp, int Hp, void *Ot3 /*[Vp][6 Hp] bf16*/,
+hipError_t launch_split3_weights(const float *Ot /*[Vp][Hp]*/, int Vp, int Hp, void *Ot3 /*[Vp][3 Hp] bf16*/,
                                  hipStream_t stream);
 hipError_t launch_fill_cvec(const float *bias_or_null, const float *half_colsum, int V, int Vp,
                             float m2_fixed, float *bias_out, float *cvec2, float *cvec2_fixed,
