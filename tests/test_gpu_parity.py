@@ -405,22 +405,29 @@ def test_running_maximum_fallback_when_logits_are_huge():
 
 
 # ------------------------------------------------------------------------ a vocabulary of the paper's largest size
-def test_million_word_vocabulary():
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_million_word_vocabulary(dtype):
     """V = 1,000,003 (Section 5.1's in-house vocabulary is about a million words; odd on purpose:
-    ragged last tile), H = 128, bf16: full softmax on 130 rows through the staged kernel."""
+    ragged last tile), H = 128, full softmax: 130 rows (bf16: staged kernel; fp32: three-term
+    kernel) and the first 20 of them alone (weight-streaming kernels)."""
     rng = np.random.default_rng(99)
     V, H, B, K = 1000003, 128, 130, 6
     from workloads import bounded_zipf_ids, round_to_bf16
-    model = {"U": round_to_bf16(rng.normal(0, 0.05, (V, H)).astype(np.float32)),
-             "W": round_to_bf16(rng.normal(0, 0.05, (H, H)).astype(np.float32)),
-             "O": round_to_bf16(rng.normal(0, 0.05, (H, V)).astype(np.float32)), "bias": None}
-    m = load_model(model, "bf16", B)
+    model = {k: rng.normal(0, 0.05, s).astype(np.float32) for k, s in (("U", (V, H)), ("W", (H, H)), ("O", (H, V)))}
+    model["bias"] = None
+    if dtype == "bf16":
+        for k in ("U", "W", "O"):
+            model[k] = round_to_bf16(model[k])
+    m = load_model(model, dtype, B)
     prev = bounded_zipf_ids(rng, V, 1.1, B)
     prev[0] = V - 1
     h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
     query = bounded_zipf_ids(rng, V, 1.1, (B, K))
     query[:, 0] = V - 1 - np.arange(B)                  # words of the last, ragged tile
+    ref = oracle.step(model, prev, h_in, query)
     h, lp = gpu_step(m, prev, h_in, query)
-    check(h, lp, oracle.step(model, prev, h_in, query), "bf16", "V=1000003")
+    check(h, lp, ref, dtype, "V=1000003 %s, %d rows" % (dtype, B))
+    h, lp = gpu_step(m, prev[:20], h_in[:20], query[:20])
+    check(h, lp, {"h_out": ref["h_out"][:20], "logprob": ref["logprob"][:20]}, dtype, "V=1000003 %s, 20 rows" % dtype)
     assert m.last_error() == 0
     m.close()
