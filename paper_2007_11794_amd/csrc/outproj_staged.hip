@@ -27,10 +27,15 @@
 // direct loads write LDS linearly (lane i -> base + 16 i), so the swizzle is applied on the
 // global side: lane i fetches the chunk that belongs at position i.
 //
+// When the batch turns out to hold at most 64 rows (the count may be known on the device only),
+// the kernel runs the weight-streaming body instead (outproj_stream_body.h): see the top of
+// the kernel.
+//
 // Work split (staged_plan): workgroup id modulo 8 is the XCD; vocabulary split s runs on
 // XCD s % 8, with all row groups of that split next to each other, so the row groups that
 // stream the same weights hit in the same 4 MB L2 and HBM is read once.
 #include "device_utils.h"
+#include "outproj_stream_body.h"
 #include "rnnlm_internal.h"
 
 namespace rnnlm {
@@ -167,6 +172,17 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
     char *const cring = lds + kStages * C::kStageBytes;
     const int B = B_dev ? *B_dev : rows;
     if (B <= 0) return;                                       // uniform: nothing to do, no barrier met
+    // Few rows after all (after the grouping or the cache lookup only the device knows how many
+    // are left): the time is then the time to read the weights once, and the workgroup streams
+    // them instead.  Same grid, and the same partials come out: with one row group the vocabulary
+    // is cut into as many splits as there are workgroups, split = workgroup index.
+    static_assert(kThreads == kStreamThreads, "");
+    static_assert(C::kLdsBytes >= 2 * KS * 1024 + kStreamWaves * 64 * 8, "LDS for two row blocks of the streaming form");
+    if (B <= 64 && m.Ofrag && (int)gridDim.x == staged_plan(B, wg_per_xcd).S) {
+        if (B <= 32) outproj_stream_body<1, FIXED>(m, B, 0, (int)blockIdx.x, (int)gridDim.x, lds);
+        else outproj_stream_body<2, FIXED>(m, B, 0, (int)blockIdx.x, (int)gridDim.x, lds);
+        return;
+    }
     const StagedPlan plan = staged_plan(B, wg_per_xcd);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;

@@ -19,23 +19,17 @@
 //   - exp-and-add per block in registers as elsewhere; at the end the eight waves' (max, sum)
 //     pairs are merged through LDS in a fixed order: one partial per row and workgroup.
 #include "device_utils.h"
+#include "outproj_stream_body.h"
 #include "rnnlm_internal.h"
 
 namespace rnnlm {
 
 namespace {
 
-constexpr int kThreads = 512;
-constexpr int kWaves = kThreads / 64;
-constexpr int kGroup = 4;          // MFMA operands (k-steps) per group of loads; Hp is a multiple of 64
-constexpr int kRing = 5;           // groups per wave: one being consumed, four in flight
-
-struct Cursor {                    // walks the groups of the blocks blk, blk + kWaves, ... of one wave
-    int blk, part;
-    __device__ __forceinline__ void advance(int groups_per_block) {
-        if (++part == groups_per_block) { part = 0; blk += kWaves; }
-    }
-};
+constexpr int kThreads = kStreamThreads;
+constexpr int kWaves = kStreamWaves;
+constexpr int kRing = kStreamRing;
+typedef StreamCursor Cursor;
 
 template <int RB, bool FIXED>
 __global__ __launch_bounds__(kThreads) void outproj_stream_kernel(ModelDev m, int rows,
@@ -44,110 +38,7 @@ __global__ __launch_bounds__(kThreads) void outproj_stream_kernel(ModelDev m, in
     // this launch serves rows row0 .. row0 + 32 RB - 1 (row0 a multiple of 32)
     const int B = (B_dev ? *B_dev : rows) - row0;
     if (B <= 0) return;                                       // uniform: no barrier is met
-    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, g = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KS = m.Hp >> 4, GPB = KS / kGroup;
-    const int T = m.Vp / 32, S = gridDim.x, split = blockIdx.x;
-    const int blk1 = (int)(((long long)(split + 1) * T) / S);
-    const int blk0 = (int)(((long long)split * T) / S);
-    const bf16x8 *Of = static_cast<const bf16x8 *>(m.Ofrag) + lane;
-    const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
-    bf16x8 *dl = reinterpret_cast<bf16x8 *>(lds);
-    float2 *red = reinterpret_cast<float2 *>(lds + (size_t)RB * KS * 1024);    // [kWaves][RB * 32]
-
-    // the hidden block first (its arrival is then not queued behind the weights)
-    {
-        const bf16x8 *src = static_cast<const bf16x8 *>(m.dfrag) + (size_t)(row0 >> 5) * KS * 64;
-        const int n = RB * KS * 64;
-        for (int i = tid; i < n; i += kThreads) dl[i] = src[i];
-    }
-    bf16x8 ring[kRing][kGroup];
-    Cursor in = {blk0 + wave, 0};
-    // Always kGroup loads, so that the number of younger loads behind any operand is the same on
-    // every path and the waits for the ring stay partial; past the end of the wave's blocks the
-    // loads go to the first kilobytes of the weights (cache hits, results unused).
-    auto issue = [&](bf16x8(&dst)[kGroup]) {
-        const bf16x8 *p = Of + (in.blk < blk1 ? ((size_t)in.blk * KS + in.part * kGroup) * 64 : (size_t)0);
-#pragma unroll
-        for (int i = 0; i < kGroup; ++i) dst[i] = p[i * 64];
-        in.advance(GPB);
-    };
-#pragma unroll
-    for (int st = 0; st < kRing - 1; ++st) issue(ring[st]);
-    __syncthreads();                                          // hidden block visible to all waves
-
-    Cursor out = {blk0 + wave, 0};
-    f32x16 acc[RB];
-    float mrun[RB], srun[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        mrun[rb] = FIXED ? m.m2_fixed : -INFINITY;
-        srun[rb] = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
-    }
-    f32x4 cc[4];
-    auto load_constants = [&]() {
-        const int blk = out.blk < blk1 ? out.blk : blk0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) cc[q] = *reinterpret_cast<const f32x4 *>(cvec + blk * 32 + 8 * q + 4 * g);
-    };
-    load_constants();
-    // The wave leaves the unrolled ring loop from wherever its last group falls (a return out of
-    // the lambda, never a skip that rejoins the loop: the compiler sizes each wait by the path
-    // with the fewest younger loads).
-    [&]() {
-        for (;;) {
-#pragma unroll
-            for (int st = 0; st < kRing; ++st) {
-                if (out.blk >= blk1) return;
-                issue(ring[(st + kRing - 1) % kRing]);
-#pragma unroll
-                for (int i = 0; i < kGroup; ++i) {
-                    const int ks = out.part * kGroup + i;
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[st][i], dl[(rb * KS + ks) * 64 + lane],
-                                                                          acc[rb], 0, 0, 0);
-                }
-                if (out.part == GPB - 1) {                    // block complete: exp-and-add, next block
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb) {
-                        float x[16];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) x[4 * q + i] = acc[rb][4 * q + i] + cc[q][i];
-                        lse2_fold16<FIXED>(x, mrun[rb], srun[rb]);
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
-                    }
-                    out.advance(GPB);
-                    load_constants();
-                } else {
-                    out.advance(GPB);
-                }
-            }
-        }
-    }();
-    // lanes l and l + 32 hold the two halves of a row; then the eight waves of the workgroup
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const float m2 = __shfl_xor(mrun[rb], 32, 64), s2 = __shfl_xor(srun[rb], 32, 64);
-        if (FIXED) srun[rb] += s2;
-        else lse2_merge(mrun[rb], srun[rb], m2, s2);
-        if (g == 0) red[wave * (RB * 32) + rb * 32 + col] = make_float2(mrun[rb], srun[rb]);
-    }
-    __syncthreads();
-    if (tid < RB * 32) {
-        float mm = red[tid].x, ss = red[tid].y;
-        for (int w = 1; w < kWaves; ++w) {
-            const float2 p = red[w * (RB * 32) + tid];
-            if (FIXED) ss += p.y;
-            else lse2_merge(mm, ss, p.x, p.y);
-        }
-        if (tid < B) m.part[(size_t)(row0 + tid) * kMaxSplits + split] = make_float2(mm, ss);
-    }
+    outproj_stream_body<RB, FIXED>(m, B, row0, blockIdx.x, gridDim.x, lds);
 }
 
 // ------------------------------------------------------------------------------ fp32 models
@@ -300,11 +191,6 @@ __global__ __launch_bounds__(kThreads) void outproj_stream_f32_kernel(ModelDev m
         }
         if (tid < B) m.part[(size_t)(row0 + tid) * kMaxSplits + split] = make_float2(mm, ss);
     }
-}
-
-// terms = copies of the hidden block kept in LDS: 1 (bf16 models) or 3 (fp32 models)
-size_t stream_lds_bytes(int terms, int RB, int KS) {
-    return (size_t)terms * RB * KS * 1024 + (size_t)kWaves * RB * 32 * sizeof(float2);
 }
 
 template <int RB>

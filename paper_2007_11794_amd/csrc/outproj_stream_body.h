@@ -1,0 +1,140 @@
+// The weight-streaming output projection for bf16 models as a device function: the kernel of its
+// own (few rows known on the host) and the staged kernel (few rows known only on the device)
+// both run it.  See outproj_stream.hip for the design.
+#pragma once
+
+#include "device_utils.h"
+#include "rnnlm_internal.h"
+
+namespace rnnlm {
+
+constexpr int kStreamThreads = 512;
+constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kStreamGroup = 4;          // MFMA operands (k-steps) per group of loads; Hp is a multiple of 64
+constexpr int kStreamRing = 5;           // groups per wave: one being consumed, four in flight
+
+struct StreamCursor {                    // walks the groups of the blocks blk, blk + kStreamWaves, ... of one wave
+    int blk, part;
+    __device__ __forceinline__ void advance(int groups_per_block) {
+        if (++part == groups_per_block) { part = 0; blk += kStreamWaves; }
+    }
+};
+
+// One launch's worth of streaming for the workgroup `split` of `S`: rows row0 .. row0 + 32 RB - 1 of
+// the hidden block (B = number of valid ones among them, > 0), partials into m.part.  Needs
+// stream_lds_bytes(1, RB, Hp / 16) bytes of LDS at `lds` and kStreamThreads threads; contains two
+// workgroup barriers, so all threads of the workgroup must call it.
+template <int RB, bool FIXED>
+__device__ __forceinline__ void outproj_stream_body(const ModelDev &m, int B, int row0, int split, int S, char *lds) {
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int KS = m.Hp >> 4, GPB = KS / kStreamGroup;
+    const int T = m.Vp / 32;
+    const int blk1 = (int)(((long long)(split + 1) * T) / S);
+    const int blk0 = (int)(((long long)split * T) / S);
+    const bf16x8 *Of = static_cast<const bf16x8 *>(m.Ofrag) + lane;
+    const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
+    bf16x8 *dl = reinterpret_cast<bf16x8 *>(lds);
+    float2 *red = reinterpret_cast<float2 *>(lds + (size_t)RB * KS * 1024);    // [kStreamWaves][RB * 32]
+
+    // the hidden block first (its arrival is then not queued behind the weights)
+    {
+        const bf16x8 *src = static_cast<const bf16x8 *>(m.dfrag) + (size_t)(row0 >> 5) * KS * 64;
+        const int n = RB * KS * 64;
+        for (int i = tid; i < n; i += kStreamThreads) dl[i] = src[i];
+    }
+    bf16x8 ring[kStreamRing][kStreamGroup];
+    StreamCursor in = {blk0 + wave, 0};
+    // Always kStreamGroup loads, so that the number of younger loads behind any operand is the same on
+    // every path and the waits for the ring stay partial; past the end of the wave's blocks the
+    // loads go to the first kilobytes of the weights (cache hits, results unused).
+    auto issue = [&](bf16x8(&dst)[kStreamGroup]) {
+        const bf16x8 *p = Of + (in.blk < blk1 ? ((size_t)in.blk * KS + in.part * kStreamGroup) * 64 : (size_t)0);
+#pragma unroll
+        for (int i = 0; i < kStreamGroup; ++i) dst[i] = p[i * 64];
+        in.advance(GPB);
+    };
+#pragma unroll
+    for (int st = 0; st < kStreamRing - 1; ++st) issue(ring[st]);
+    __syncthreads();                                          // hidden block visible to all waves
+
+    StreamCursor out = {blk0 + wave, 0};
+    f32x16 acc[RB];
+    float mrun[RB], srun[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        mrun[rb] = FIXED ? m.m2_fixed : -INFINITY;
+        srun[rb] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
+    }
+    f32x4 cc[4];
+    auto load_constants = [&]() {
+        const int blk = out.blk < blk1 ? out.blk : blk0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) cc[q] = *reinterpret_cast<const f32x4 *>(cvec + blk * 32 + 8 * q + 4 * g);
+    };
+    load_constants();
+    // The wave leaves the unrolled ring loop from wherever its last group falls (a return out of
+    // the lambda, never a skip that rejoins the loop: the compiler sizes each wait by the path
+    // with the fewest younger loads).
+    [&]() {
+        for (;;) {
+#pragma unroll
+            for (int st = 0; st < kStreamRing; ++st) {
+                if (out.blk >= blk1) return;
+                issue(ring[(st + kStreamRing - 1) % kStreamRing]);
+#pragma unroll
+                for (int i = 0; i < kStreamGroup; ++i) {
+                    const int ks = out.part * kStreamGroup + i;
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[st][i], dl[(rb * KS + ks) * 64 + lane],
+                                                                          acc[rb], 0, 0, 0);
+                }
+                if (out.part == GPB - 1) {                    // block complete: exp-and-add, next block
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) {
+                        float x[16];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) x[4 * q + i] = acc[rb][4 * q + i] + cc[q][i];
+                        lse2_fold16<FIXED>(x, mrun[rb], srun[rb]);
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
+                    }
+                    out.advance(GPB);
+                    load_constants();
+                } else {
+                    out.advance(GPB);
+                }
+            }
+        }
+    }();
+    // lanes l and l + 32 hold the two halves of a row; then the eight waves of the workgroup
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const float m2 = __shfl_xor(mrun[rb], 32, 64), s2 = __shfl_xor(srun[rb], 32, 64);
+        if (FIXED) srun[rb] += s2;
+        else lse2_merge(mrun[rb], srun[rb], m2, s2);
+        if (g == 0) red[wave * (RB * 32) + rb * 32 + col] = make_float2(mrun[rb], srun[rb]);
+    }
+    __syncthreads();
+    if (tid < RB * 32) {
+        float mm = red[tid].x, ss = red[tid].y;
+        for (int w = 1; w < kStreamWaves; ++w) {
+            const float2 p = red[w * (RB * 32) + tid];
+            if (FIXED) ss += p.y;
+            else lse2_merge(mm, ss, p.x, p.y);
+        }
+        if (tid < B) m.part[(size_t)(row0 + tid) * kMaxSplits + split] = make_float2(mm, ss);
+    }
+}
+
+// terms = copies of the hidden block kept in LDS: 1 (bf16 models) or 3 (fp32 models)
+__host__ __device__ inline size_t stream_lds_bytes(int terms, int RB, int KS) {
+    return (size_t)terms * RB * KS * 1024 + (size_t)kStreamWaves * RB * 32 * sizeof(float2);
+}
+
+}  // namespace rnnlm

@@ -174,6 +174,32 @@ def test_config3_model_few_rows_full_vocabulary():
     m.close()
 
 
+@pytest.mark.parametrize("V,H,N,distinct", [(5000, 512, 400, 20), (3000, 256, 300, 50), (2000, 128, 200, 64),
+                                            (2000, 512, 260, 65), (40000, 512, 1024, 7)])
+def test_many_raw_queries_few_distinct_histories(V, H, N, distinct):
+    """The search repeats itself (Section 5.2): N raw queries, a handful of distinct histories.  The
+    host sizes the launch for N rows; the kernel learns the true count on the device and streams
+    the weights when it is small."""
+    cfg = CONFIGS[3].scaled(V=V, H=H, B=N, K=5)
+    model = make_model(cfg)
+    rng = np.random.default_rng(V + N)
+    x = make_step_inputs(cfg, rng)
+    pick = rng.integers(0, distinct, N)
+    pick[:distinct] = np.arange(distinct)
+    keys = (pick.astype(np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+    prev, h_in = x["prev"][pick], x["h_in"][pick]
+    m = load_model(model, "bf16", N)
+    for lse_mode in (1, 2):
+        m.set_option(rn.OPT_LSE_MODE, lse_mode)
+        out = gpu_step_dedup(m, keys, prev, h_in, x["query"])
+        U_, rep, inv = oracle.dedup(keys)
+        assert out["n_unique"] == U_ == distinct and np.array_equal(out["rep"], rep) and np.array_equal(out["inverse"], inv)
+        ref = oracle.step(model, prev[rep], h_in[rep], x["query"], row_of_query=inv)
+        check(out["h_out"], out["logprob"], ref, "bf16", "N=%d distinct=%d lse=%d" % (N, distinct, lse_mode))
+    assert m.last_error() == 0
+    m.close()
+
+
 # ------------------------------------------------------------------------ config 5: stress, full size, sampled rows
 def test_config5_stress_full_size_sampled():
     cfg = CONFIGS[5]
