@@ -186,6 +186,13 @@ def main() -> int:
                     help="config 4 only: time a decode trace of --trace-steps steps through a cache of "
                          "CAPACITY histories kept between the steps (reset at the start of every pass)")
     ap.add_argument("--trace-steps", type=int, default=8)
+    ap.add_argument("--unique-frac", type=float, default=None,
+                    help="config 4 only: share of distinct histories among the N raw queries of a step "
+                         "(0.3 in the workload as specified; the paper reports about 0.1)")
+    ap.add_argument("--carry-frac", type=float, default=0.5,
+                    help="config 4 with --cache: share of the distinct histories kept from one step of the "
+                         "trace to the next, i.e. found in the cache (0.5 as specified; the paper reports "
+                         "a hit ratio of almost 0.89)")
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time the platform's GEMM (torch.matmul, bf16) on the output projection's "
                          "contraction alone, logits written to HBM, no log-sum-exp: context for the roofline")
@@ -221,6 +228,12 @@ def main() -> int:
                   file=sys.stderr)
             return 2
         cfg = cfg.scaled(B=args.rows)
+    if args.unique_frac is not None:
+        if cfg.unique_frac is None or not 0.0 < args.unique_frac <= 1.0:
+            print("bench.py: --unique-frac needs the decode-trace workload (--config 4) and a share in (0, 1]",
+                  file=sys.stderr)
+            return 2
+        cfg = cfg.scaled(unique_frac=args.unique_frac, B=int(round(args.unique_frac * cfg.N)))
     if args.index_table:
         return bench_index_table(args, cfg, rn, torch, np)
     if args.hs:
@@ -260,7 +273,7 @@ def main() -> int:
             print("bench.py: --cache needs the decode-trace workload (--config 4)", file=sys.stderr)
             return 2
         # The trace is built once, untimed: step t+1 grows from the hidden vectors step t returned.
-        tr = DecodeTrace(cfg)
+        tr = DecodeTrace(cfg, carry_frac=args.carry_frac)
         xt, trace = tr.first(), []
         for _ in range(args.trace_steps):
             dev_in = tuple(torch.from_numpy(a).to(dev) for a in
@@ -288,7 +301,7 @@ def main() -> int:
         for _ in range(20):
             uncached_pass()
         torch.cuda.synchronize()
-        cache_info = {"capacity": args.cache, "trace_steps": args.trace_steps,
+        cache_info = {"capacity": args.cache, "trace_steps": args.trace_steps, "carry_frac": args.carry_frac,
                       "uncached_value": round(N * args.trace_steps * 20 / (time.perf_counter() - t0), 1)}
 
     if args.calibrate_copy:

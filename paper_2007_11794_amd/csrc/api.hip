@@ -376,9 +376,14 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
         return RNNLM_EDEVICE;
     if (launch_outproj(d, N, c.n_miss, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
         return RNNLM_EDEVICE;
-    if (launch_cache_commit(c, d, N, n_unique, splits, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
-    if (launch_query(d, N, n_unique, N, K, splits, query_word, inverse, h_out, c.lse_rows, base_score, score,
-                     s) != hipSuccess)
+    // With words to score, the query kernel also does the cache's bookkeeping after the computation
+    // (stored values out, new entries in): one launch less.
+    if (K == 0) {
+        if (launch_cache_commit(c, d, N, n_unique, splits, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+        return RNNLM_OK;
+    }
+    if (launch_query_cached(d, c, N, n_unique, N, K, splits, query_word, inverse, rep, h_out, base_score, score,
+                            s) != hipSuccess)
         return RNNLM_EDEVICE;
     return RNNLM_OK;
 }

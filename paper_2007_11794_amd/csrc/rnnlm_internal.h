@@ -175,6 +175,15 @@ hipError_t launch_query(const ModelDev &m, int rows, const int *B_dev, int N, in
                         const float *h_out, const float *lse_rows, const float *base_score,
                         float *logprob, hipStream_t stream);
 
+// The same through a cache (after launch_cache_lookup and the computation of the histories not
+// found): found histories take h' and lse from the stores, and the first raw query of every distinct
+// history passes its h' on (to h_out when found, into the store with its lse when it got an entry),
+// which is all that launch_cache_commit does otherwise.  rows / n_unique: distinct histories.
+hipError_t launch_query_cached(const ModelDev &m, const CacheDev &c, int rows, const int32_t *n_unique, int N, int K,
+                               SplitInfo splits, const int32_t *query_word, const int32_t *inverse,
+                               const int32_t *rep, float *h_out, const float *base_score, float *score,
+                               hipStream_t stream);
+
 // ---- cache kept between steps (cache.hip)
 hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream);
 // Looks the distinct histories ids[rep[u]], u < *n_unique, up; numbers the ones not found

@@ -145,9 +145,13 @@ class DecodeTrace:
     never computes anything of the method.
     """
 
-    def __init__(self, cfg: Workload, seed: Optional[int] = None):
-        assert cfg.unique_frac is not None
+    def __init__(self, cfg: Workload, seed: Optional[int] = None, carry_frac: float = 0.5):
+        """carry_frac: expected share of the distinct histories kept from one step to the next
+        (one half in the workload as specified; the paper's search finds about nine lookups in
+        ten again, Section 5.2)."""
+        assert cfg.unique_frac is not None and 0.0 <= carry_frac <= 1.0
         self.cfg = cfg
+        self.carry_frac = carry_frac
         self.rng = np.random.default_rng(cfg.seed if seed is None else seed)
         self.U0 = int(round(cfg.unique_frac * cfg.N))
         self._ctx_counter = 0
@@ -185,7 +189,7 @@ class DecodeTrace:
         of h_out."""
         rng, U0, N = self.rng, self.U0, self.cfg.N
         old = self._uniq
-        carried = rng.random(U0) < 0.5
+        carried = rng.random(U0) < self.carry_frac
         grow_from = rng.integers(0, N, size=U0)
         new_ids = self._fresh_ids(U0)
         h_new = np.asarray(h_out, dtype=np.float32)[np.asarray(inverse)[grow_from]]
