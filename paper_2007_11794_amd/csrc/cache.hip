@@ -49,9 +49,16 @@ __global__ __launch_bounds__(256) void cache_reset_kernel(CacheDev c) {
 constexpr int kLookupPer = 4;
 
 __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
-    CacheDev c, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
+    CacheDev c, int rows, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
     const int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
     __shared__ int wsum[kLookupThreads / 64 + 1];
+    // The first slice's representatives and ids are requested before the number of distinct
+    // histories is known (rep has `rows` slots; what lies beyond the true count is clamped into
+    // range and dropped later): one memory latency less at the head of the chain.
+    const int u_first = (int)threadIdx.x;
+    int raw_first = (u_first < rows) ? rep[u_first] : 0;
+    raw_first = max(min(raw_first, rows - 1), 0);
+    const uint64_t key_first = (rows > 0) ? ids[raw_first] : 0;
     const int U = *n_unique;
     const int base = *c.n_entries;          // read by everyone before thread 0 updates it below
     const uint32_t mask = (uint32_t)(c.table_size - 1);
@@ -64,12 +71,12 @@ __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
 #pragma unroll
         for (int i = 0; i < kLookupPer; ++i) {
             const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
-            raw[i] = (u < U) ? rep[u] : 0;
+            raw[i] = (u0 == 0 && i == 0) ? raw_first : ((u < U) ? rep[u] : 0);
         }
 #pragma unroll
         for (int i = 0; i < kLookupPer; ++i) {
             const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
-            key[i] = (u < U) ? ids[raw[i]] : 0;
+            key[i] = (u0 == 0 && i == 0) ? (u < U ? key_first : 0) : ((u < U) ? ids[raw[i]] : 0);
             h[i] = mix64(key[i]) & mask;
             cell[i] = c.table[h[i]];
         }
@@ -88,6 +95,8 @@ __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
 #pragma unroll
         for (int i = 0; i < kLookupPer; ++i) {
             const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
+            entry[i] = -1;
+            if (u0 + i * kLookupThreads >= U) continue;       // uniform: nobody has a history in this slice
             const bool active = u < U;
             const int miss = (active && found[i] < 0) ? 1 : 0;
             int total;
@@ -287,7 +296,7 @@ hipError_t launch_cache_lookup(const CacheDev &c, int rows, int one_group_rows, 
                                const int32_t *rep, const int32_t *n_unique, int32_t *step_stats,
                                hipStream_t stream) {
     if (rows <= one_group_rows) {                       // few histories: one workgroup, one launch
-        hipLaunchKernelGGL(cache_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, rep, n_unique,
+        hipLaunchKernelGGL(cache_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, rows, ids, rep, n_unique,
                            step_stats);
         return hipGetLastError();
     }
