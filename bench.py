@@ -80,12 +80,6 @@ def bench_hs(args, cfg, rn, torch, np) -> int:
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        if cache_info is not None:
-            # the buffers hold the last step of the trace: score the first step (the one whose host
-            # inputs are at hand) once more, untimed, so that the oracle is compared like with like
-            rn.rnnlm_step_dedup(m, keys, prev, h_in, query, rep, inv, nu, h_out, lp, ws)
-            torch.cuda.synchronize()
-            B = int(nu.item())
         om = {"U": model["U"], "W": model["W"], "theta": theta,
               "path_off": off, "path_entry": entry}
         rows = N                                   # the whole step: the tree makes the oracle cheap too
