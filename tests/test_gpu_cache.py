@@ -182,16 +182,20 @@ def test_empty_batch_and_argument_errors():
     m.close()
 
 
-def test_config4_trace_through_the_cache():
+@pytest.mark.parametrize("unique_frac,carry_frac", [(0.3, 0.5), (0.1, 0.9)])
+def test_config4_trace_through_the_cache(unique_frac, carry_frac):
     """The decode trace at full size (N = 4096, V = 65536, H = 512), 6 steps: half of the
-    distinct histories of a step were seen in the step before and must come from the cache."""
-    cfg = CONFIGS[4]
+    distinct histories of a step were seen in the step before and must come from the cache.
+    Second case: the paper's redundancy (Section 5.2: about a tenth of the lookups are distinct,
+    nine in ten are found again): about 41 histories are computed per step, which the output
+    projection learns on the device."""
+    cfg = CONFIGS[4].scaled(unique_frac=unique_frac, B=int(round(unique_frac * CONFIGS[4].N)))
     model = make_model(cfg)
     m = load_model(model, cfg.dtype, cfg.N)
     cache = rn.rnnlm_cache_create(m, 20000)
     ocache = oracle.Cache(cfg.H, 20000)
     st = CachedStepper(m, cache, cfg.N, cfg.K)
-    tr_g, tr_o = DecodeTrace(cfg), DecodeTrace(cfg)
+    tr_g, tr_o = DecodeTrace(cfg, carry_frac=carry_frac), DecodeTrace(cfg, carry_frac=carry_frac)
     xg, xo = tr_g.first(), tr_o.first()
     for step in range(6):
         out = st.step(xg["keys"], xg["prev"], xg["h_in"], xg["query"])
