@@ -319,7 +319,7 @@ int rnnlm_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word,
     if (B > 0 && h_out == h_in) return RNNLM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
-    SplitInfo splits = {1, 0};
+    SplitInfo splits = fixed_split_info(1);
     if (launch_recur(d, B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
     if (launch_outproj(d, B, nullptr, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
         return RNNLM_EDEVICE;
@@ -353,7 +353,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
     if (rc != RNNLM_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
-    SplitInfo splits = {1, 0};
+    SplitInfo splits = fixed_split_info(1);
     if (!cache) {
         if (N == 0) return RNNLM_OK;
         // Grids cover N rows; the kernels read the true number of rows from *n_unique.
@@ -632,7 +632,7 @@ int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_s
     if (!model || !ms_per_launch || repeats <= 0 || B <= 0 || model->dev.hs) return RNNLM_EINVAL;
     if (B > model->max_B) return RNNLM_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    SplitInfo splits = {1, 0};
+    SplitInfo splits = fixed_split_info(1);
     const bool fixed = use_fixed_offset(model);
     if (hipEventRecord(model->ev0, s) != hipSuccess) return RNNLM_EDEVICE;
     for (int i = 0; i < repeats; ++i)

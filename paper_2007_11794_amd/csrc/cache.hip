@@ -258,8 +258,7 @@ __global__ __launch_bounds__(256) void cache_commit_kernel(CacheDev c, ModelDev 
     if (row >= 0) {
         // computed in this step: its partials are in row `row` of the block of *n_miss rows
         if (wave == 0) {
-            const int splits = si.fixed_splits > 0 ? si.fixed_splits
-                                                   : staged_plan(*c.n_miss, si.staged_wg_per_xcd).S;
+            const int splits = splits_of(si, *c.n_miss);
             const float lse = lse_from_partials(m.part + (size_t)row * kMaxSplits, splits, lane);
             if (lane == 0) {
                 c.lse_rows[u] = lse;

@@ -217,8 +217,7 @@ static bool stream_choice(const ModelDev &m, int rows, int kernel_choice) {
 
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream) {
-    splits->fixed_splits = 1;
-    splits->staged_wg_per_xcd = 0;
+    *splits = fixed_split_info(1);
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16) {
         if (stream_choice(m, rows, kernel_choice)) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
@@ -235,7 +234,7 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
             hipLaunchKernelGGL(outproj_plain_bf16_kernel<true>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
         else
             hipLaunchKernelGGL(outproj_plain_bf16_kernel<false>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
-        splits->fixed_splits = S;
+        *splits = fixed_split_info(S);
     } else {
         // fp32 on the bf16 matrix cores through the three-term split of both operands (six bf16
         // products per fp32 product at sixteen times the fp32 matrix rate, same accuracy): weight
@@ -255,7 +254,7 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
             hipLaunchKernelGGL(outproj_plain_f32_kernel<true>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
         else
             hipLaunchKernelGGL(outproj_plain_f32_kernel<false>, grid, dim3(256), 0, stream, m, rows, B_dev, per, S);
-        splits->fixed_splits = S;
+        *splits = fixed_split_info(S);
     }
     return hipGetLastError();
 }

@@ -53,14 +53,17 @@ __device__ __forceinline__ int lds_chunk_pos(int row, int c) { return (c + ((row
 
 template <bool FIXED, int WN>
 __global__ __launch_bounds__(2 * WN * 64) void outproj_split3_kernel(ModelDev m, int rows,
-                                                                     const int *__restrict__ B_dev, int RG, int S) {
+                                                                     const int *__restrict__ B_dev, int wg_per_xcd,
+                                                                     int sx_cap) {
     using C = Split3Cfg<WN>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // The split follows the TRUE number of rows (after the grouping of ids or the cache lookup only
+    // the device knows it): few rows get many vocabulary splits, and the whole grid works.
     const int B = B_dev ? *B_dev : rows;
+    if (B <= 0) return;                                       // uniform: no barrier is met
+    const RowPlan plan = plan_rows(B, C::kRows, wg_per_xcd, sx_cap);
+    const int S = plan.S, items = plan.RG * plan.Sx;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    const int rg = local % RG, split = xcd + kXcds * (local / RG);
-    const int b0 = rg * C::kRows;
-    if (b0 >= B) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int wm = wave & 1, wn = wave >> 1;                  // word half, 64-row slice of the tile
     const int Hp = m.Hp;
@@ -69,9 +72,7 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_split3_kernel(ModelDev m,
     const bf16_t *D3 = static_cast<const bf16_t *>(m.d3);
     const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
     const int ntiles = m.Vp / C::kWords;
-    const int t_begin = (int)(((long long)split * ntiles) / S), t_end = (int)(((long long)(split + 1) * ntiles) / S);
     const int nk = Hp / kChunkUnits;                          // chunks per tile
-    const int nchunks = (t_end - t_begin) * nk;
 
     // loader: load q of this thread fills physical 16-byte chunk f = q * threads + tid of an operand
     // tile (row f / 12, position f % 12) with the logical chunk that belongs there
@@ -86,6 +87,24 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_split3_kernel(ModelDev m,
     }
     const uint32_t wave_s = __builtin_amdgcn_readfirstlane(wave);
     const uint32_t lds0 = lds_address(lds);
+    int aoff[2][3][2], boff[2][3][2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                // LDS offsets of this lane's operands: term t, k-step ks of a chunk = logical chunk 4 t + 2 ks + g
+                const int ra = wm * 64 + h * 32 + col, rb = wn * 64 + h * 32 + col;
+                aoff[h][t][ks] = ra * kRowLds + lds_chunk_pos(ra, 4 * t + 2 * ks + g) * 16;
+                boff[h][t][ks] = C::kWordBytes + rb * kRowLds + lds_chunk_pos(rb, 4 * t + 2 * ks + g) * 16;
+            }
+
+    for (int item = local; item < items; item += wg_per_xcd) {
+    const int rg = item % plan.RG, split = xcd + kXcds * (item / plan.RG);
+    const int b0 = rg * C::kRows;
+    const int t_begin = (int)(((long long)split * ntiles) / S), t_end = (int)(((long long)(split + 1) * ntiles) / S);
+    const int nchunks = (t_end - t_begin) * nk;
     auto issue = [&](int chunk, int stage) {
         const int t = t_begin + chunk / nk, kc = chunk % nk;
         const bf16_t *wsrc = Ot3 + (size_t)t * C::kWords * row_elems + (size_t)kc * (3 * kChunkUnits);
@@ -97,19 +116,6 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_split3_kernel(ModelDev m,
         for (int q = 0; q < C::kRowLoads; ++q)
             lds_dma_16(dsrc, voff[q], base + C::kWordBytes + q * (C::kThreads * 16));
     };
-
-    // LDS offsets of this lane's operands: term t, k-step ks of a chunk = logical chunk 4 t + 2 ks + g
-    int aoff[2][3][2], boff[2][3][2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int t = 0; t < 3; ++t)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const int ra = wm * 64 + h * 32 + col, rb = wn * 64 + h * 32 + col;
-                aoff[h][t][ks] = ra * kRowLds + lds_chunk_pos(ra, 4 * t + 2 * ks + g) * 16;
-                boff[h][t][ks] = C::kWordBytes + rb * kRowLds + lds_chunk_pos(rb, 4 * t + 2 * ks + g) * 16;
-            }
 
     float mrun[2], srun[2];
 #pragma unroll
@@ -189,6 +195,7 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_split3_kernel(ModelDev m,
         else lse2_merge(p.x, p.y, q.x, q.y);
         m.part[(size_t)(b0 + tid) * kMaxSplits + split] = p;
     }
+    }   // items
 }
 
 template <int WN>
@@ -204,22 +211,18 @@ hipError_t launch_split3_shape(const ModelDev &m, int rows, const int *B_dev, bo
         if (e != hipSuccess) return e;
         attr_set[which] = true;
     }
-    const int RG = (rows + C::kRows - 1) / C::kRows, ntiles = m.Vp / C::kWords;
-    // one workgroup per compute unit (a stage pair takes most of its LDS); splits in multiples of 8
-    // so that the row groups streaming the same weights share an XCD; at most one split per tile,
-    // rounded UP to a multiple of 8 so that no split gets two tiles while the others have one
-    int Sx = 256 / (kXcds * RG);
-    if (Sx > (ntiles + kXcds - 1) / kXcds) Sx = (ntiles + kXcds - 1) / kXcds;
-    if (Sx < 1) Sx = 1;
-    if (Sx > kMaxSplits / kXcds) Sx = kMaxSplits / kXcds;
-    const int S = kXcds * Sx;
-    splits->fixed_splits = S;
-    splits->staged_wg_per_xcd = 0;
-    dim3 grid(kXcds * RG * Sx), block(C::kThreads);
+    // one workgroup per compute unit (a stage pair takes most of its LDS); at most one split per
+    // tile of words, rounded UP to a multiple of 8 so that no split gets two tiles while the others
+    // have one
+    const int wg_per_xcd = 32, ntiles = m.Vp / C::kWords, sx_cap = (ntiles + kXcds - 1) / kXcds;
+    *splits = SplitInfo{0, wg_per_xcd, C::kRows, sx_cap};
+    dim3 grid(kXcds * wg_per_xcd), block(C::kThreads);
     if (fixed_offset)
-        hipLaunchKernelGGL((outproj_split3_kernel<true, WN>), grid, block, C::kLdsBytes, stream, m, rows, B_dev, RG, S);
+        hipLaunchKernelGGL((outproj_split3_kernel<true, WN>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,
+                           wg_per_xcd, sx_cap);
     else
-        hipLaunchKernelGGL((outproj_split3_kernel<false, WN>), grid, block, C::kLdsBytes, stream, m, rows, B_dev, RG, S);
+        hipLaunchKernelGGL((outproj_split3_kernel<false, WN>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,
+                           wg_per_xcd, sx_cap);
     return hipGetLastError();
 }
 

@@ -245,8 +245,7 @@ hipError_t launch_outproj_stream(const ModelDev &m, int rows, const int *B_dev, 
     if (per == 0) return hipErrorInvalidValue;
     const int T = m.Vp / 32;
     const int S = T < kMaxSplits ? T : kMaxSplits;
-    splits->fixed_splits = S;
-    splits->staged_wg_per_xcd = 0;
+    *splits = fixed_split_info(S);
     for (int row0 = 0; row0 < rows; row0 += per) {
         const int n = rows - row0 < per ? rows - row0 : per;
         hipError_t e = n <= 32   ? launch_rb<1>(m, rows, B_dev, row0, fixed_offset, S, stream)

@@ -342,8 +342,7 @@ hipError_t launch_tiled_shape(const ModelDev &m, int rows, const int *B_dev, boo
     if (Sx < 1) Sx = 1;
     if (Sx > kMaxSplits / kXcds) Sx = kMaxSplits / kXcds;
     const int S = kXcds * Sx;
-    splits->fixed_splits = S;
-    splits->staged_wg_per_xcd = 0;
+    *splits = fixed_split_info(S);
     dim3 grid(kXcds * RG * Sx), block(C::kThreads);
     // hidden rows of all row groups beyond half an L2 (4 MB per XCD): two parts (1.3 % at the
     // stress workload; four or eight parts are slower, the weights cross the fabric too often)

@@ -77,8 +77,7 @@ __global__ __launch_bounds__(256) void query_kernel(
     } else {
         // (found histories load the partials of row 0 and never use them: no branch before the loads)
         const int pr = prow > 0 ? prow : 0;
-        const int splits = si.fixed_splits > 0 ? si.fixed_splits
-                                               : staged_plan(CACHED ? *c.n_miss : B, si.staged_wg_per_xcd).S;
+        const int splits = splits_of(si, CACHED ? *c.n_miss : B);
 #pragma unroll
         for (int i = 0; i < kPartsPerLane; ++i) {
             const int s = lane + 64 * i;

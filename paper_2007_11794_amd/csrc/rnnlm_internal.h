@@ -134,32 +134,45 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
                         const int32_t *row_dst, const int32_t *prev_word, const float *h_in,
                         float *h_out, hipStream_t stream);
 
-// How many (max, sum) partials per row the output projection left in m.part: a fixed
-// number, or (staged kernel, whose split count follows the true number of rows that only
-// the device may know) the number staged_plan derives from B and the grid size.
-struct SplitInfo {
-    int fixed_splits;      // > 0: that many
-    int staged_wg_per_xcd; // used when fixed_splits == 0
-};
-
 constexpr int kStagedRows = 256;   // rows per workgroup of the staged kernel
 constexpr int kStagedWords = 32;   // words per LDS stage
 constexpr int kXcds = 8;           // workgroup id modulo 8 = the XCD (L2 domain) it runs on
 
-// Work split of the staged kernel for B rows on a grid of kXcds * wg_per_xcd workgroups:
-// RG row groups of 256 rows; the vocabulary is cut into S = kXcds * Sx splits; split s is
+// Work split of an output-projection kernel for B rows on a grid of kXcds * wg_per_xcd workgroups.
+// The true B may be known on the device only (after the grouping of ids or the cache lookup), so the
+// kernels derive the split there, and the kernels that read the partials afterwards derive the
+// same: RG row groups of group_rows rows; the vocabulary is cut into S = kXcds * Sx splits, as
+// many as the grid gives every row group (at most sx_cap: one per tile of words); split s is
 // served by XCD s % kXcds, so the RG workgroups that stream the same weights share one L2.
-struct StagedPlan { int RG, Sx, S; };
-__host__ __device__ inline StagedPlan staged_plan(int B, int wg_per_xcd) {
-    StagedPlan p;
-    p.RG = (B + kStagedRows - 1) / kStagedRows;
+struct RowPlan { int RG, Sx, S; };
+__host__ __device__ inline RowPlan plan_rows(int B, int group_rows, int wg_per_xcd, int sx_cap) {
+    RowPlan p;
+    p.RG = (B + group_rows - 1) / group_rows;
     if (p.RG < 1) p.RG = 1;
     p.Sx = wg_per_xcd / p.RG;
-    if (p.Sx < 1) p.Sx = 1;
+    if (p.Sx > sx_cap) p.Sx = sx_cap;
     if (p.Sx > kMaxSplits / kXcds) p.Sx = kMaxSplits / kXcds;
+    if (p.Sx < 1) p.Sx = 1;
     p.S = kXcds * p.Sx;
     return p;
 }
+typedef RowPlan StagedPlan;
+__host__ __device__ inline StagedPlan staged_plan(int B, int wg_per_xcd) {
+    return plan_rows(B, kStagedRows, wg_per_xcd, kMaxSplits / kXcds);
+}
+
+// How many (max, sum) partials per row the output projection left in m.part: a fixed number, or
+// the S of plan_rows for the true number of rows.
+struct SplitInfo {
+    int fixed_splits;      // > 0: that many
+    int wg_per_xcd;        // else plan_rows(B, group_rows, wg_per_xcd, sx_cap).S
+    int group_rows;
+    int sx_cap;
+};
+__host__ __device__ inline int splits_of(const SplitInfo &si, int B) {
+    return si.fixed_splits > 0 ? si.fixed_splits : plan_rows(B, si.group_rows, si.wg_per_xcd, si.sx_cap).S;
+}
+__host__ inline SplitInfo fixed_split_info(int S) { return SplitInfo{S, 0, 1, 1}; }
 
 // Output projection + log-sum-exp partials over the vocabulary, on the block m.d.
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
