@@ -83,19 +83,24 @@ struct TiledCfg {
 // whose chunks wait for their loads anyway, is 1 % faster without: measured on one box).
 template <typename T, bool FIXED, int MB, int WN, int NS, bool OVL>
 __global__ __launch_bounds__(2 * WN * 64) void outproj_tiled_kernel(ModelDev m, int rows,
-                                                                    const int *__restrict__ B_dev, int RG,
-                                                                    int S, int P) {
+                                                                    const int *__restrict__ B_dev,
+                                                                    int wg_per_xcd, int sx_cap) {
     using C = TiledCfg<MB, WN, NS>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // The split follows the TRUE number of rows (after the grouping of ids or the cache lookup only
+    // the device knows it): few rows get many vocabulary splits, and the whole grid works.
     const int B = B_dev ? *B_dev : rows;
+    if (B <= 0) return;                                       // uniform: no barrier is met
+    const RowPlan plan = plan_rows(B, C::kRows, wg_per_xcd, sx_cap);
+    const int RG = plan.RG, S = plan.S, items = plan.RG * plan.Sx;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    // The XCDs form P parts; part p serves the row groups p RG/P .. (p+1) RG/P - 1 with all splits,
-    // split s on XCD p + P (s % (8 / P)): the hidden rows one L2 has to keep shrink by P, the weights
-    // are fetched by P XCDs.
+    // Hidden rows of all row groups beyond half an L2 (4 MB per XCD): the XCDs form P = 2 parts; part
+    // p serves the row groups p RG/P .. (p+1) RG/P - 1 with all splits, split s on XCD
+    // p + P (s % (8 / P)): the hidden rows one L2 has to keep shrink by P, the weights are fetched by
+    // P XCDs (1.3 % at the stress workload; four or eight parts are slower, the weights cross the
+    // fabric too often).
+    const int P = (RG % 2 == 0 && (size_t)RG * C::kRows * m.Hp * sizeof(T) > ((size_t)2 << 20)) ? 2 : 1;
     const int RGp = RG / P, part = xcd % P;
-    const int rg = part * RGp + local % RGp, split = xcd / P + (kXcds / P) * (local / RGp);
-    const int b0 = rg * C::kRows;
-    if (b0 >= B) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int wm = wave & 1, wn = wave >> 1;                  // word half, 64-row slice of the tile
     const int Hp = m.Hp;
@@ -105,9 +110,7 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_tiled_kernel(ModelDev m, 
     const T *D = static_cast<const T *>(m.d);
     const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
     const int ntiles = m.Vp / C::kWords;
-    const int t_begin = (int)(((long long)split * ntiles) / S), t_end = (int)(((long long)(split + 1) * ntiles) / S);
     const int nk = Hp / kTK;                                  // chunks per tile
-    const int nchunks = (t_end - t_begin) * nk;
 
     // loader: load q of this thread fills physical 16-byte chunk f = q * threads + tid of an
     // operand tile (row f / 8, position f % 8) with the logical chunk that belongs there
@@ -123,6 +126,11 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_tiled_kernel(ModelDev m, 
     const uint32_t lds0 = lds_address(lds);
     const char *const clds = lds + NS * C::kStageBytes + C::kRedBytes;   // constants, one slot per stage
     const uint32_t cl0 = lds_address(clds);
+    for (int item = local; item < items; item += wg_per_xcd) {
+    const int rg = part * RGp + item % RGp, split = xcd / P + (kXcds / P) * (item / RGp);
+    const int b0 = rg * C::kRows;
+    const int t_begin = (int)(((long long)split * ntiles) / S), t_end = (int)(((long long)(split + 1) * ntiles) / S);
+    const int nchunks = (t_end - t_begin) * nk;
     auto issue = [&](int chunk, int stage) {
         const int t = t_begin + chunk / nk, k0 = (chunk % nk) * kTK;
         const T *wsrc = Ot + (size_t)t * C::kWords * Hp + k0;
@@ -318,6 +326,7 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_tiled_kernel(ModelDev m, 
         else lse2_merge(p.x, p.y, q.x, q.y);
         m.part[(size_t)(b0 + tid) * kMaxSplits + split] = p;
     }
+    }   // items
 }
 
 template <typename T, int MB, int WN, int NS, bool OVL>
@@ -333,26 +342,17 @@ hipError_t launch_tiled_shape(const ModelDev &m, int rows, const int *B_dev, boo
         if (e != hipSuccess) return e;
         attr_set[which] = true;
     }
-    const int RG = (rows + C::kRows - 1) / C::kRows, ntiles = m.Vp / C::kWords;
-    // about wg_target workgroups; splits in multiples of 8 so that the row groups streaming the
-    // same weights share an XCD; at most one split per tile, rounded UP to a multiple of 8 (a
-    // few splits stay empty) so that no split gets two tiles while the others have one
-    int Sx = wg_target / (kXcds * RG);
-    if (Sx > (ntiles + kXcds - 1) / kXcds) Sx = (ntiles + kXcds - 1) / kXcds;
-    if (Sx < 1) Sx = 1;
-    if (Sx > kMaxSplits / kXcds) Sx = kMaxSplits / kXcds;
-    const int S = kXcds * Sx;
-    *splits = fixed_split_info(S);
-    dim3 grid(kXcds * RG * Sx), block(C::kThreads);
-    // hidden rows of all row groups beyond half an L2 (4 MB per XCD): two parts (1.3 % at the
-    // stress workload; four or eight parts are slower, the weights cross the fabric too often)
-    const int P = (RG % 2 == 0 && (size_t)RG * C::kRows * m.Hp * sizeof(T) > ((size_t)2 << 20)) ? 2 : 1;
+    // wg_target workgroups; at most one split per tile of words, rounded UP to a multiple of 8 (a few
+    // splits stay empty) so that no split gets two tiles while the others have one
+    const int wg_per_xcd = wg_target / kXcds, ntiles = m.Vp / C::kWords, sx_cap = (ntiles + kXcds - 1) / kXcds;
+    *splits = SplitInfo{0, wg_per_xcd, C::kRows, sx_cap};
+    dim3 grid(kXcds * wg_per_xcd), block(C::kThreads);
     if (fixed_offset)
         hipLaunchKernelGGL((outproj_tiled_kernel<T, true, MB, WN, NS, OVL>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,
-                           RG, S, P);
+                           wg_per_xcd, sx_cap);
     else
         hipLaunchKernelGGL((outproj_tiled_kernel<T, false, MB, WN, NS, OVL>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,
-                           RG, S, P);
+                           wg_per_xcd, sx_cap);
     return hipGetLastError();
 }
 
