@@ -175,7 +175,9 @@ def test_config3_model_few_rows_full_vocabulary():
 
 
 @pytest.mark.parametrize("V,H,N,distinct", [(5000, 512, 400, 20), (3000, 256, 300, 50), (2000, 128, 200, 64),
-                                            (2000, 512, 260, 65), (40000, 512, 1024, 7)])
+                                            (2000, 512, 260, 65), (40000, 512, 1024, 7),
+                                            (66000, 640, 300, 20),      # tiled kernel (256 x 256 tiles): one row group, 256 splits
+                                            (9000, 640, 300, 20)])      # tiled kernel, fewer word tiles than workgroups
 def test_many_raw_queries_few_distinct_histories(V, H, N, distinct):
     """The search repeats itself (Section 5.2): N raw queries, a handful of distinct histories.  The
     host sizes the launch for N rows; the kernel learns the true count on the device and streams
