@@ -27,6 +27,7 @@
 // over all 16 bank groups.  The direct loads write LDS linearly, so the rotation is applied on the
 // global side: lane i fetches the chunk that belongs at position i.
 #include "device_utils.h"
+#include "outproj_stream_body.h"
 #include "rnnlm_internal.h"
 
 namespace rnnlm {
@@ -63,6 +64,22 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_split3_kernel(ModelDev m,
     if (B <= 0) return;                                       // uniform: no barrier is met
     const RowPlan plan = plan_rows(B, C::kRows, wg_per_xcd, sx_cap);
     const int S = plan.S, items = plan.RG * plan.Sx;
+    // At most 64 rows after all: the time is then the time to read the weights once, and the first S
+    // workgroups stream the fp32 weights instead (4 bytes per weight instead of 6, no LDS round trip
+    // for them; eight-wave shape only, when the three terms of the hidden block fit this kernel's
+    // LDS).  Same partials: split = workgroup index.
+    if constexpr (C::kThreads == kStreamThreads) {
+        if (B <= 64 && m.Ofrag) {
+            const int KS = m.Hp >> 4;
+            if (stream_lds_bytes(3, B <= 32 ? 1 : 2, KS) <= (size_t)C::kLdsBytes) {
+                if ((int)blockIdx.x < S) {
+                    if (B <= 32) outproj_stream_f32_body<1, FIXED>(m, B, 0, (int)blockIdx.x, S, lds);
+                    else outproj_stream_f32_body<2, FIXED>(m, B, 0, (int)blockIdx.x, S, lds);
+                }
+                return;
+            }
+        }
+    }
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, g = lane >> 5;
     const int wm = wave & 1, wn = wave >> 1;                  // word half, 64-row slice of the tile

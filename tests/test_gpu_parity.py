@@ -202,6 +202,34 @@ def test_many_raw_queries_few_distinct_histories(V, H, N, distinct):
     m.close()
 
 
+@pytest.mark.parametrize("V,H,N,distinct", [(20000, 256, 300, 20),     # fewer splits than workgroups
+                                            (40000, 256, 400, 50),     # two row blocks
+                                            (5000, 512, 260, 30),      # one row block is all that fits
+                                            (5000, 512, 260, 40),      # does not fit: three-term kernel, one row group
+                                            (3000, 256, 500, 150)])
+def test_many_raw_queries_few_distinct_histories_fp32(V, H, N, distinct):
+    """The same for fp32 models (the paper's precision): the three-term kernel derives its work split
+    from the true count and streams the fp32 weights when at most 64 rows are left."""
+    cfg = CONFIGS[2].scaled(V=V, H=H, B=N, K=5)
+    model = make_model(cfg)
+    rng = np.random.default_rng(V + N)
+    x = make_step_inputs(cfg, rng)
+    pick = rng.integers(0, distinct, N)
+    pick[:distinct] = np.arange(distinct)
+    keys = (pick.astype(np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+    prev, h_in = x["prev"][pick], x["h_in"][pick]
+    m = load_model(model, "f32", N)
+    for lse_mode in (1, 2):
+        m.set_option(rn.OPT_LSE_MODE, lse_mode)
+        out = gpu_step_dedup(m, keys, prev, h_in, x["query"])
+        U_, rep, inv = oracle.dedup(keys)
+        assert out["n_unique"] == U_ == distinct and np.array_equal(out["rep"], rep) and np.array_equal(out["inverse"], inv)
+        ref = oracle.step(model, prev[rep], h_in[rep], x["query"], row_of_query=inv)
+        check(out["h_out"], out["logprob"], ref, "f32", "fp32 N=%d distinct=%d lse=%d" % (N, distinct, lse_mode))
+    assert m.last_error() == 0
+    m.close()
+
+
 # ------------------------------------------------------------------------ config 5: stress, full size, sampled rows
 def test_config5_stress_full_size_sampled():
     cfg = CONFIGS[5]
