@@ -230,6 +230,21 @@ def test_many_raw_queries_few_distinct_histories_fp32(V, H, N, distinct):
     m.close()
 
 
+@pytest.mark.parametrize("dtype,V,H,B,K", [("bf16", 1500, 640, 5000, 2),     # tiled kernel: more row groups than workgroups per XCD
+                                           ("bf16", 3000, 256, 9000, 2),     # staged kernel, 36 row groups
+                                           ("f32", 1200, 128, 6000, 2)])     # three-term kernel, 24 row groups
+def test_more_row_groups_than_workgroups(dtype, V, H, B, K):
+    """Large batches on a small vocabulary: a workgroup takes several (row group, split) items in turn."""
+    cfg = CONFIGS[3 if dtype == "bf16" else 2].scaled(V=V, H=H, B=B, K=K)
+    model = make_model(cfg)
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed + B))
+    m = load_model(model, dtype, B)
+    h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
+    check(h, lp, oracle.step(model, x["prev"], x["h_in"], x["query"]), dtype, "%s V=%d H=%d B=%d" % (dtype, V, H, B))
+    assert m.last_error() == 0
+    m.close()
+
+
 # ------------------------------------------------------------------------ config 5: stress, full size, sampled rows
 def test_config5_stress_full_size_sampled():
     cfg = CONFIGS[5]
