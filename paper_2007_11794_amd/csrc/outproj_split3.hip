@@ -232,7 +232,7 @@ hipError_t launch_split3_shape(const ModelDev &m, int rows, const int *B_dev, bo
     // tile of words, rounded UP to a multiple of 8 so that no split gets two tiles while the others
     // have one
     const int wg_per_xcd = 32, ntiles = m.Vp / C::kWords, sx_cap = (ntiles + kXcds - 1) / kXcds;
-    *splits = SplitInfo{0, wg_per_xcd, C::kRows, sx_cap};
+    *splits = SplitInfo{0, wg_per_xcd, C::kRows, sx_cap, 0};
     dim3 grid(kXcds * wg_per_xcd), block(C::kThreads);
     if (fixed_offset)
         hipLaunchKernelGGL((outproj_split3_kernel<true, WN>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,

@@ -309,7 +309,7 @@ hipError_t launch_outproj_staged(const ModelDev &m, int rows, const int *B_dev, 
                                  SplitInfo *splits, hipStream_t stream) {
     // One workgroup per compute unit: 256 CUs in 8 XCDs.
     const int wg_per_xcd = 32;
-    *splits = SplitInfo{0, wg_per_xcd, kStagedRows, kMaxSplits / kXcds};
+    *splits = SplitInfo{0, wg_per_xcd, kStagedRows, kMaxSplits / kXcds, 0};
     switch (m.Hp) {
         case 128: return launch_hp<128>(m, rows, B_dev, fixed_offset, wg_per_xcd, stream);
         case 256: return launch_hp<256>(m, rows, B_dev, fixed_offset, wg_per_xcd, stream);

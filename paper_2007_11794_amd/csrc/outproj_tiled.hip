@@ -25,6 +25,7 @@
 // LDS rows are 128 bytes (8 chunks of 16); chunk c of row r sits at c ^ ((r >> 1) & 7), which
 // spreads the 16 lanes served together by one ds_read_b128 over all 16 bank groups.
 #include "device_utils.h"
+#include "outproj_stream_body.h"
 #include "rnnlm_internal.h"
 
 namespace rnnlm {
@@ -84,13 +85,24 @@ struct TiledCfg {
 template <typename T, bool FIXED, int MB, int WN, int NS, bool OVL>
 __global__ __launch_bounds__(2 * WN * 64) void outproj_tiled_kernel(ModelDev m, int rows,
                                                                     const int *__restrict__ B_dev,
-                                                                    int wg_per_xcd, int sx_cap) {
+                                                                    int wg_per_xcd, int sx_cap, int stream_rows) {
     using C = TiledCfg<MB, WN, NS>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // The split follows the TRUE number of rows (after the grouping of ids or the cache lookup only
     // the device knows it): few rows get many vocabulary splits, and the whole grid works.
     const int B = B_dev ? *B_dev : rows;
     if (B <= 0) return;                                       // uniform: no barrier is met
+    // Very few rows after all (stream_rows: as many as this kernel's LDS holds over the whole
+    // reduction length, 0 if the shape cannot do it): a tile would be a chain of 2 Hp / 128 load ->
+    // barrier -> use steps on a fraction of the compute units; every workgroup streams its share
+    // of the weights instead, split = workgroup index.
+    if constexpr (sizeof(T) == 2 && C::kThreads == kStreamThreads) {
+        if (B <= stream_rows) {
+            if (B <= 32) outproj_stream_body<1, FIXED>(m, B, 0, (int)blockIdx.x, (int)gridDim.x, lds);
+            else outproj_stream_body<2, FIXED>(m, B, 0, (int)blockIdx.x, (int)gridDim.x, lds);
+            return;
+        }
+    }
     const RowPlan plan = plan_rows(B, C::kRows, wg_per_xcd, sx_cap);
     const int RG = plan.RG, S = plan.S, items = plan.RG * plan.Sx;
     const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
@@ -345,14 +357,21 @@ hipError_t launch_tiled_shape(const ModelDev &m, int rows, const int *B_dev, boo
     // wg_target workgroups; at most one split per tile of words, rounded UP to a multiple of 8 (a few
     // splits stay empty) so that no split gets two tiles while the others have one
     const int wg_per_xcd = wg_target / kXcds, ntiles = m.Vp / C::kWords, sx_cap = (ntiles + kXcds - 1) / kXcds;
-    *splits = SplitInfo{0, wg_per_xcd, C::kRows, sx_cap};
+    // rows the weight-streaming body can take inside this kernel: 64 or 32, as its LDS allows
+    int stream_rows = 0;
+    if (sizeof(T) == 2 && C::kThreads == kStreamThreads && m.Ofrag && kXcds * wg_per_xcd <= kMaxSplits) {
+        const int KS = m.Hp >> 4;
+        if (stream_lds_bytes(1, 2, KS) <= (size_t)C::kLdsBytes) stream_rows = 64;
+        else if (stream_lds_bytes(1, 1, KS) <= (size_t)C::kLdsBytes) stream_rows = 32;
+    }
+    *splits = SplitInfo{0, wg_per_xcd, C::kRows, sx_cap, stream_rows};
     dim3 grid(kXcds * wg_per_xcd), block(C::kThreads);
     if (fixed_offset)
         hipLaunchKernelGGL((outproj_tiled_kernel<T, true, MB, WN, NS, OVL>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,
-                           wg_per_xcd, sx_cap);
+                           wg_per_xcd, sx_cap, stream_rows);
     else
         hipLaunchKernelGGL((outproj_tiled_kernel<T, false, MB, WN, NS, OVL>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,
-                           wg_per_xcd, sx_cap);
+                           wg_per_xcd, sx_cap, stream_rows);
     return hipGetLastError();
 }
 

@@ -162,17 +162,21 @@ __host__ __device__ inline StagedPlan staged_plan(int B, int wg_per_xcd) {
 }
 
 // How many (max, sum) partials per row the output projection left in m.part: a fixed number, or
-// the S of plan_rows for the true number of rows.
+// the S of plan_rows for the true number of rows; a kernel that streams the weights when at most
+// stream_rows rows are left then leaves one partial per workgroup of its grid.
 struct SplitInfo {
     int fixed_splits;      // > 0: that many
     int wg_per_xcd;        // else plan_rows(B, group_rows, wg_per_xcd, sx_cap).S
     int group_rows;
     int sx_cap;
+    int stream_rows;       // 0 < B <= stream_rows: kXcds * wg_per_xcd instead
 };
 __host__ __device__ inline int splits_of(const SplitInfo &si, int B) {
-    return si.fixed_splits > 0 ? si.fixed_splits : plan_rows(B, si.group_rows, si.wg_per_xcd, si.sx_cap).S;
+    if (si.fixed_splits > 0) return si.fixed_splits;
+    if (B > 0 && B <= si.stream_rows) return kXcds * si.wg_per_xcd;
+    return plan_rows(B, si.group_rows, si.wg_per_xcd, si.sx_cap).S;
 }
-__host__ inline SplitInfo fixed_split_info(int S) { return SplitInfo{S, 0, 1, 1}; }
+__host__ inline SplitInfo fixed_split_info(int S) { return SplitInfo{S, 0, 1, 1, 0}; }
 
 // Output projection + log-sum-exp partials over the vocabulary, on the block m.d.
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,

@@ -177,7 +177,11 @@ def test_config3_model_few_rows_full_vocabulary():
 @pytest.mark.parametrize("V,H,N,distinct", [(5000, 512, 400, 20), (3000, 256, 300, 50), (2000, 128, 200, 64),
                                             (2000, 512, 260, 65), (40000, 512, 1024, 7),
                                             (66000, 640, 300, 20),      # tiled kernel (256 x 256 tiles): one row group, 256 splits
-                                            (9000, 640, 300, 20)])      # tiled kernel, fewer word tiles than workgroups
+                                            (9000, 640, 300, 20),       # tiled kernel, fewer word tiles than workgroups
+                                            (12000, 1216, 300, 30),     # tiled kernel streams one row block (all its LDS holds)
+                                            (12000, 1216, 300, 40),     # ... and does not: one row group of tiles
+                                            (2000, 640, 500, 10),       # 128 x 256 tiles; more workgroups than 32-word blocks
+                                            (2000, 640, 500, 50)])      # ... two row blocks streamed
 def test_many_raw_queries_few_distinct_histories(V, H, N, distinct):
     """The search repeats itself (Section 5.2): N raw queries, a handful of distinct histories.  The
     host sizes the launch for N rows; the kernel learns the true count on the device and streams
