@@ -17,6 +17,8 @@
 // Three kernels: the LDS-tiled bf16 kernel (the default), the register-direct bf16 kernel it
 // replaced (kept for hidden sizes that are not a multiple of 4 or unaligned buffers), and the
 // fp32 kernel on the full-precision matrix instruction.
+#include <limits.h>
+
 #include "device_utils.h"
 #include "rnnlm_internal.h"
 
@@ -176,10 +178,12 @@ template <int NS, int TB, int SUB>
 __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
-    float *__restrict__ h_out) {
+    float *__restrict__ h_out, int b_min, int b_max) {
     using C = RtCfg<TB>;
     constexpr bool kSplitK = TB == 32;
     const int B = B_dev ? *B_dev : rows;
+    // When only the device knows the row count, both shapes are launched and the count picks one.
+    if (B < b_min || B > b_max) return;
     // Workgroup id modulo 8 is the XCD (L2 domain).  Row block rb runs on XCD rb % 8 with all
     // its unit blocks, so h_in (the larger operand) is fetched into one L2 only.
     const int JB = m.Hp / kRtTile;
@@ -461,31 +465,47 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16 && m.H % 4 == 0 && (reinterpret_cast<uintptr_t>(h_in) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(h_out) & 15) == 0) {
-        const int big_blocks = (rows + 63) / 64, units = m.Hp / kRtTile;
-        if (big_blocks * units > 256) {                 // several 64 x 64 workgroups per compute unit
+        const int units = m.Hp / kRtTile;
+        static bool attr_set = false;                   // the small shape takes more than the default 64 KB of dynamic LDS
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 1>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 4 * RtCfg<32>::kStageBytes);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 2>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 8 * RtCfg<32>::kStageBytes);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        // The small shape (32 rows per workgroup) while its workgroups fit the compute units in one
+        // round, the large one (64 rows, three workgroups per unit) beyond: the crossover measured
+        // at H = 512, 768, 1024 and 2048 lies there.
+        const int small_max = 32 * (256 / units);       // most rows the small shape is chosen for
+        auto launch_big = [&](int b_min) {
+            const int big_blocks = (rows + 63) / 64;
             dim3 grid(kXcds * ((big_blocks + kXcds - 1) / kXcds) * units);
             hipLaunchKernelGGL((recur_bf16_tiled_kernel<2, 64, 1>), grid, dim3(256), 2 * RtCfg<64>::kStageBytes, stream,
-                               m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
-        } else {                                        // small problem: 64 x 32, all compute units
-            static bool attr_set = false;               // more than the default 64 KB of dynamic LDS
-            if (!attr_set) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 1>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   4 * RtCfg<32>::kStageBytes);
-                if (e == hipSuccess)
-                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 2>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 8 * RtCfg<32>::kStageBytes);
-                if (e != hipSuccess) return e;
-                attr_set = true;
-            }
-            const int small_blocks = (rows + 31) / 32;
+                               m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, b_min, INT_MAX);
+        };
+        auto launch_small = [&](int upto) {             // grid for `upto` rows
+            const int small_blocks = (upto + 31) / 32;
             dim3 grid(kXcds * ((small_blocks + kXcds - 1) / kXcds) * units);
             if (m.Hp % 128 == 0)
                 hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32, 2>), grid, dim3(256), 8 * RtCfg<32>::kStageBytes,
-                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
+                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, 0, upto);
             else
                 hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32, 1>), grid, dim3(256), 4 * RtCfg<32>::kStageBytes,
-                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out);
+                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, 0, upto);
+        };
+        if (rows <= small_max) {
+            launch_small(rows);
+        } else if (B_dev && small_max > 0 && m.Hp >= 1024) {
+            // The true count may be far below the bound: launch both, the count on the device picks
+            // and the other one ends at once.  The extra launch costs 1 to 3 us per step; for few rows
+            // the small shape saves 5 us from Hp = 1024 on and under 1 us at Hp = 768 (measured).
+            launch_small(small_max);
+            launch_big(small_max + 1);
+        } else {
+            launch_big(0);
         }
     } else if (m.dtype == RNNLM_BF16) {
         dim3 grid(m.Hp / 32, (rows + 31) / 32);

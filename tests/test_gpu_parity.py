@@ -181,7 +181,9 @@ def test_config3_model_few_rows_full_vocabulary():
                                             (12000, 1216, 300, 30),     # tiled kernel streams one row block (all its LDS holds)
                                             (12000, 1216, 300, 40),     # ... and does not: one row group of tiles
                                             (2000, 640, 500, 10),       # 128 x 256 tiles; more workgroups than 32-word blocks
-                                            (2000, 640, 500, 50)])      # ... two row blocks streamed
+                                            (2000, 640, 500, 50),       # ... two row blocks streamed
+                                            (3000, 1024, 700, 25),      # hidden update: both shapes launched, the small one works
+                                            (3000, 1024, 700, 600)])    # ... the large one works
 def test_many_raw_queries_few_distinct_histories(V, H, N, distinct):
     """The search repeats itself (Section 5.2): N raw queries, a handful of distinct histories.  The
     host sizes the launch for N rows; the kernel learns the true count on the device and streams
