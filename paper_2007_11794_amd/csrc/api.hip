@@ -349,9 +349,18 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
     if (N > 0 && K > 0 && (!query_word || !score)) return RNNLM_EINVAL;
     if (N > 0 && h_out == h_in) return RNNLM_EINVAL;
     if (cache && (cache->dev.H != model->dev.H || N > cache->max_B)) return RNNLM_ERANGE;
-    rc = rnnlm_dedup(history_ids, N, rep, inverse, n_unique, workspace, workspace_bytes, hip_stream);
-    if (rc != RNNLM_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // through a cache, few enough raw queries: grouping and lookup are one launch
+    const bool one_launch = cache && N > 0 && N <= dedup_lookup_max_rows();
+    if (one_launch) {
+        if (!workspace || workspace_bytes < dedup_workspace_bytes(N)) return RNNLM_EWORKSPACE;   // as rnnlm_dedup
+        if (reinterpret_cast<uintptr_t>(workspace) & 15) return RNNLM_EWORKSPACE;
+        if (launch_dedup_lookup(cache->dev, history_ids, N, rep, inverse, n_unique, step_stats, s) != hipSuccess)
+            return RNNLM_EDEVICE;
+    } else {
+        rc = rnnlm_dedup(history_ids, N, rep, inverse, n_unique, workspace, workspace_bytes, hip_stream);
+        if (rc != RNNLM_OK) return rc;
+    }
     const ModelDev &d = model->dev;
     SplitInfo splits = fixed_split_info(1);
     if (!cache) {
@@ -368,7 +377,9 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
         return RNNLM_OK;
     }
     const CacheDev &c = cache->dev;
-    if (launch_cache_lookup(c, N, 4096, history_ids, rep, n_unique, step_stats, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (!one_launch &&
+        launch_cache_lookup(c, N, 4096, history_ids, rep, n_unique, step_stats, s) != hipSuccess)
+        return RNNLM_EDEVICE;
     if (N == 0) return RNNLM_OK;
     // Only the histories the cache does not hold are computed: *c.n_miss rows, row r taken
     // from raw query c.miss_src[r], its hidden vector written to row c.miss_dst[r] of h_out.

@@ -17,6 +17,7 @@
 //   (hidden update and output projection run on the numbered rows only)
 //   commit   per distinct history: normaliser into lse_rows; new entries are written to the
 //            stores, found ones copy their stored h' to the caller's h_out.
+#include "dedup_small_body.h"
 #include "device_utils.h"
 #include "rnnlm_internal.h"
 
@@ -48,18 +49,12 @@ __global__ __launch_bounds__(256) void cache_reset_kernel(CacheDev c) {
 // earlier round of the same step inserted.
 constexpr int kLookupPer = 4;
 
-__global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
-    CacheDev c, int rows, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
-    const int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
+// raw_of(u0, i, u) / key_of(u0, i, u, raw): representative and id of distinct history u (slice i of
+// the round that starts at u0), u < U.
+template <typename RawOf, typename KeyOf>
+__device__ __forceinline__ void cache_lookup_body(const CacheDev &c, int U, int32_t *__restrict__ step_stats,
+                                                  RawOf raw_of, KeyOf key_of) {
     __shared__ int wsum[kLookupThreads / 64 + 1];
-    // The first slice's representatives and ids are requested before the number of distinct
-    // histories is known (rep has `rows` slots; what lies beyond the true count is clamped into
-    // range and dropped later): one memory latency less at the head of the chain.
-    const int u_first = (int)threadIdx.x;
-    int raw_first = (u_first < rows) ? rep[u_first] : 0;
-    raw_first = max(min(raw_first, rows - 1), 0);
-    const uint64_t key_first = (rows > 0) ? ids[raw_first] : 0;
-    const int U = *n_unique;
     const int base = *c.n_entries;          // read by everyone before thread 0 updates it below
     const uint32_t mask = (uint32_t)(c.table_size - 1);
     int n_miss = 0;                         // misses numbered so far (same in every thread)
@@ -71,12 +66,12 @@ __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
 #pragma unroll
         for (int i = 0; i < kLookupPer; ++i) {
             const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
-            raw[i] = (u0 == 0 && i == 0) ? raw_first : ((u < U) ? rep[u] : 0);
+            raw[i] = (u < U) ? raw_of(u0, i, u) : 0;
         }
 #pragma unroll
         for (int i = 0; i < kLookupPer; ++i) {
             const int u = u0 + i * kLookupThreads + (int)threadIdx.x;
-            key[i] = (u0 == 0 && i == 0) ? (u < U ? key_first : 0) : ((u < U) ? ids[raw[i]] : 0);
+            key[i] = (u < U) ? key_of(u0, i, u, raw[i]) : 0;
             h[i] = mix64(key[i]) & mask;
             cell[i] = c.table[h[i]];
         }
@@ -145,6 +140,36 @@ __global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
             step_stats[3] = base + stored;
         }
     }
+}
+
+__global__ __launch_bounds__(kLookupThreads) void cache_lookup_kernel(
+    CacheDev c, int rows, const uint64_t *__restrict__ ids, const int32_t *__restrict__ rep,
+    const int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
+    // The first slice's representatives and ids are requested before the number of distinct
+    // histories is known (rep has `rows` slots; what lies beyond the true count is clamped into
+    // range and dropped later): one memory latency less at the head of the chain.
+    const int u_first = (int)threadIdx.x;
+    int raw_first = (u_first < rows) ? rep[u_first] : 0;
+    raw_first = max(min(raw_first, rows - 1), 0);
+    const uint64_t key_first = (rows > 0) ? ids[raw_first] : 0;
+    const int U = *n_unique;
+    cache_lookup_body(
+        c, U, step_stats, [&](int u0, int i, int u) { return (u0 == 0 && i == 0) ? raw_first : rep[u]; },
+        [&](int u0, int i, int u, int raw) { return (u0 == 0 && i == 0) ? key_first : ids[raw]; });
+}
+
+// Grouping of the step's ids and the lookup of the distinct ones in one launch of one workgroup
+// (N <= kSmallN): the lookup takes representatives and ids from LDS, where the grouping left them,
+// so nothing is read back from memory between the two and one launch is saved.
+static_assert(kLookupThreads == kSmallThreads, "");
+__global__ __launch_bounds__(kLookupThreads) void dedup_lookup_kernel(
+    CacheDev c, const uint64_t *__restrict__ ids, int N, int32_t *__restrict__ rep,
+    int32_t *__restrict__ inverse, int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
+    const SmallGroups g = dedup_small_body(ids, N, rep, inverse, n_unique);
+    __syncthreads();                        // the groups in LDS are complete
+    cache_lookup_body(
+        c, g.total, step_stats, [&](int, int, int u) { return g.rep[u]; },
+        [&](int, int, int u, int) { return g.id[u]; });
 }
 
 // ---- the same lookup for many histories (more than one workgroup can number in one round):
@@ -305,6 +330,16 @@ hipError_t launch_cache_lookup(const CacheDev &c, int rows, int one_group_rows, 
                        step_stats);
     hipLaunchKernelGGL(lookup_assign_kernel, dim3(blocks), dim3(kLookupThreads), 0, stream, c, blocks, ids, rep,
                        n_unique);
+    return hipGetLastError();
+}
+
+int dedup_lookup_max_rows() { return kSmallN; }
+
+hipError_t launch_dedup_lookup(const CacheDev &c, const uint64_t *ids, int N, int32_t *rep, int32_t *inverse,
+                               int32_t *n_unique, int32_t *step_stats, hipStream_t stream) {
+    if (N <= 0 || N > kSmallN) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dedup_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, N, rep, inverse,
+                       n_unique, step_stats);
     return hipGetLastError();
 }
 

@@ -211,6 +211,11 @@ hipError_t launch_cache_reset(const CacheDev &c, hipStream_t stream);
 hipError_t launch_cache_lookup(const CacheDev &c, int rows, int one_group_rows, const uint64_t *ids,
                                const int32_t *rep, const int32_t *n_unique, int32_t *step_stats,
                                hipStream_t stream);
+// Grouping of the ids (launch_dedup) and this lookup in ONE launch of one workgroup, for
+// 0 < N <= dedup_lookup_max_rows() raw queries.
+int dedup_lookup_max_rows();
+hipError_t launch_dedup_lookup(const CacheDev &c, const uint64_t *ids, int N, int32_t *rep, int32_t *inverse,
+                               int32_t *n_unique, int32_t *step_stats, hipStream_t stream);
 // After the computed block is done: normalisers of all distinct histories into c.lse_rows,
 // new entries into the stores, stored hidden vectors of found histories into h_out.
 hipError_t launch_cache_commit(const CacheDev &c, const ModelDev &m, int rows, const int32_t *n_unique,
