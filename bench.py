@@ -196,6 +196,11 @@ def main() -> int:
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time the platform's GEMM (torch.matmul, bf16) on the output projection's "
                          "contraction alone, logits written to HBM, no log-sum-exp: context for the roofline")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the matrix-core rate probe that is run after the timed region when the "
+                         "roofline is the MFMA one (rnnlm_probe_mfma_rate: what the device sustains on the "
+                         "output projection's loop shape, reported beside the data-sheet peak); "
+                         "--no-cpu-baseline skips it too (runs under a profiler)")
     ap.add_argument("--hs", action="store_true",
                     help="the chosen workload with the hierarchical output layer (Huffman tree over the "
                          "Zipf word frequencies) in place of the full softmax")
@@ -367,6 +372,17 @@ def main() -> int:
                     "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) and args.config == 3 and args.rows is None else None,
                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
                     "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
+
+    if roofline["bound"] == "mfma" and not args.no_mfma_probe and not args.no_cpu_baseline:
+        # context for `frac`: the rate this device sustains on the same loop shape with nothing else
+        # to do (one probe launch = 68.7 GFLOP, the size of the headline launch), after the timed region
+        probe = {}
+        for name, feed, data in (("registers_zeros", 0, 0), ("registers_random", 0, 1),
+                                 ("lds_feed_exp_zeros", 1, 0), ("lds_feed_exp_random", 1, 1)):
+            tf, ghz = rn.rnnlm_probe_mfma_rate(feed, data, 20)
+            probe[name] = {"tflops": round(tf, 1), "core_ghz": round(ghz, 3)}
+        roofline["sustained_probe"] = probe
+        roofline["frac_of_sustained"] = round(achieved / probe["lds_feed_exp_random"]["tflops"], 4)
 
     gemm_ref = None
     if args.gemm_reference and bf16:

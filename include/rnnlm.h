@@ -337,6 +337,23 @@ int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N,
 int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream,
                        float *ms_per_launch);
 
+/*
+ * Measurement aid, no part of the method: the rate the bf16 matrix cores of the current device
+ * sustain on a loop shaped like the output projection's inner loop (the whole-vocabulary
+ * normalisation of Section 2 is where the time goes), so that the kernel's rate can be set against
+ * what this device gives under load and not only against the data-sheet peak.  One workgroup of
+ * eight waves per compute unit, chains of 32 dependent 32x32x16 bf16 MFMAs, no memory traffic.
+ *   feed 0: both operands in registers; feed 1: one operand read from LDS four steps ahead and
+ *           one exp2-and-add per produced logit in between (the output projection's steady state);
+ *   data 0: all-zero operands; data 1: random bf16 of the size of weights and centred activations
+ *           (the clock under matrix load depends on the data).
+ * Runs `launches` (1..1000) launches back to back on the null stream between two HIP events,
+ * synchronises, allocates and frees 0.6 MB of device memory of its own.  *tflops: dense bf16
+ * TFLOP/s; *core_ghz (may be NULL): core clock during the last launch, from the kernel's own cycle
+ * counter against the constant 100 MHz one.  RNNLM_EINVAL for arguments outside these ranges.
+ */
+int rnnlm_probe_mfma_rate(int feed, int data, int launches, double *tflops, double *core_ghz);
+
 #ifdef __cplusplus
 }
 #endif

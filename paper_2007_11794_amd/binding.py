@@ -26,7 +26,8 @@ EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rn
            "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
            "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
            "rnnlm_index_free", "rnnlm_index_reset", "rnnlm_index_intern", "rnnlm_index_fetch",
-           "rnnlm_index_stats", "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step", "rnnlm_hs_time_query"]
+           "rnnlm_index_stats", "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step", "rnnlm_hs_time_query",
+           "rnnlm_probe_mfma_rate"]
 
 
 class RnnlmError(RuntimeError):
@@ -68,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_step_dedup.restype = I
         L.rnnlm_time_outproj.argtypes = [P, I, I, P, ctypes.POINTER(ctypes.c_float)]
         L.rnnlm_time_outproj.restype = I
+        L.rnnlm_probe_mfma_rate.argtypes = [I, I, I, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+        L.rnnlm_probe_mfma_rate.restype = I
         L.rnnlm_cache_create.argtypes = [P, I, ctypes.POINTER(P)]
         L.rnnlm_cache_create.restype = I
         L.rnnlm_cache_free.argtypes = [P]
@@ -172,6 +175,14 @@ class RnnlmModel:
             self.close()
         except Exception:
             pass
+
+
+def rnnlm_probe_mfma_rate(feed: int, data: int, launches: int = 20):
+    """(TFLOP/s, core GHz) the bf16 matrix cores sustain on the output projection's loop shape."""
+    tf, ghz = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().rnnlm_probe_mfma_rate(int(feed), int(data), int(launches), ctypes.byref(tf), ctypes.byref(ghz)),
+           "rnnlm_probe_mfma_rate")
+    return tf.value, ghz.value
 
 
 def rnnlm_load(V: int, H: int, dtype: int, U: np.ndarray, W: np.ndarray, O: np.ndarray,

@@ -69,6 +69,12 @@ def test_host_checked_errors_return_before_any_device_work():
     assert L.rnnlm_dedup(p, (1 << 28) + 1, p, p, p, p, 1 << 20, None) == ERANGE
     ms = ctypes.c_float()
     assert L.rnnlm_time_outproj(None, 1, 1, None, ctypes.byref(ms)) == EINVAL
+    tf = ctypes.c_double()
+    assert L.rnnlm_probe_mfma_rate(2, 0, 1, ctypes.byref(tf), None) == EINVAL
+    assert L.rnnlm_probe_mfma_rate(0, -1, 1, ctypes.byref(tf), None) == EINVAL
+    assert L.rnnlm_probe_mfma_rate(0, 0, 0, ctypes.byref(tf), None) == EINVAL
+    assert L.rnnlm_probe_mfma_rate(0, 0, 1001, ctypes.byref(tf), None) == EINVAL
+    assert L.rnnlm_probe_mfma_rate(0, 0, 1, None, None) == EINVAL
 
 
 def test_binding_refuses_cpu_tensors():

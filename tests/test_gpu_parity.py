@@ -508,3 +508,16 @@ def test_million_word_vocabulary(dtype):
     check(h, lp, {"h_out": ref["h_out"][:20], "logprob": ref["logprob"][:20]}, dtype, "V=1000003 %s, 20 rows" % dtype)
     assert m.last_error() == 0
     m.close()
+
+
+# ------------------------------------------------------------------------ measurement aid
+def test_matrix_rate_probe_reports_a_rate_between_nothing_and_the_data_sheet_peak():
+    """rnnlm_probe_mfma_rate: the figures bench.py prints beside the roofline.  All-zero operands may
+    not be slower than random ones (same instruction stream; only the clock under load differs)."""
+    rates = {}
+    for feed in (0, 1):
+        for data in (0, 1):
+            tf, ghz = rn.rnnlm_probe_mfma_rate(feed, data, 5)
+            assert 100.0 < tf < 2600.0 and 0.3 < ghz < 3.0, (feed, data, tf, ghz)
+            rates[(feed, data)] = tf
+    assert rates[(0, 0)] >= 0.95 * rates[(0, 1)] and rates[(1, 0)] >= 0.95 * rates[(1, 1)]
