@@ -181,9 +181,11 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     float *__restrict__ h_out, int b_min, int b_max) {
     using C = RtCfg<TB>;
     constexpr bool kSplitK = TB == 32;
-    const int B = B_dev ? *B_dev : rows;
-    // When only the device knows the row count, both shapes are launched and the count picks one.
-    if (B < b_min || B > b_max) return;
+    // When only the device knows the row count, both shapes are launched and the count picks one:
+    // the launch whose range the count is not in sees no rows.  (Folded into B, not a branch of
+    // its own: a branch here would put two more dependent scalar loads in front of everything.)
+    const int B_true = B_dev ? *B_dev : rows;
+    const int B = (B_true < b_min || B_true > b_max) ? 0 : B_true;
     // Workgroup id modulo 8 is the XCD (L2 domain).  Row block rb runs on XCD rb % 8 with all
     // its unit blocks, so h_in (the larger operand) is fetched into one L2 only.
     const int JB = m.Hp / kRtTile;
