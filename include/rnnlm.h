@@ -72,9 +72,9 @@ enum rnnlm_option {
      * bf16 matrix-core speed: the automatic choice for fp32 from 64 rows on, 5 = the weight-
      * streaming kernel for few rows, which reads a second, operand-ordered copy of the output
      * weights once per launch at memory speed (fp32 models: cut into three bf16 terms in registers,
-     * fp32 accuracy): the automatic choice up to 64 rows when two launches suffice (bf16 models with H <= 512 and
-     * fp32 models also take it on the device, when a grouped or cached step turns out to have that
-     * few rows).  One launch
+     * fp32 accuracy): the automatic choice up to 64 rows when two launches suffice (the staged, the
+     * eight-wave tiled and the three-term kernel also take it on the device, when a grouped or
+     * cached step turns out to have that few rows and their LDS holds them).  One launch
      * serves as many rows as fit its LDS (bf16: 128 up to H = 576, 64 up to H = 1216, 32 up to
      * H = 2432; fp32: 128 up to H = 192, 64 up to H = 384, 32 up to H = 768); on request it takes
      * up to 128 rows in at most four launches, and larger batches go the automatic way.
