@@ -172,6 +172,17 @@ __global__ __launch_bounds__(kLookupThreads) void dedup_lookup_kernel(
         [&](int, int, int u, int) { return g.id[u]; });
 }
 
+// The same for up to kMediumN raw queries (the grouping keeps the keys in LDS in raw order).
+__global__ __launch_bounds__(kLookupThreads) void dedup_lookup_medium_kernel(
+    CacheDev c, const uint64_t *__restrict__ ids, int N, int32_t *__restrict__ rep,
+    int32_t *__restrict__ inverse, int32_t *__restrict__ n_unique, int32_t *__restrict__ step_stats) {
+    const MediumGroups g = dedup_medium_body(ids, N, rep, inverse, n_unique);
+    __syncthreads();                        // the representatives in LDS are complete
+    cache_lookup_body(
+        c, g.total, step_stats, [&](int, int, int u) { return g.rep[u]; },
+        [&](int, int, int, int raw) { return g.key[raw]; });
+}
+
 // ---- the same lookup for many histories (more than one workgroup can number in one round):
 // probe + per-workgroup miss counts, a scan of the counts, then numbering + insertion.  The
 // launch boundaries put every probe before every insertion.
@@ -333,13 +344,17 @@ hipError_t launch_cache_lookup(const CacheDev &c, int rows, int one_group_rows, 
     return hipGetLastError();
 }
 
-int dedup_lookup_max_rows() { return kSmallN; }
+int dedup_lookup_max_rows() { return kMediumN; }
 
 hipError_t launch_dedup_lookup(const CacheDev &c, const uint64_t *ids, int N, int32_t *rep, int32_t *inverse,
                                int32_t *n_unique, int32_t *step_stats, hipStream_t stream) {
-    if (N <= 0 || N > kSmallN) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(dedup_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, N, rep, inverse,
-                       n_unique, step_stats);
+    if (N <= 0 || N > kMediumN) return hipErrorInvalidValue;
+    if (N <= kSmallN)
+        hipLaunchKernelGGL(dedup_lookup_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, N, rep, inverse,
+                           n_unique, step_stats);
+    else
+        hipLaunchKernelGGL(dedup_lookup_medium_kernel, dim3(1), dim3(kLookupThreads), 0, stream, c, ids, N, rep,
+                           inverse, n_unique, step_stats);
     return hipGetLastError();
 }
 

@@ -9,7 +9,8 @@
 // prefix sum over the "first" flags gives the group numbers.
 //
 // Two implementations with identical results:
-//   small  (N <= kSmallN): one workgroup, table and flags in LDS, one launch;
+//   small  (N <= kSmallN): one workgroup, table and flags in LDS, one launch (N <= kMediumN: the
+//          same with a table of raw indices and the keys in LDS once);
 //   large  : table in the caller's workspace, six launches (the numbering is a grid-wide scan).
 #include "dedup_small_body.h"
 #include "device_utils.h"
@@ -30,6 +31,12 @@ __global__ __launch_bounds__(kSmallThreads) void dedup_small_kernel(
     const uint64_t *__restrict__ keys, int N, int32_t *__restrict__ rep,
     int32_t *__restrict__ inverse, int32_t *__restrict__ n_unique) {
     dedup_small_body(keys, N, rep, inverse, n_unique);
+}
+
+__global__ __launch_bounds__(kSmallThreads) void dedup_medium_kernel(
+    const uint64_t *__restrict__ keys, int N, int32_t *__restrict__ rep,
+    int32_t *__restrict__ inverse, int32_t *__restrict__ n_unique) {
+    dedup_medium_body(keys, N, rep, inverse, n_unique);
 }
 
 // ------------------------------------------------------------------------------ large path
@@ -148,6 +155,11 @@ hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inve
     }
     if (N <= kSmallN) {
         hipLaunchKernelGGL(dedup_small_kernel, dim3(1), dim3(kSmallThreads), 0, stream, keys, N, rep,
+                           inverse, n_unique);
+        return hipGetLastError();
+    }
+    if (N <= kMediumN) {
+        hipLaunchKernelGGL(dedup_medium_kernel, dim3(1), dim3(kSmallThreads), 0, stream, keys, N, rep,
                            inverse, n_unique);
         return hipGetLastError();
     }

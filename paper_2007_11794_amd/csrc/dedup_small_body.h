@@ -1,4 +1,4 @@
-// The one-workgroup grouping of history ids (N <= kSmallN) as a device function: the kernel of its
+// The one-workgroup grouping of history ids (N <= kSmallN, and a second form up to kMediumN) as device functions: the kernel of its
 // own runs it, and so does the kernel that goes on to the cache lookup in the same launch.
 #pragma once
 
@@ -105,6 +105,105 @@ __device__ __forceinline__ SmallGroups dedup_small_body(const uint64_t *__restri
     }
     if (threadIdx.x == 0) *n_unique = total;
     return SmallGroups{total, rep_lds, id_lds};
+}
+
+// ------------------------------------------------------------------------------ up to kMediumN ids
+// The same grouping for more ids in the same LDS: the table keeps, per slot, the
+// index of a raw query (4 bytes) instead of the key (8 bytes), and the keys themselves sit in LDS
+// once, in raw order; a probe compares its key with the key of the query the slot points to.  A
+// slot's index is only ever replaced by a smaller index of the SAME key (atomicMin after the
+// comparison), so the key a slot stands for never changes, and after all insertions the slot holds
+// the first raw index of its group.  No key value is special here.
+// (7 ids per thread; with 8192 ids, half of the slots taken, the probe chains make the one workgroup
+// slower than the six launches of the grid-wide form: 16 to 30 us against 21 to 23, measured)
+constexpr int kMediumN = 7168;
+constexpr int kMediumCap = 16384;
+
+struct MediumGroups {
+    int total;
+    const int *rep;          // [total]
+    const uint64_t *key;     // [N] in raw order: id of group u = key[rep[u]]
+};
+
+__device__ __forceinline__ MediumGroups dedup_medium_body(const uint64_t *__restrict__ keys, int N,
+                                                          int32_t *__restrict__ rep, int32_t *__restrict__ inverse,
+                                                          int32_t *__restrict__ n_unique) {
+    __shared__ uint64_t lkey[kMediumN];
+    __shared__ int table[kMediumCap];        // raw index, later the group number, last the representatives
+    __shared__ int wsum[kSmallThreads / 64 + 1];
+    constexpr int kPer = kMediumN / kSmallThreads;
+    const int per = (N + kSmallThreads - 1) / kSmallThreads;
+    uint64_t key[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int n = threadIdx.x * per + i;
+        key[i] = (i < per && n < N) ? keys[n] : 0;
+    }
+    for (int i = threadIdx.x; i < kMediumCap; i += kSmallThreads) table[i] = -1;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int n = threadIdx.x * per + i;
+        if (i < per && n < N) lkey[n] = key[i];
+    }
+    __syncthreads();
+    int slot[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int n = threadIdx.x * per + i;
+        slot[i] = -1;
+        if (i < per && n < N) {
+            uint32_t h = mix64(key[i]) & (uint32_t)(kMediumCap - 1);
+            // at most N <= kMediumCap / 2 slots are ever taken: a free one is always met
+            for (int probe = 0; probe < kMediumCap; ++probe) {
+                int cur = table[h];
+                if (cur < 0) {
+                    cur = atomicCAS(&table[h], -1, n);
+                    if (cur < 0) { slot[i] = (int)h; break; }          // claimed
+                }
+                if (lkey[cur] == key[i]) {
+                    atomicMin(&table[h], n);
+                    slot[i] = (int)h;
+                    break;
+                }
+                h = (h + 1) & (uint32_t)(kMediumCap - 1);
+            }
+        }
+    }
+    __syncthreads();
+
+    int is_first[kPer];
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int n = threadIdx.x * per + i;
+        is_first[i] = (slot[i] >= 0 && table[slot[i]] == n) ? 1 : 0;
+        mine += is_first[i];
+    }
+    int total;
+    const int u0 = block_exclusive_scan(mine, wsum, total);   // barriers inside: all reads of the first indices done
+    int u = u0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        if (is_first[i]) {
+            rep[u] = threadIdx.x * per + i;
+            table[slot[i]] = u;                                // the slot now carries its group number
+            ++u;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int n = threadIdx.x * per + i;
+        if (slot[i] >= 0) inverse[n] = table[slot[i]];
+    }
+    if (threadIdx.x == 0) *n_unique = total;
+    __syncthreads();                                           // the group numbers are read: the table is free
+    u = u0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        if (is_first[i]) table[u++] = threadIdx.x * per + i;   // representatives, for a consumer in this workgroup
+    }
+    return MediumGroups{total, table, lkey};
 }
 
 }  // namespace rnnlm

@@ -90,7 +90,8 @@ def test_steps_through_the_cache_match_the_oracle(dtype, V, H, kernel, capacity)
 
 
 def test_many_histories_take_the_grid_wide_lookup():
-    """More than 4096 raw queries: grouping and lookup run as grid-wide scans."""
+    """More than 4096 raw queries: grouping and lookup in one workgroup with the keys in LDS (up to
+    7168), as grid-wide scans beyond."""
     rng = np.random.default_rng(77)
     V, H, K = 2000, 64, 2
     model = small_model(rng, V, H, "bf16", 0.1)
@@ -100,7 +101,7 @@ def test_many_histories_take_the_grid_wide_lookup():
         cache = rn.rnnlm_cache_create(m, capacity)
         ocache = oracle.Cache(H, capacity)
         st = CachedStepper(m, cache, 9000, K)
-        for step, N in enumerate([6000, 9000, 4097]):
+        for step, N in enumerate([6000, 9000, 4097, 7168]):
             ids, prev, h_in, query, base = draw_step(rng, V, H, N, K, pool)
             out = st.step(ids, prev, h_in, query, base)
             ref = oracle.step_cached(model, ocache, ids, prev, h_in, query, base_score=base)
