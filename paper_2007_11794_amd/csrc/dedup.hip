@@ -11,7 +11,8 @@
 // Two implementations with identical results:
 //   small  (N <= kSmallN): one workgroup, table and flags in LDS, one launch (N <= kMediumN: the
 //          same with a table of raw indices and the keys in LDS once);
-//   large  : table in the caller's workspace, six launches (the numbering is a grid-wide scan).
+//   large  : table in the caller's workspace, five launches (the numbering is a grid-wide scan; six
+//            beyond a million ids).
 #include "dedup_small_body.h"
 #include "device_utils.h"
 #include "rnnlm_internal.h"
@@ -77,9 +78,9 @@ __global__ void dedup_insert_kernel(const uint64_t *__restrict__ keys, int N, ui
     atomicMin(&tfirst[s], n);
 }
 
-// Group numbers in raw order = exclusive prefix sum over the "first" flags, in three launches so
-// that every query is touched by a full grid: per-workgroup counts, a scan of those counts by
-// one workgroup, then the numbering proper.
+// Group numbers in raw order = exclusive prefix sum over the "first" flags, so that every query is
+// touched by a full grid: per-workgroup counts, then the numbering proper, which adds up the counts
+// of the workgroups before it (beyond 1024 workgroups a scan of the counts by one workgroup comes in between).
 constexpr int kRankThreads = 1024;
 
 __device__ __forceinline__ int first_flag(int n, int N, const int *__restrict__ slot,
@@ -114,20 +115,33 @@ __global__ __launch_bounds__(kRankThreads) void dedup_scan_kernel(int blocks, in
     if (threadIdx.x == 0) *n_unique = carry;
 }
 
+// SCANNED: block_total holds the exclusive prefix already (dedup_scan_kernel ran).  Otherwise (at
+// most kRankThreads workgroups) it holds the plain counts, every workgroup adds up the counts before
+// its own, and the last one writes the total: one launch less.
+template <bool SCANNED>
 __global__ __launch_bounds__(kRankThreads) void dedup_number_kernel(int N, const int *__restrict__ slot,
                                                                     const int *__restrict__ tfirst,
                                                                     const int *__restrict__ block_total,
                                                                     int *__restrict__ tgroup,
-                                                                    int32_t *__restrict__ rep) {
+                                                                    int32_t *__restrict__ rep,
+                                                                    int32_t *__restrict__ n_unique) {
     __shared__ int wsum[kRankThreads / 64 + 1];
     const int n = blockIdx.x * kRankThreads + threadIdx.x;
     int s, total;
     const int first = first_flag(n, N, slot, tfirst, s);
-    const int u = block_total[blockIdx.x] + block_exclusive_scan(first, wsum, total);
+    int before;
+    if (SCANNED) {
+        before = block_total[blockIdx.x];
+    } else {
+        const int v = ((int)threadIdx.x < (int)blockIdx.x) ? block_total[threadIdx.x] : 0;
+        (void)block_exclusive_scan(v, wsum, before);
+    }
+    const int u = before + block_exclusive_scan(first, wsum, total);
     if (first) {
         rep[u] = n;
         tgroup[s] = u;
     }
+    if (!SCANNED && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) *n_unique = before + total;
 }
 
 __global__ void dedup_inverse_kernel(int N, const int *__restrict__ slot,
@@ -172,9 +186,15 @@ hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inve
     const int blocks = (N + kRankThreads - 1) / kRankThreads;
     hipLaunchKernelGGL(dedup_count_kernel, dim3(blocks), dim3(kRankThreads), 0, stream, N, w.slot, w.tfirst,
                        w.block_total);
-    hipLaunchKernelGGL(dedup_scan_kernel, dim3(1), dim3(kRankThreads), 0, stream, blocks, w.block_total, n_unique);
-    hipLaunchKernelGGL(dedup_number_kernel, dim3(blocks), dim3(kRankThreads), 0, stream, N, w.slot, w.tfirst,
-                       w.block_total, w.tgroup, rep);
+    if (blocks <= kRankThreads) {
+        hipLaunchKernelGGL(dedup_number_kernel<false>, dim3(blocks), dim3(kRankThreads), 0, stream, N, w.slot,
+                           w.tfirst, w.block_total, w.tgroup, rep, n_unique);
+    } else {
+        hipLaunchKernelGGL(dedup_scan_kernel, dim3(1), dim3(kRankThreads), 0, stream, blocks, w.block_total,
+                           n_unique);
+        hipLaunchKernelGGL(dedup_number_kernel<true>, dim3(blocks), dim3(kRankThreads), 0, stream, N, w.slot,
+                           w.tfirst, w.block_total, w.tgroup, rep, n_unique);
+    }
     hipLaunchKernelGGL(dedup_inverse_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, N, w.slot,
                        w.tgroup, inverse);
     return hipGetLastError();

@@ -336,7 +336,8 @@ def test_config4_full_size_trace():
 # ------------------------------------------------------------------------ grouping of equal ids
 @pytest.mark.parametrize("N,distinct", [(0, 1), (1, 1), (2, 1), (63, 7), (1024, 1024), (4096, 1229), (4096, 1),
                                         (4097, 1300), (6000, 2500), (7168, 7168), (7168, 1), (7169, 3000),   # up to 7168: one workgroup
-                                        (100000, 30000), (100000, 100000), (50000, 3)])
+                                        (100000, 30000), (100000, 100000), (50000, 3),
+                                        (1100000, 300000)])                                                # more than 1024 counting workgroups
 def test_dedup_bit_exact(N, distinct):
     rng = np.random.default_rng(N * 7 + distinct)
     pool = rng.integers(0, 2 ** 64, size=distinct, dtype=np.uint64)
