@@ -223,3 +223,35 @@ def test_pack_ids_bit_exact():
         rn.rnnlm_pack_ids(torch.from_numpy(ctx.view(np.int32)).to(DEV), torch.from_numpy(small.view(np.int32)).to(DEV), ids)
         torch.cuda.synchronize()
         assert np.array_equal(ids.cpu().numpy().view(np.uint64), oracle.pack_ids(ctx, small))
+
+
+@pytest.mark.parametrize("seed", [201, 202, 203])
+def test_random_traces_through_the_cache(seed):
+    """Seeded random traces: sizes on both sides of the one-workgroup limits of grouping and lookup
+    (4096 and 7168 raw queries), caches that never fill, fill up, or hold nothing."""
+    rng = np.random.default_rng(seed)
+    for case in range(8):
+        dtype = str(rng.choice(["bf16", "f32"]))
+        H = int(rng.choice([64, 96, 160, 256, 512, 640, 1024]))
+        if dtype == "f32":
+            H = min(H, 512)
+        V, K = int(rng.choice([500, 2049, 4099, 8200])), int(rng.choice([1, 4, 9]))
+        max_n = int(rng.choice([300, 1100, 4096, 4500, 7168, 7300]))
+        n_pool, capacity = int(rng.choice([5, 50, 400, 3000])), int(rng.choice([0, 37, 1000, 100000]))
+        model = small_model(rng, V, H, dtype, 0.05)
+        m = load_model(model, dtype, max_n)
+        cache = rn.rnnlm_cache_create(m, capacity)
+        ocache = oracle.Cache(H, capacity)
+        pool = rng.integers(0, 2 ** 64, n_pool, dtype=np.uint64)
+        st = CachedStepper(m, cache, max_n, K)
+        what = "seed %d case %d: %s V=%d H=%d K=%d max N=%d pool=%d capacity=%d" % (seed, case, dtype, V, H, K, max_n, n_pool, capacity)
+        for step in range(4):
+            N = int(rng.choice([1, max_n // 3 + 1, max_n]))
+            ids, prev, h_in, query, base = draw_step(rng, V, H, N, K, pool)
+            use_base = base if step % 2 else None
+            out = st.step(ids, prev, h_in, query, use_base)
+            ref = oracle.step_cached(model, ocache, ids, prev, h_in, query, base_score=use_base)
+            compare(out, ref, dtype, "%s step %d N=%d" % (what, step, N))
+        assert cache.stats() == ocache.stats() and m.last_error() == 0, what
+        cache.close()
+        m.close()
