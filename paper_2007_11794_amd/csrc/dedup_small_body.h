@@ -115,7 +115,7 @@ __device__ __forceinline__ SmallGroups dedup_small_body(const uint64_t *__restri
 // comparison), so the key a slot stands for never changes, and after all insertions the slot holds
 // the first raw index of its group.  No key value is special here.
 // (7 ids per thread; with 8192 ids, half of the slots taken, the probe chains make the one workgroup
-// slower than the six launches of the grid-wide form: 16 to 30 us against 21 to 23, measured)
+// slower than the launches of the grid-wide form: 16 to 30 us against 18 to 20, measured)
 constexpr int kMediumN = 7168;
 constexpr int kMediumCap = 16384;
 
