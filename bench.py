@@ -242,6 +242,10 @@ def main() -> int:
     if args.index_table:
         return bench_index_table(args, cfg, rn, torch, np)
     if args.hs:
+        if cfg.unique_frac is not None:
+            print("bench.py: --hs times one row per raw query (workloads 1, 2, 3, 5); the decode-trace "
+                  "workload repeats histories and is timed with the full softmax only", file=sys.stderr)
+            return 2
         return bench_hs(args, cfg, rn, torch, np)
     bf16 = cfg.dtype == "bf16"
     model = make_model(cfg)
