@@ -201,6 +201,9 @@ def main() -> int:
                          "roofline is the MFMA one (rnnlm_probe_mfma_rate: what the device sustains on the "
                          "output projection's loop shape, reported beside the data-sheet peak); "
                          "--no-cpu-baseline skips it too (runs under a profiler)")
+    ap.add_argument("--graph-steps", type=int, default=0, metavar="G",
+                    help="also record G steps into one HIP graph and time its replays (reported under "
+                         "\"graph\"; the headline value stays the eager one)")
     ap.add_argument("--hs", action="store_true",
                     help="the chosen workload with the hierarchical output layer (Huffman tree over the "
                          "Zipf word frequencies) in place of the full softmax")
@@ -340,6 +343,30 @@ def main() -> int:
                           note="value = raw queries / s over the trace through the cache; hit_ratio over "
                                "distinct histories per step; uncached_value = same trace without the cache")
 
+    graph_info = None
+    if args.graph_steps > 0 and cache_info is None:
+        # the same steps recorded once and replayed: what a serving loop that batches several steps
+        # (of different utterances) into one graph launch sees
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(args.graph_steps):
+                step()
+        torch.cuda.synchronize()
+        replays = max(1, args.steps // args.graph_steps)
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            g.replay()
+        torch.cuda.synchronize()
+        g_dt = time.perf_counter() - t0
+        graph_info = {"steps_per_graph": args.graph_steps, "replays": replays,
+                      "ms_per_step": round(g_dt / (replays * args.graph_steps) * 1e3, 4),
+                      "value": round(N * replays * args.graph_steps / g_dt, 1)}
+
     # dominant kernel: output projection + log-sum-exp, timed alone with HIP events on its stream
     reps = 50 if args.config == 3 else 10
     k3_ms = m.time_outproj(B, reps)
@@ -463,6 +490,8 @@ def main() -> int:
         out["cache"] = cache_info
     if gemm_ref is not None:
         out["gemm_reference"] = gemm_ref
+    if graph_info is not None:
+        out["graph"] = graph_info
     print(json.dumps(out))
     m.close()
     return 0
