@@ -486,6 +486,10 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if B != N and cache_info is None:
+        # raw queries are the hypothesis-steps (grouping is the method's gain); the rate over the
+        # distinct histories that were actually computed, for comparison with the other workloads
+        out["distinct_rows_per_s"] = round(B * args.steps / dt, 1)
     if cache_info is not None:
         out["cache"] = cache_info
     if gemm_ref is not None:
