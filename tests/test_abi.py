@@ -117,3 +117,13 @@ def test_host_checked_errors_of_the_cache_index_and_tree_entry_points():
     assert L.rnnlm_hs_step(None, 1, 1, p, p, p, None, 1, None, p, p, None) == EINVAL
     assert L.rnnlm_step_cached(None, None, 1, 1, p, p, p, p, None, p, p, p, p, p, None, p, 64, None) == EINVAL
     assert out.value is None
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N > 1 says so and exits before it touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
