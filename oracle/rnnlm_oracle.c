@@ -412,23 +412,55 @@ int oracle_index_fetch(const oracle_index *t, int N, const uint32_t *index, int3
  * + for a step to the child with code bit 0, - for code bit 1, so that the two children of a
  * node share its probability mass and the leaves sum to one.
  *
- * Huffman's method as two queues: the leaves sorted by (frequency, word id) ascending, and the
- * inner nodes in order of creation (their weights never decrease).  Each merge takes the two
- * lightest heads; on equal weight a leaf goes before an inner node.  The first taken becomes
- * the child with code bit 0.  Inner nodes are numbered 0 .. V-2 in order of creation (the root
- * is V-2).  Output per word: its path from the root down as entries node | code << 31.
+ * Huffman's method by its definition: keep the set of live subtrees; while more than one is left,
+ * take out the two of least weight and put back a new inner node that has them as children and
+ * the sum of their weights as weight.  The set is a binary heap ordered by (weight, node number),
+ * where words are nodes 0 .. V-1 and the n-th inner node created is node V + n: among equal
+ * weights the lower number is taken first, i.e. a word before an inner node, words in order of
+ * their id, inner nodes in order of creation.  (Any tie rule gives an optimal code; this one is
+ * fixed so that exactly one tree is right.)  The first of the two taken becomes the child with
+ * code bit 0.  Codes are then read off by walking down from the root (node 2V-2).
+ * Output per word: its path from the root down as entries inner-node index (0 .. V-2, the root
+ * is V-2) | code bit << 31.
  * Returns the number of entries, or -1 (V < 2, a negative frequency, out of memory), or
  * -(needed) - 1 when `capacity` is too small.
  */
-typedef struct { double f; int32_t id; } hs_leaf;
+typedef struct { double w; int32_t node; } hs_item;
 
-static int hs_leaf_cmp(const void *a, const void *b)
+static int hs_before(hs_item a, hs_item b)
 {
-    const hs_leaf *x = (const hs_leaf *)a, *y = (const hs_leaf *)b;
-    if (x->f < y->f) return -1;
-    if (x->f > y->f) return 1;
-    return (x->id > y->id) - (x->id < y->id);
+    return a.w < b.w || (a.w == b.w && a.node < b.node);
 }
+
+static void hs_push(hs_item *heap, int *n, hs_item x)
+{
+    int i = (*n)++;
+    while (i > 0 && hs_before(x, heap[(i - 1) / 2])) {
+        heap[i] = heap[(i - 1) / 2];
+        i = (i - 1) / 2;
+    }
+    heap[i] = x;
+}
+
+static hs_item hs_pop(hs_item *heap, int *n)
+{
+    hs_item top = heap[0], last = heap[--(*n)];
+    int i = 0;
+    for (;;) {
+        int c = 2 * i + 1;
+        if (c >= *n) break;
+        if (c + 1 < *n && hs_before(heap[c + 1], heap[c])) ++c;
+        if (!hs_before(heap[c], last)) break;
+        heap[i] = heap[c];
+        i = c;
+    }
+    if (*n > 0) heap[i] = last;
+    return top;
+}
+
+/* A node waiting to be visited on the walk down: how deep it is and the entry (parent's inner
+ * index | code bit << 31) that leads to it. */
+typedef struct { int32_t node, depth; uint32_t via; } hs_visit;
 
 long long oracle_huffman_build(int V, const double *freq, int32_t *path_off, int32_t *path_entry,
                                long long capacity)
@@ -436,46 +468,56 @@ long long oracle_huffman_build(int V, const double *freq, int32_t *path_off, int
     if (V < 2) return -1;
     for (int v = 0; v < V; ++v)
         if (!(freq[v] >= 0.0)) return -1;
-    hs_leaf *leaves = (hs_leaf *)malloc((size_t)V * sizeof(hs_leaf));
-    double *iw = (double *)malloc((size_t)(V - 1) * sizeof(double));       /* inner node weights */
-    int32_t *parent = (int32_t *)malloc((size_t)(2 * V - 1) * sizeof(int32_t));  /* leaves 0..V-1, inner V+i */
-    unsigned char *bit = (unsigned char *)malloc((size_t)(2 * V - 1));
-    if (!leaves || !iw || !parent || !bit) { free(leaves); free(iw); free(parent); free(bit); return -1; }
-    for (int v = 0; v < V; ++v) { leaves[v].f = freq[v]; leaves[v].id = v; }
-    qsort(leaves, (size_t)V, sizeof(hs_leaf), hs_leaf_cmp);
-    int li = 0, ii = 0;                       /* heads of the two queues */
-    for (int n = 0; n < V - 1; ++n) {         /* create inner node n */
-        double w = 0.0;
-        for (int c = 0; c < 2; ++c) {
-            int take_leaf;
-            if (li >= V) take_leaf = 0;
-            else if (ii >= n) take_leaf = 1;
-            else take_leaf = leaves[li].f <= iw[ii];
-            int child;
-            if (take_leaf) { child = leaves[li].id; w += leaves[li].f; ++li; }
-            else { child = V + ii; w += iw[ii]; ++ii; }
-            parent[child] = V + n;
-            bit[child] = (unsigned char)c;
-        }
-        iw[n] = w;
+    hs_item *heap = (hs_item *)malloc((size_t)V * sizeof(hs_item));
+    int32_t *child = (int32_t *)malloc((size_t)(V - 1) * 2 * sizeof(int32_t));   /* child[2n + bit] of inner node n */
+    hs_visit *todo = (hs_visit *)malloc((size_t)(V + 1) * sizeof(hs_visit));
+    uint32_t *trail = (uint32_t *)malloc((size_t)V * sizeof(uint32_t));          /* entries from the root to here */
+    if (!heap || !child || !todo || !trail) {
+        free(heap); free(child); free(todo); free(trail);
+        return -1;
     }
-    parent[V + V - 2] = -1;
-    long long total = 0;
+    int live = 0;
     for (int v = 0; v < V; ++v) {
-        int len = 0;
-        for (int x = v; parent[x] >= 0; x = parent[x]) ++len;
-        path_off[v] = (int32_t)total;
-        if (total + len <= capacity) {
-            int at = len;
-            for (int x = v; parent[x] >= 0; x = parent[x]) {
-                --at;
-                path_entry[total + at] = (int32_t)((uint32_t)(parent[x] - V) | ((uint32_t)bit[x] << 31));
+        hs_item x = { freq[v], v };
+        hs_push(heap, &live, x);
+    }
+    for (int n = 0; live > 1; ++n) {
+        hs_item a = hs_pop(heap, &live), b = hs_pop(heap, &live);
+        child[2 * n + 0] = a.node;
+        child[2 * n + 1] = b.node;
+        hs_item merged = { a.w + b.w, V + n };
+        hs_push(heap, &live, merged);
+    }
+    /* Two walks down from the root, depth first: the first measures the code lengths (a word's
+     * offset needs the lengths of all words with smaller ids), the second writes the entries. */
+    long long total = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        int top = 0;
+        todo[top].node = 2 * V - 2; todo[top].depth = 0; todo[top].via = 0; ++top;
+        while (top > 0) {
+            const hs_visit at = todo[--top];
+            if (at.depth > 0) trail[at.depth - 1] = at.via;
+            if (at.node < V) {                                 /* a word: trail[0 .. depth) is its path */
+                if (pass == 0) path_off[at.node + 1] = at.depth;
+                else if (total <= capacity)
+                    for (int e = 0; e < at.depth; ++e) path_entry[path_off[at.node] + e] = (int32_t)trail[e];
+                continue;
+            }
+            const int n = at.node - V;
+            for (int bit = 1; bit >= 0; --bit) {               /* bit 0 is visited first */
+                todo[top].node = child[2 * n + bit];
+                todo[top].depth = at.depth + 1;
+                todo[top].via = (uint32_t)n | ((uint32_t)bit << 31);
+                ++top;
             }
         }
-        total += len;
+        if (pass == 0) {
+            path_off[0] = 0;
+            for (int v = 0; v < V; ++v) path_off[v + 1] += path_off[v];
+            total = path_off[V];
+        }
     }
-    path_off[V] = (int32_t)total;
-    free(leaves); free(iw); free(parent); free(bit);
+    free(heap); free(child); free(todo); free(trail);
     return total <= capacity ? total : -total - 1;
 }
 

@@ -1,6 +1,10 @@
-"""The library's host-side Huffman builder against the oracle's (no GPU needed): the
-construction rule is fixed (two queues, ties: word before inner node, lower id first), so the
-trees must be identical, entry for entry."""
+"""The library's host-side Huffman builder (no GPU needed).  The oracle builds the tree by the
+definition (a priority queue over the live nodes, codes read off from the root down), the
+library by two queues and parent links; the tie rule is fixed (of equal weights the word goes
+before the inner node, words by id, inner nodes by age), so exactly one tree is right and the two
+must agree entry for entry.  Pinned besides against the hand-worked trees of
+tests/golden/huffman_ties.txt and against what holds for any tie rule: prefix-free codes over a
+full binary tree, Kraft sum exactly 1, optimal cost."""
 import ctypes
 
 import numpy as np
@@ -26,6 +30,19 @@ def test_same_tree_as_the_oracle(V, kind):
     off_l, ent_l = rn.rnnlm_huffman_build(f)
     off_o, ent_o = oracle.huffman_build(f)
     assert np.array_equal(off_l, off_o) and np.array_equal(ent_l, ent_o)
+    # whatever the tie rule: optimal cost (sum of merged weights, Python's heapq) and a full tree
+    from test_oracle_hs_pins import check_tree, heap_cost, lengths
+    assert float(np.dot(f, lengths(off_l))) == pytest.approx(heap_cost(f), rel=1e-12)
+    if V <= 4096:
+        check_tree(V, off_l, ent_l)
+
+
+@pytest.mark.parametrize("case", ["T1", "T2", "T3", "T4", "T5"])
+def test_hand_worked_trees(case):
+    from test_oracle_hs_pins import golden_trees, paths_of
+    freq, paths = golden_trees()[case]
+    off, entry = rn.rnnlm_huffman_build(np.array(freq))
+    assert paths_of(off, entry) == paths
 
 
 def test_errors_and_size_query():

@@ -1,9 +1,12 @@
 """Pins for the oracle's hierarchical output layer (Section 2.1): Huffman tree and path
-probabilities.  Expected values: the textbook example of Huffman's method, the cost of an
-independent heap-based construction (heapq), exact Kraft sums, the closed form for zero node
-vectors, a pure-Python evaluation of the definition, and the sum over all leaves."""
+probabilities.  Expected values: hand-worked trees with and without ties
+(tests/golden/huffman_ties.txt), a pure-Python restatement of the definition that finds the two
+lightest live nodes by scanning, the cost of a construction on Python's heapq, exact Kraft
+sums, the closed form for zero node vectors, a pure-Python evaluation of the path
+probabilities, and the sum over all leaves."""
 import heapq
 import math
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -52,6 +55,74 @@ def check_tree(V, off, entry):
     assert len(nxt) + len(leaf) == 2 * (V - 1)
     for n in range(V - 1):
         assert ((n, 0) in nxt or (n, 0) in leaf) and ((n, 1) in nxt or (n, 1) in leaf)
+
+
+def golden_trees():
+    """{case: (freq, [path of word 0, ...])}, a path being a list of node | bit << 31 entries."""
+    raw = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "huffman_ties.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                key, *vals = line.split()
+                raw[key] = vals
+    cases = {}
+    for key, vals in raw.items():
+        case, what = key.split("_")
+        if what == "freq":
+            freq = [float(v) for v in vals]
+            paths = []
+            for w in range(len(freq)):
+                steps = [s.split(".") for s in raw["%s_w%d" % (case, w)]]
+                paths.append([int(n) | (int(b) << 31) for n, b in steps])
+            cases[case] = (freq, paths)
+    return cases
+
+
+def paths_of(off, entry):
+    return [[int(e) & 0xFFFFFFFF for e in entry[off[v]:off[v + 1]]] for v in range(len(off) - 1)]
+
+
+def scan_huffman(freq):
+    """The definition, by scanning: nodes 0 .. V-1 are the words, node V + n the n-th inner node
+    made; take the two live nodes of least (weight, node number), the first gets code bit 0."""
+    V = len(freq)
+    weight = {v: float(freq[v]) for v in range(V)}
+    parent = {}
+    for n in range(V - 1):
+        a = min(weight, key=lambda x: (weight[x], x))
+        wa = weight.pop(a)
+        b = min(weight, key=lambda x: (weight[x], x))
+        wb = weight.pop(b)
+        parent[a], parent[b] = (n, 0), (n, 1)
+        weight[V + n] = wa + wb
+    paths = []
+    for v in range(V):
+        p, x = [], v
+        while x in parent:
+            n, bit = parent[x]
+            p.append(n | (bit << 31))
+            x = V + n
+        paths.append(p[::-1])
+    return paths
+
+
+@pytest.mark.parametrize("case", ["T1", "T2", "T3", "T4", "T5"])
+def test_hand_worked_trees(case):
+    freq, paths = golden_trees()[case]
+    off, entry = oracle.huffman_build(freq)
+    assert paths_of(off, entry) == paths
+    assert scan_huffman(freq) == paths            # the restatement used below reads the same rule
+
+
+@pytest.mark.parametrize("V,levels", [(2, 1), (3, 1), (9, 2), (40, 3), (200, 4), (500, 1000)])
+def test_same_tree_as_the_scan_on_many_ties(V, levels):
+    rng = np.random.default_rng(V * 31 + levels)
+    for _ in range(4):
+        freq = rng.integers(1, levels + 1, V).astype(np.float64)
+        off, entry = oracle.huffman_build(freq)
+        assert paths_of(off, entry) == scan_huffman(freq)
+        check_tree(V, off, entry)
 
 
 def test_textbook_example():
