@@ -116,19 +116,31 @@ __device__ __forceinline__ void lse2_fold16(const float (&x)[16], float &mrun, f
 // inline assembly on purpose: when the compiler knows of a pending LDS-DMA it makes every
 // later LDS read wait for ALL outstanding LDS reads (lgkmcnt(0)) instead of just its own,
 // which stalls the MFMA pipeline; completion is awaited explicitly with vmcnt before the
-// workgroup barrier that publishes the data.
+// workgroup barrier that publishes the data.  M0 is an input operand, so the compiler writes it
+// and knows that it is in use; the s_nop is the wait state between that write and the load.
 __device__ __forceinline__ void lds_dma_16(const void *sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_base), "v"(voff), "s"(sbase)
+                 : "{m0}"(lds_base), "v"(voff), "s"(sbase)
                  : "memory");
 }
 
 // The same with a full 64-bit address per lane (rows gathered from anywhere in a buffer).
 __device__ __forceinline__ void lds_dma_16_ptr(const void *lane_ptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+    asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                  :
-                 : "s"(lds_base), "v"(lane_ptr)
+                 : "{m0}"(lds_base), "v"(lane_ptr)
+                 : "memory");
+}
+
+// The same as lds_dma_16 by lane 0 alone (16 bytes to lds_base), without a branch around it: the
+// execution mask is narrowed to lane 0 for the one instruction and put back.  Counts as one
+// vector-memory operation of the wave like any other load.
+__device__ __forceinline__ void lds_dma_16_lane0(const void *sbase, uint32_t voff, uint32_t lds_base) {
+    uint64_t saved_exec;
+    asm volatile("s_mov_b64 %0, exec\n\ts_mov_b64 exec, 1\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+                 : "=&s"(saved_exec)
+                 : "{m0}"(lds_base), "v"(voff), "s"(sbase)
                  : "memory");
 }
 

@@ -18,10 +18,17 @@
 //     of ONE row and the sum over words stays inside the lane;
 //   - the exp-and-add of block i is interleaved, instruction by instruction, with the MFMAs
 //     of block i+1, so the vector ALU works in the shadow of the matrix core (the unrolled
-//     block body is kept free of branches for that: see staged_block);
+//     block body is kept free of branches for that: see staged_block_fixed / staged_block);
 //   - one workgroup barrier per block.  It publishes the landing of block i+1 while block i
 //     is being computed, so no wave ever waits at a barrier for data it is about to use, and
 //     the first operands of block i+1 are already in registers when block i ends.
+// With the fixed log-sum-exp offset (the usual case) nothing at all happens at the boundary
+// between two blocks: the barrier sits in the MIDDLE of a block's MFMA chain (a wave that waits
+// there has its last MFMA in the pipe, and the chain goes on without any hand-over), the loads of
+// block i+3 are issued one by one between the MFMAs of the block's second half instead of in a
+// burst behind the barrier, two accumulator sets alternate (no copy between blocks, the next chain
+// does not wait for the last MFMA of this one), and the constants a chain starts from are read
+// from LDS into the resting accumulator set half a block before they are needed.
 // LDS rows are XOR-swizzled in 16-byte chunks (chunk c of word r sits at c ^ (r & 15)) so
 // that the 16 lanes served together by one ds_read_b128 hit 16 different bank groups.  The
 // direct loads write LDS linearly (lane i -> base + 16 i), so the swizzle is applied on the
@@ -91,6 +98,25 @@ struct Loader {
             lds_dma_16(blk, voff[q], stage_lds + (q * kThreads + wave * 64) * 16);
         // the 32 constants of the block: 16 bytes per wave, by its lane 0
         if (lane == 0) lds_dma_16(cvec + v0, wave * 16, cslot_lds + wave * 16);
+    }
+    // The same in pieces and without branches (the fixed-offset block body is one basic block):
+    // weight load q of the block, and its constants.  real = false turns the load into a dummy
+    // that counts like a real one for vmcnt but fetches the first bytes of the weights (always
+    // there, one cache line for the whole wave) into the same, free, LDS stage.
+    __device__ __forceinline__ void issue_weights(const bf16_t *blk, int q, bool real, uint32_t stage_lds) const {
+        lds_dma_16(blk, real ? voff[q] : 0u, stage_lds + (q * kThreads + wave * 64) * 16);
+    }
+    __device__ __forceinline__ void issue_consts(const float *cblk, uint32_t cslot_lds) const {
+        lds_dma_16_lane0(cblk, wave * 16, cslot_lds + wave * 16);
+    }
+    __device__ __forceinline__ void issue_all(const bf16_t *Ot, const float *cvec, int v0, bool real,
+                                              uint32_t stage_lds, uint32_t cslot_lds) const {
+        using C = StagedCfg<HP>;
+        const int v = real ? v0 : 0;
+        const bf16_t *blk = Ot + (size_t)v * HP;
+#pragma unroll
+        for (int q = 0; q < C::kLoadsPerThread; ++q) issue_weights(blk, q, real, stage_lds);
+        issue_consts(cvec + v, cslot_lds);
     }
 };
 
@@ -162,6 +188,178 @@ __device__ __forceinline__ void staged_block(const char *stage, const char *next
     pacc = acc;
 }
 
+// One MFMA B operand (this lane's 16 bytes of a 1 KB fragment) requested WITHOUT the compiler
+// knowing that a load is in flight: the register is defined for it at once, and the caller keeps
+// it unread until await_d_operand has waited for the data.  (A load the compiler can see makes
+// it guard the operand with vmcnt waits of its own inside the block loop, and those drain the
+// direct-to-LDS loads, which it cannot see.)
+template <int OFFSET>
+__device__ __forceinline__ void load_d_operand(bf16x8 &dst, const bf16_t *lane_ptr) {
+    static_assert(OFFSET >= 0 && OFFSET < 4096, "immediate offset of a global load");
+    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(lane_ptr), "n"(OFFSET) : "memory");
+}
+// Wait until at most `younger` of this wave's vector-memory operations are outstanding; the
+// operand goes in and out so that its first use cannot move in front of the wait.
+__device__ __forceinline__ void await_d_operand(bf16x8 &op, int younger) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(op) : "n"(younger));
+}
+
+// Fixed offset: one 32-word block for this wave's 32 rows, as ONE basic block.
+//   acc     on entry the block's constants (the base-2 logits start from them), on return the
+//           finished logits of the block
+//   other   on entry the finished logits of the previous block (-inf before the first): their
+//           exp-and-add is spread over the first half of the k-steps; on return the constants of
+//           block bi+1 (read from the ring in the second half; after the last block: a landed
+//           slot, unused)
+// Half way through, the barrier publishes block bi+1 (everybody's loads of it have landed: the
+// only younger loads of a wave are those of block bi+2) and frees the stage of block bi-1, which
+// takes block bi+3 (past the end of the split: dummy loads, so that every wave always has the same
+// number of loads in flight and the vmcnt immediates hold).  On return a[] holds the first
+// kPrefetch A operands of block bi+1.
+//
+// FIRST (block 0 of an item): the rows of d were requested by load_d_operand just before and are
+// still arriving; every MFMA waits for ITS operand only (await_d_operand with the number of
+// younger loads of this wave: the rest of d, block 2, and what this block has issued of block 3),
+// so the chain starts when the first kilobytes are there, not the last.  No wait is needed at its
+// barrier: block 1 was requested before d, so it has landed when the first operand has.
+template <int HP, bool FIRST>
+__device__ __forceinline__ void staged_block_fixed(const char *lds, const char *cring, uint32_t lds0,
+                                                   uint32_t cring0, const Loader<HP> &loader, const bf16_t *Ot,
+                                                   const float *cvec, int blk0, int nblk, int bi,
+                                                   const int (&aoff)[8], bf16x8 (&a)[kPrefetch],
+                                                   bf16x8 (&dreg)[HP / 16], int g, f32x16 &acc,
+                                                   f32x16 &other, float &srun) {
+    using C = StagedCfg<HP>;
+    constexpr int KS = C::KS, HALF = KS / 2, NW = C::kLoadsPerThread;
+    constexpr int kLoadStep = (HALF - 2) / NW;                 // k-steps between two weight loads
+    static_assert(KS >= 2 * kPrefetch && kLoadStep >= 1 && HALF + 1 + (NW - 1) * kLoadStep < KS - 2, "");
+    const char *stage = lds + (bi & 3) * C::kStageBytes;
+    const char *next_stage = lds + (((bi + 1 < nblk) ? bi + 1 : bi) & 3) * C::kStageBytes;
+    const f32x4 *cnext = reinterpret_cast<const f32x4 *>(cring + ((bi + 1) & 7) * kCSlotBytes);
+    const bool real = bi + 3 < nblk;
+    const int v3 = real ? (blk0 + bi + 3) * kStagedWords : 0;
+    const bf16_t *blk3 = Ot + (size_t)v3 * HP;
+    const uint32_t stage3 = lds0 + ((bi + 3) & 3) * C::kStageBytes, cslot3 = cring0 + ((bi + 3) & 7) * kCSlotBytes;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        if (ks == HALF) {
+            if (!FIRST) wait_vmcnt<C::kLoadsPerBlock>();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        const bf16x8 cur = a[ks % kPrefetch];
+        if (ks + kPrefetch < KS) a[ks % kPrefetch] = RNNLM_A_FRAG(stage, ks + kPrefetch);
+        else a[ks % kPrefetch] = RNNLM_A_FRAG(next_stage, ks + kPrefetch - KS);
+        if (FIRST) {
+            // loads of this wave younger than d[ks]: the later operands, block 2, and the loads of
+            // block 3 that the k-steps before this one have issued
+            int younger = (KS - 1 - ks) + C::kLoadsPerBlock;
+#pragma unroll
+            for (int q = 0; q < NW; ++q)
+                if (HALF + 1 + q * kLoadStep < ks) ++younger;
+            if (KS - 2 < ks) ++younger;
+            await_d_operand(dreg[ks], younger);
+        }
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[ks], acc, 0, 0, 0);
+        // the previous block's sixteen logits, over k-steps 1 .. HALF
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (1 + (e * HALF) / 16 == ks) srun += fast_exp2(other[e]);
+        // second half: loads of block bi+3, constants of block bi+1 into the resting accumulators
+#pragma unroll
+        for (int q = 0; q < NW; ++q)
+            if (ks == HALF + 1 + q * kLoadStep) loader.issue_weights(blk3, q, real, stage3);
+        if (ks == KS - 2) loader.issue_consts(cvec + v3, cslot3);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (ks == HALF + 1 + (q * (HALF - 1)) / 4) {
+                const f32x4 c = cnext[2 * q + g];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) other[4 * q + i] = c[i];
+            }
+        // keep this order: the compiler's scheduler would otherwise sink every LDS read to
+        // just before its MFMA and expose the LDS latency on each step
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Fixed offset: all blocks of one (row group, split) item for this wave's rows; returns the sum
+// of 2^(logit - offset) over the item's words for this lane's half of its row.
+template <int HP>
+__device__ __forceinline__ float staged_item_fixed(const ModelDev &m, char *lds, char *cring, const Loader<HP> &loader,
+                                                   const int (&aoff)[8], int rg, int blk0, int nblk, int wave,
+                                                   int lane, int g) {
+    using C = StagedCfg<HP>;
+    constexpr int KS = C::KS;
+    const bf16_t *Ot = static_cast<const bf16_t *>(m.Ot);
+    const float *cvec = m.cvec2_fixed;
+    const uint32_t lds0 = lds_address(lds), cring0 = lds_address(cring);
+    // Blocks 0 and 1, then this wave's rows of d (all k, as MFMA B operands; rows beyond B hold
+    // stale scratch: rows are independent and those lanes' results are dropped).
+    loader.issue_all(Ot, cvec, blk0 * kStagedWords, true, lds0, cring0);
+    loader.issue_all(Ot, cvec, (blk0 + 1) * kStagedWords, 1 < nblk, lds0 + C::kStageBytes, cring0 + kCSlotBytes);
+    bf16x8 dreg[KS];
+    {
+        // fragment (row block, ks) of the fragment-ordered copy: 64 lanes x 16 bytes in a row
+        const bf16_t *dfr = static_cast<const bf16_t *>(m.dfrag) +
+                            ((size_t)(rg * (kStagedRows / 32) + wave) * KS * 64 + lane) * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16_t *p4 = dfr + (size_t)(ks / 4) * 2048;          // a pointer every 4 KB, offsets in between
+            if (ks % 4 == 0) load_d_operand<0>(dreg[ks], p4);
+            else if (ks % 4 == 1) load_d_operand<1024>(dreg[ks], p4);
+            else if (ks % 4 == 2) load_d_operand<2048>(dreg[ks], p4);
+            else load_d_operand<3072>(dreg[ks], p4);
+        }
+    }
+    // Block 0 has landed once only the younger loads are outstanding: block 1 and d.
+    static_assert(C::kLoadsPerBlock + KS < 64, "the vmcnt immediates of the first block");
+    wait_vmcnt<C::kLoadsPerBlock + KS>();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();                             // block 0 is published
+    asm volatile("" ::: "memory");
+    // Block 2 has until the barrier in the middle of block 1 to land.  From there on every wave has,
+    // at the barrier in the middle of block bi, the loads of blocks bi+1 and bi+2 in flight at most.
+    loader.issue_all(Ot, cvec, (blk0 + 2) * kStagedWords, 2 < nblk, lds0 + 2 * C::kStageBytes, cring0 + 2 * kCSlotBytes);
+    bf16x8 a[kPrefetch];
+#pragma unroll
+    for (int i = 0; i < kPrefetch; ++i) a[i] = RNNLM_A_FRAG(lds, i);
+    f32x16 acc0, acc1;
+    {
+        const f32x4 *c0 = reinterpret_cast<const f32x4 *>(cring);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 c = c0[2 * q + g];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc0[4 * q + i] = c[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc1[i] = -INFINITY;        // "previous block" of block 0: adds 2^-inf = 0
+    float srun = 0.f;
+#define RNNLM_BLOCK(FIRST, BI, ACC, OTHER) \
+    staged_block_fixed<HP, FIRST>(lds, cring, lds0, cring0, loader, Ot, cvec, blk0, nblk, BI, aoff, a, dreg, g, ACC, OTHER, srun)
+    RNNLM_BLOCK(true, 0, acc0, acc1);
+    int bi = 1;
+    for (; bi + 1 < nblk; bi += 2) {
+        RNNLM_BLOCK(false, bi, acc1, acc0);
+        RNNLM_BLOCK(false, bi + 1, acc0, acc1);
+    }
+    if (bi < nblk) {
+        RNNLM_BLOCK(false, bi, acc1, acc0);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) srun += fast_exp2(acc1[e]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) srun += fast_exp2(acc0[e]);
+    }
+#undef RNNLM_BLOCK
+    // dummy loads may still be in flight into stages the next item fills first
+    wait_vmcnt<0>();
+    return srun;
+}
+
 template <int HP, bool FIXED>
 __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, int rows,
                                                                   const int *__restrict__ B_dev,
@@ -205,6 +403,14 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
         const int blk0 = (int)(((long long)split * T) / plan.S);
         const int nblk = (int)(((long long)(split + 1) * T) / plan.S) - blk0;
         const int b = rg * kStagedRows + wave * 32 + col;     // this lane's row
+        if (FIXED) {
+            float srun = 0.f;
+            if (nblk > 0) srun = staged_item_fixed<HP>(m, lds, cring, loader, aoff, rg, blk0, nblk, wave, lane, g);
+            srun += __shfl_xor(srun, 32, 64);                 // lanes l and l+32 hold the two halves of a row
+            if (g == 0 && b < B) m.part[(size_t)b * kMaxSplits + split] = make_float2(m.m2_fixed, srun);
+            __syncthreads();                                  // LDS is reused by the next item
+            continue;
+        }
 
         // Blocks 0 and 1 first, then this wave's rows of d (all k, as MFMA B operands; rows
         // beyond B hold stale scratch: rows are independent and those lanes' results are dropped).

@@ -107,9 +107,9 @@ def test_hs_bad_indices_and_wrong_entry_point():
     mod.close()
 
 
-def test_hs_headline_shape_sampled():
-    """V = 65536, H = 512, B = 1024, K = 32 (the headline workload's shape): all hidden rows and
-    the queries of 64 sampled rows against the oracle."""
+def test_hs_headline_shape_every_row():
+    """V = 65536, H = 512, B = 1024, K = 32 (the headline workload's shape): every hidden row and
+    every one of the 1024 x 32 log-probabilities against the oracle."""
     cfg = CONFIGS[3]
     rng = np.random.default_rng(cfg.seed)
     m = hs_model(rng, cfg.V, cfg.H, "bf16", cfg.sigma)
@@ -118,12 +118,38 @@ def test_hs_headline_shape_sampled():
     h_in = (1.0 / (1.0 + np.exp(-rng.normal(0, 1, (cfg.B, cfg.H))))).astype(np.float32)
     query = bounded_zipf_ids(rng, cfg.V, 1.1, (cfg.B, cfg.K)).astype(np.int32)
     h, lp = gpu_hs_step(mod, prev, h_in, query)
-    rows = np.sort(rng.choice(cfg.B, 64, replace=False))
-    ref = oracle.hs_step(m, prev[rows], h_in[rows], query[rows])
-    dh, dlp = np.max(np.abs(h[rows] - ref["h_out"])), np.max(np.abs(lp[rows] - ref["logprob"]))
+    ref = oracle.hs_step(m, prev, h_in, query)
+    dh, dlp = np.max(np.abs(h - ref["h_out"])), np.max(np.abs(lp - ref["logprob"]))
     print("hs headline shape: max|dh|=%.3g max|dlogprob|=%.3g mean path %.1f" %
           (dh, dlp, float(np.diff(m["path_off"])[query].mean())), flush=True)
     assert dh <= 1e-3 and dlp <= 2e-3 and np.all(np.isfinite(lp)) and np.all(lp < 0)
+    assert mod.last_error() == 0
+    mod.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_hs_million_words_few_rows(dtype):
+    """The regime the paper runs the tree in (Section 5.1): about a million words, a hidden layer of
+    100 units, and the few distinct histories a step of a well-cached search leaves.  V is odd on
+    purpose; rare words sit 25 to 30 nodes deep, frequent ones a handful."""
+    rng = np.random.default_rng(1234)
+    V, H, K = 1000003, 100, 32
+    m = hs_model(rng, V, H, dtype, 0.05)
+    depth = np.diff(m["path_off"])
+    assert depth.min() >= 1 and depth.max() >= 20
+    mod = load(m, dtype, 64)
+    for B in (1, 20, 64):
+        prev = bounded_zipf_ids(rng, V, 1.1, B).astype(np.int32)
+        h_in = rng.uniform(0, 1, (B, H)).astype(np.float32)
+        query = bounded_zipf_ids(rng, V, 1.1, (B, K)).astype(np.int32)
+        query[:, 0] = V - 1 - np.arange(B)                  # the rarest words: the longest paths
+        query[:, 1] = np.arange(B)                          # the most frequent ones
+        ref = oracle.hs_step(m, prev, h_in, query)
+        h, lp = gpu_hs_step(mod, prev, h_in, query)
+        dh, dlp = np.max(np.abs(h - ref["h_out"])), np.max(np.abs(lp - ref["logprob"]))
+        print("hs V=%d H=%d %s B=%d: max|dh|=%.3g max|dlogprob|=%.3g deepest queried path %d" %
+              (V, H, dtype, B, dh, dlp, int(depth[query].max())), flush=True)
+        assert dh <= TOL[dtype][1] and dlp <= TOL[dtype][0]
     assert mod.last_error() == 0
     mod.close()
 

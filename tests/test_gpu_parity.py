@@ -125,30 +125,25 @@ def test_f32_reduced_elementwise_both_lse_modes(V, H, B, K):
     m.close()
 
 
-# ------------------------------------------------------------------------ config 3: headline, full size, sampled rows
-def sampled_rows_check(cfg, model, x, h, lp, rows, what):
-    ref = oracle.step(model, x["prev"][rows], x["h_in"][rows], x["query"][rows])
-    return check(h[rows], lp[rows], ref, cfg.dtype, what)
-
-
-def test_config3_headline_full_size_sampled():
+# ------------------------------------------------------------------------ config 3: headline, full size, every row
+def test_config3_headline_full_size_every_row():
+    """All 1024 rows and all 1024 x 32 log-probabilities against the oracle, in the launch
+    configuration bench.py times (automatic kernel choice) and with the plain kernel."""
     cfg = CONFIGS[3]
     model = make_model(cfg)
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
     m = load_model(model, cfg.dtype, cfg.B)
-    rng = np.random.default_rng(7)
-    rows = np.sort(np.concatenate([[0, cfg.B - 1], rng.choice(np.arange(1, cfg.B - 1), 46, replace=False)]))
+    ref = oracle.step(model, x["prev"], x["h_in"], x["query"])
     outs = {}
-    for kernel in (0, 1):                 # the launch configuration bench.py times, and the plain kernel
+    for kernel in (0, 1):
         m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
         h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
-        sampled_rows_check(cfg, model, x, h, lp, rows, "cfg3 kernel=%d (48 sampled rows)" % kernel)
+        check(h, lp, ref, cfg.dtype, "cfg3 kernel=%d (all %d rows)" % (kernel, cfg.B))
         outs[kernel] = (h, lp)
-    # every row, not only the sampled ones: the two kernels agree with each other
+    # extra, not the check: the two kernels share the hidden update, and their sums differ by rounding only
     assert np.array_equal(outs[0][0], outs[1][0])
     assert np.max(np.abs(outs[0][1] - outs[1][1])) <= 1e-4
-    # properties that hold at any size: finite, log-probabilities negative
-    assert np.all(np.isfinite(outs[0][1])) and np.all(outs[0][1] < 0)
+    assert np.all(outs[0][1] < 0)
     assert m.last_error() == 0
     m.close()
 
@@ -251,19 +246,22 @@ def test_more_row_groups_than_workgroups(dtype, V, H, B, K):
     m.close()
 
 
-# ------------------------------------------------------------------------ config 5: stress, full size, sampled rows
-def test_config5_stress_full_size_sampled():
+# ------------------------------------------------------------------------ config 5: stress, full size, every row
+def test_config5_stress_full_size_every_row():
+    """All 2048 rows and all 2048 x 64 log-probabilities against the oracle (V = 200000 is not a
+    multiple of any tile: the ragged last tile is part of every row's sum)."""
     cfg = CONFIGS[5]
     model = make_model(cfg)
     x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
     m = load_model(model, cfg.dtype, cfg.B)
     h, lp = gpu_step(m, x["prev"], x["h_in"], x["query"])
-    rows = np.sort(np.concatenate([[0, cfg.B - 1], np.random.default_rng(9).choice(np.arange(1, cfg.B - 1), 14, replace=False)]))
-    sampled_rows_check(cfg, model, x, h, lp, rows, "cfg5 (16 sampled rows)")
-    assert np.all(np.isfinite(lp)) and np.all(lp < 0) and np.all(np.isfinite(h))
-    m.set_option(rn.OPT_OUTPROJ_KERNEL, 1)        # every row: the plain kernel agrees with the default one
+    ref = oracle.step(model, x["prev"], x["h_in"], x["query"])
+    check(h, lp, ref, cfg.dtype, "cfg5 (all %d rows)" % cfg.B)
+    assert np.all(lp < 0)
+    m.set_option(rn.OPT_OUTPROJ_KERNEL, 1)        # extra: the plain kernel, against the oracle as well
     h1, lp1 = gpu_step(m, x["prev"], x["h_in"], x["query"])
-    assert np.array_equal(h1, h) and np.max(np.abs(lp1 - lp)) <= 1e-4
+    check(h1, lp1, ref, cfg.dtype, "cfg5 plain kernel (all %d rows)" % cfg.B)
+    assert np.array_equal(h1, h)
     assert m.last_error() == 0
     m.close()
 
@@ -295,40 +293,41 @@ def test_config4_reduced_trace_elementwise():
 
 
 def test_config4_full_size_trace():
-    """N = 4096 raw queries, about 30 % distinct, 50 steps at V = 65536, H = 512.  Every step:
-    grouping bit-exact against the oracle; carried-over histories score bit-identically to
-    the step before.  Steps 0, 24, 49: sampled rows against the oracle."""
+    """N = 4096 raw queries, about 30 % distinct, 50 chained steps at V = 65536, H = 512; the GPU
+    feeds on its own h_out and the oracle on its own.  Every step: grouping bit-exact, every distinct
+    history's hidden vector and every raw query's log-probabilities against the oracle, and
+    carried-over histories score bit-identically to the step before."""
     cfg = CONFIGS[4]
     model = make_model(cfg)
     m = load_model(model, cfg.dtype, cfg.N)
-    tr = DecodeTrace(cfg)
-    x = tr.first()
+    tr_g, tr_o = DecodeTrace(cfg), DecodeTrace(cfg)
+    xg, xo = tr_g.first(), tr_o.first()
     prev_by_key = {}
-    rng = np.random.default_rng(11)
+    worst_h = worst_lp = 0.0
     for step in range(cfg.steps):
-        out = gpu_step_dedup(m, x["keys"], x["prev"], x["h_in"], x["query"])
-        U, rep, inv = oracle.dedup(x["keys"])
-        assert out["n_unique"] == U == tr.U0, step
+        assert np.array_equal(xg["keys"], xo["keys"]) and np.array_equal(xg["query"], xo["query"])
+        assert np.array_equal(xg["prev"], xo["prev"])
+        out = gpu_step_dedup(m, xg["keys"], xg["prev"], xg["h_in"], xg["query"])
+        U, rep, inv = oracle.dedup(xo["keys"])
+        assert out["n_unique"] == U == tr_o.U0, step
         assert np.array_equal(out["rep"], rep) and np.array_equal(out["inverse"], inv), step
-        assert np.all(np.isfinite(out["logprob"])) and np.all(out["logprob"] < 0), step
+        ref = oracle.step(model, xo["prev"][rep], xo["h_in"][rep], xo["query"], row_of_query=inv)
+        dh, dlp = check(out["h_out"], out["logprob"], ref, "bf16", "cfg4 step %d (all %d histories)" % (step, U))
+        worst_h, worst_lp = max(worst_h, dh), max(worst_lp, dlp)
+        assert np.all(out["logprob"] < 0), step
         # cache reuse: the same history id seen in the previous step gives the same h_out bits
-        keys_u = x["keys"][rep]
+        keys_u = xg["keys"][rep]
         hits = 0
         for u, k in enumerate(keys_u.tolist()):
             if k in prev_by_key:
                 assert np.array_equal(out["h_out"][u], prev_by_key[k]), (step, u)
                 hits += 1
         if step:
-            assert hits == int(x["carried"].sum()) > 0
+            assert hits == int(xg["carried"].sum()) > 0
         prev_by_key = {k: out["h_out"][u].copy() for u, k in enumerate(keys_u.tolist())}
-        if step in (0, 24, 49):
-            rows_u = np.sort(rng.choice(U, 12, replace=False))
-            raw = np.flatnonzero(np.isin(inv, rows_u))
-            remap = {int(u): i for i, u in enumerate(rows_u)}
-            roq = np.array([remap[int(inv[n])] for n in raw], np.int32)
-            ref = oracle.step(model, x["prev"][rep[rows_u]], x["h_in"][rep[rows_u]], x["query"][raw], row_of_query=roq)
-            check(out["h_out"][rows_u], out["logprob"][raw], ref, "bf16", "cfg4 step %d (12 sampled histories)" % step)
-        x = tr.next(x, out["h_out"], out["inverse"])
+        xg = tr_g.next(xg, out["h_out"], out["inverse"])
+        xo = tr_o.next(xo, ref["h_out"], inv)
+    print("cfg4 trace: worst max|dh|=%.3g max|dlogprob|=%.3g over %d steps" % (worst_h, worst_lp, cfg.steps), flush=True)
     assert m.last_error() == 0
     m.close()
 
