@@ -47,7 +47,7 @@ enum rnnlm_status {
     RNNLM_EINVAL = -1,        /* NULL pointer, bad size, unknown dtype or option */
     RNNLM_ENOMEM = -2,        /* device or host allocation failed */
     RNNLM_EDEVICE = -3,       /* a HIP call failed */
-    RNNLM_ERANGE = -4,        /* B or N beyond what the model was loaded for */
+    RNNLM_ERANGE = -4,        /* B or N beyond what the model was loaded for, or beyond a stated maximum */
     RNNLM_EWORKSPACE = -5     /* workspace too small or misaligned */
 };
 
@@ -130,6 +130,20 @@ size_t rnnlm_dedup_workspace_bytes(int N);
  */
 int rnnlm_dedup(const uint64_t *history_ids, int N, int32_t *rep, int32_t *inverse,
                 int32_t *n_unique, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * rnnlm_dedup for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results
+ * as rnnlm_dedup without `workspace`; the table lives in a fixed device array inside the library
+ * (2.3 MB per GPU, held until the process ends), so N may not exceed RNNLM_DEDUP_STATIC_MAX_N
+ * (RNNLM_ERANGE otherwise).  Calls no hipMalloc / hipFree, asynchronous on `hip_stream`.  All calls
+ * on one GPU share the one array: calls that overlap in time on the same GPU (two streams, two
+ * threads) race; order them.  The array's address is looked up on the first call on a device (or by
+ * rnnlm_load / rnnlm_hs_load before that).
+ */
+#define RNNLM_DEDUP_STATIC_MAX_N 65536
+int rnnlm_dedup_static(const uint64_t *history_ids, int N, int32_t *rep, int32_t *inverse,
+                       int32_t *n_unique, void *hip_stream);
 
 /*
  * Score one step for B distinct histories and N raw queries (ComputeRnnlm of Table 1,

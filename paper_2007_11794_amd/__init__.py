@@ -3,7 +3,7 @@ projection + log-sum-exp -> query gather) behind a C ABI; this package is the th
 binding over librnnlm.so.  PyTorch is used only for device memory and streams."""
 from .binding import (RNNLM_BF16, RNNLM_F32, FLAG_BAD_PREV_WORD, FLAG_BAD_QUERY_WORD, FLAG_BAD_ROW,
                       OPT_LSE_MODE, OPT_OUTPROJ_KERNEL, RnnlmError, RnnlmModel, lib, lib_path,
-                      rnnlm_dedup, rnnlm_dedup_workspace_bytes, rnnlm_load, rnnlm_step,
+                      rnnlm_dedup, rnnlm_dedup_static, DEDUP_STATIC_MAX_N, rnnlm_dedup_workspace_bytes, rnnlm_load, rnnlm_step,
                       rnnlm_step_dedup, rnnlm_strerror, RnnlmCache, rnnlm_cache_create,
                       rnnlm_step_cached, rnnlm_pack_ids, RnnlmIndexTable, rnnlm_index_create,
                       rnnlm_index_intern, rnnlm_index_fetch, INDEX_NOT_STORED, INDEX_COLLISION,
@@ -12,7 +12,7 @@ from .binding import (RNNLM_BF16, RNNLM_F32, FLAG_BAD_PREV_WORD, FLAG_BAD_QUERY_
 
 __all__ = ["RNNLM_BF16", "RNNLM_F32", "FLAG_BAD_PREV_WORD", "FLAG_BAD_QUERY_WORD", "FLAG_BAD_ROW",
            "OPT_LSE_MODE", "OPT_OUTPROJ_KERNEL", "RnnlmError", "RnnlmModel", "lib", "lib_path",
-           "rnnlm_dedup", "rnnlm_dedup_workspace_bytes", "rnnlm_load", "rnnlm_step",
+           "rnnlm_dedup", "rnnlm_dedup_static", "DEDUP_STATIC_MAX_N", "rnnlm_dedup_workspace_bytes", "rnnlm_load", "rnnlm_step",
            "rnnlm_step_dedup", "rnnlm_strerror", "RnnlmCache", "rnnlm_cache_create",
            "rnnlm_step_cached", "rnnlm_pack_ids", "RnnlmIndexTable", "rnnlm_index_create",
            "rnnlm_index_intern", "rnnlm_index_fetch", "INDEX_NOT_STORED", "INDEX_COLLISION",

@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "librnnlm.so")
 _lib = None
 
 EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rnnlm_last_error",
-           "rnnlm_dedup_workspace_bytes", "rnnlm_dedup", "rnnlm_step", "rnnlm_step_dedup",
+           "rnnlm_dedup_workspace_bytes", "rnnlm_dedup", "rnnlm_dedup_static", "rnnlm_step", "rnnlm_step_dedup",
            "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
            "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
            "rnnlm_index_free", "rnnlm_index_reset", "rnnlm_index_intern", "rnnlm_index_fetch",
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_dedup_workspace_bytes.restype = Z
         L.rnnlm_dedup.argtypes = [P, I, P, P, P, P, Z, P]
         L.rnnlm_dedup.restype = I
+        L.rnnlm_dedup_static.argtypes = [P, I, P, P, P, P]
+        L.rnnlm_dedup_static.restype = I
         L.rnnlm_step.argtypes = [P, I, I, P, P, P, P, I, P, P, P]
         L.rnnlm_step.restype = I
         L.rnnlm_step_dedup.argtypes = [P, I, I, P, P, P, P, P, P, P, P, P, P, Z, P]
@@ -217,6 +219,18 @@ def rnnlm_dedup(history_ids, rep, inverse, n_unique, workspace, stream=None):
                              _dev(n_unique, torch.int32, "n_unique"),
                              _dev(workspace, torch.uint8, "workspace"),
                              0 if workspace is None else workspace.numel(), _stream(stream)), "rnnlm_dedup")
+
+
+DEDUP_STATIC_MAX_N = 65536
+
+
+def rnnlm_dedup_static(history_ids, rep, inverse, n_unique, stream=None):
+    """rnnlm_dedup without a workspace (the library's own fixed device array; N <= DEDUP_STATIC_MAX_N)."""
+    import torch
+    N = int(history_ids.shape[0])
+    _check(lib().rnnlm_dedup_static(_dev(history_ids, torch.int64, "history_ids"), N,
+                                    _dev(rep, torch.int32, "rep"), _dev(inverse, torch.int32, "inverse"),
+                                    _dev(n_unique, torch.int32, "n_unique"), _stream(stream)), "rnnlm_dedup_static")
 
 
 def rnnlm_step(model: RnnlmModel, prev_word, h_in, query_word, h_out, logprob,

@@ -158,7 +158,7 @@ const char *rnnlm_strerror(int status) {
         case RNNLM_EINVAL: return "invalid argument";
         case RNNLM_ENOMEM: return "out of memory";
         case RNNLM_EDEVICE: return "HIP call failed";
-        case RNNLM_ERANGE: return "batch larger than the model was loaded for";
+        case RNNLM_ERANGE: return "batch larger than the model was loaded for, or size beyond the stated maximum";
         case RNNLM_EWORKSPACE: return "workspace too small or misaligned";
         default: return "unknown status";
     }
@@ -241,6 +241,7 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     }
     HIP_TRY(hipDeviceSynchronize());
     (void)hipFree(O_stage); (void)hipFree(bias_stage); (void)hipFree(upper); (void)hipFree(lower);
+    (void)dedup_static_prepare();
     *out = m;
     return RNNLM_OK;
 
@@ -492,6 +493,7 @@ int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const v
     HIP_TRY(hipMalloc(&p, entries * 4)); d.path_entry = static_cast<int32_t *>(p);
     HIP_TRY(hipMemcpy(p, path_entry, entries * 4, hipMemcpyHostToDevice));
     HIP_TRY(hipDeviceSynchronize());
+    (void)dedup_static_prepare();
     *out = m;
     return RNNLM_OK;
 fail:

@@ -13,6 +13,8 @@
 //          same with a table of raw indices and the keys in LDS once);
 //   large  : table in the caller's workspace, five launches (the numbering is a grid-wide scan; six
 //            beyond a million ids).
+#include <mutex>
+
 #include "dedup_small_body.h"
 #include "device_utils.h"
 #include "rnnlm_internal.h"
@@ -21,7 +23,7 @@ namespace rnnlm {
 
 namespace {
 
-__host__ __device__ inline int table_capacity(int N) {
+__host__ __device__ constexpr int table_capacity(int N) {
     int cap = 64;
     while (cap < 2 * N) cap <<= 1;
     return cap;
@@ -154,12 +156,15 @@ __global__ void dedup_empty_kernel(int32_t *n_unique) { *n_unique = 0; }
 
 }  // namespace
 
-size_t dedup_workspace_bytes(int N) {
+namespace {
+constexpr size_t workspace_bytes_for(int N) {
     if (N <= 0) return 0;
-    int cap = table_capacity(N);
-    size_t bytes = (size_t)(cap + 2) * 16 + (size_t)N * 4 + ((size_t)N / kRankThreads + 2) * 4;
+    const size_t bytes = (size_t)(table_capacity(N) + 2) * 16 + (size_t)N * 4 + ((size_t)N / kRankThreads + 2) * 4;
     return (bytes + 255) & ~(size_t)255;
 }
+}  // namespace
+
+size_t dedup_workspace_bytes(int N) { return workspace_bytes_for(N); }
 
 hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inverse,
                         int32_t *n_unique, void *workspace, hipStream_t stream) {
@@ -201,3 +206,59 @@ hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inve
 }
 
 }  // namespace rnnlm
+
+// ---- grouping without a workspace argument, for callers that cannot allocate one -------------------
+//
+// The hash table, the slots and the counts of the large path live in a file-scope device array of a
+// fixed size instead (2.3 MB: every GPU the library runs on holds its own copy until the process ends).
+// In host code the array's name is only a stand-in for the symbol; the address the kernels take is
+// asked for once per device with hipGetSymbolAddress and kept.
+namespace {
+
+constexpr size_t kStaticScratchBytes = rnnlm::workspace_bytes_for(RNNLM_DEDUP_STATIC_MAX_N);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];          // per device: where `scratch` lives there, or null before the first use
+
+// Device address of `scratch` on the current device (looked up on first use, under a lock).
+int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RNNLM_EDEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return RNNLM_EDEVICE;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RNNLM_OK;
+}
+
+}  // namespace
+
+namespace rnnlm {
+// Called by rnnlm_load / rnnlm_hs_load as well, so that a caller who loads a model first never meets
+// the look-up inside a stream capture.
+int dedup_static_prepare() {
+    void *p = nullptr;
+    return static_scratch(&p);
+}
+}  // namespace rnnlm
+
+extern "C" int rnnlm_dedup_static(const uint64_t *history_ids, int N, int32_t *rep, int32_t *inverse,
+                                  int32_t *n_unique, void *hip_stream) {
+    if (N < 0 || !n_unique) return RNNLM_EINVAL;
+    if (N > 0 && (!history_ids || !rep || !inverse)) return RNNLM_EINVAL;
+    if (N > RNNLM_DEDUP_STATIC_MAX_N) return RNNLM_ERANGE;
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != RNNLM_OK) return rc;
+    // the kernels clear what they use of the table themselves (a fill kernel, no memset node)
+    hipError_t e = rnnlm::launch_dedup(history_ids, N, rep, inverse, n_unique, ws, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
+}

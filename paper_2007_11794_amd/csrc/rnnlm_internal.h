@@ -125,6 +125,8 @@ namespace rnnlm {
 size_t dedup_workspace_bytes(int N);
 hipError_t launch_dedup(const uint64_t *keys, int N, int32_t *rep, int32_t *inverse,
                         int32_t *n_unique, void *workspace, hipStream_t stream);
+// Looks the address of rnnlm_dedup_static's device array up for the current device (status code).
+int dedup_static_prepare();
 
 // Hidden update.  rows = number of rows the grid must cover (>= the true B); the true B is
 // *B_dev when B_dev != nullptr, else rows.  row_src (nullable) maps row b to the raw row
