@@ -24,13 +24,44 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0        # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3         # MI355X fp32 vector (and fp32 matrix), published
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
-# HBM bytes per launch of the output-projection kernel on this workload, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain copy of known size; cannot be measured live.
-# Source and commands: profiles/step_kernels_cfg3_large_vocab_hbm_traffic.md
-OUTPROJ_TRAFFIC_BYTES = {"staged": 78.0e6}
-# The same for the weight-streaming kernel (few rows), by workload number (FETCH_SIZE only: it
-# writes 8 KB).  Source and commands: profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md
-STREAM_TRAFFIC_BYTES = {2: 21.2e6, 3: 67.8e6, 5: 411.5e6}
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled
+# by a plain copy of known size; they cannot be measured live, so every figure names the kernel it was
+# measured on and the summary under profiles/ that holds the command, and is only reported when the
+# launch that was timed is that kernel on that workload (otherwise "traffic" is null).
+TRAFFIC = {
+    ("outproj_staged_kernel<512, true>", 3): (78.0e6, "profiles/step_kernels_cfg3_large_vocab_hbm_traffic.md"),
+    ("outproj_stream_kernel", 2): (21.2e6, "profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md"),
+    ("outproj_stream_kernel", 3): (67.8e6, "profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md"),
+    ("outproj_stream_kernel", 5): (411.5e6, "profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md"),
+}
+# The path kernel of the hierarchical output layer, by workload number (filled from profiles/).
+HS_TRAFFIC = {}
+MIN_TIMED_REGION_S = 0.1         # the event-timed repetitions together last at least this long
+MIN_REPETITIONS = 20
+
+
+def timed_repetitions(step, steps, first_pass_s, torch):
+    """`steps` calls of step() between two events on the launch stream, repeated at least
+    MIN_REPETITIONS times and for at least MIN_TIMED_REGION_S in all (whatever --steps says);
+    the repetitions queue back to back.  Returns the per-repetition times in ms, sorted."""
+    reps = max(MIN_REPETITIONS, int(MIN_TIMED_REGION_S / max(first_pass_s, 1e-6)) + 1)
+    reps = min(reps, 2000)
+    pairs = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    return sorted(a.elapsed_time(b) for a, b in pairs)
+
+
+def median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
 def bench_hs(args, cfg, rn, torch, np) -> int:
@@ -68,15 +99,22 @@ def bench_hs(args, cfg, rn, torch, np) -> int:
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_first = time.perf_counter() - t0
+    rep_ms = timed_repetitions(step, args.steps, dt_first, torch)
+    dt = median(rep_ms) * 1e-3
     assert m.last_error() == 0
-    k_ms = min(rn.rnnlm_hs_time_query(m, query, h_out, lp, 20), rn.rnnlm_hs_time_query(m, query, h_out, lp, 20))
+    k_ms = median([rn.rnnlm_hs_time_query(m, query, h_out, lp, 20) for _ in range(7)])
     nodes = int(np.diff(off)[x["query"]].sum())              # path nodes of all queried words
     # the kernel computes one dot product per DISTINCT node of a raw query's K paths
     node_of = entry & 0x7FFFFFFF
     distinct = sum(len(set(np.concatenate([node_of[off[w]:off[w + 1]] for w in row]).tolist())) for row in x["query"])
     es = 2 if bf16 else 4
     alg_bytes = distinct * H * es + N * H * 4 + N * K * 8.0
+    # HBM bytes per launch of the path kernel as rocprofv3 counted them (FETCH_SIZE + WRITE_SIZE, scaled by a
+    # plain copy of known size): the upper tree levels repeat across queries and come out of L2, so this is
+    # less than the algorithmic figure; the roofline fraction is taken on what HBM really moved
+    traffic, traffic_source = HS_TRAFFIC.get(args.config, (None, None))
+    moved = traffic if traffic is not None else alg_bytes
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -98,12 +136,20 @@ def bench_hs(args, cfg, rn, torch, np) -> int:
                                   "Zipf(%g) frequencies, mean path of a queried word %.1f nodes, %.0f distinct nodes "
                                   "among the %d words of a query"
                                   % (cfg.name, V, H, N, K, cfg.zipf_s or 0, nodes / float(N * K), distinct / float(N), K)},
-           "roofline": {"kernel": "hs_query", "bound": "hbm", "achieved": round(alg_bytes / (k_ms * 1e-3) / 1e9, 1),
-                        "peak": 8000.0, "unit": "GB/s", "frac": round(alg_bytes / (k_ms * 1e-3) / 8e12, 4),
-                        "traffic": None, "us_per_launch": round(k_ms * 1e3, 2), "bytes_per_launch": alg_bytes,
-                        "note": "algorithmic bytes: one node vector per distinct path node of every raw query (the "
-                                "upper tree levels repeat across queries and are served by L2, so the rate can "
-                                "exceed HBM's) + hidden rows + ids and outputs"},
+           "timing": {"method": "median of %d repetitions of %d steps, each bracketed by HIP events on the launch stream"
+                                % (len(rep_ms), args.steps)},
+           "roofline": {"kernel": "hs_query_shared_kernel" if K >= 4 else "hs_query_kernel", "bound": "hbm",
+                        "achieved": round(moved / (k_ms * 1e-3) / 1e9, 1),
+                        "peak": 8000.0, "unit": "GB/s", "frac": round(moved / (k_ms * 1e-3) / 8e12, 4),
+                        "traffic": traffic, "traffic_source": traffic_source,
+                        "us_per_launch": round(k_ms * 1e3, 2), "algorithmic_bytes_per_launch": alg_bytes,
+                        "algorithmic_gbs_incl_l2_hits": round(alg_bytes / (k_ms * 1e-3) / 1e9, 1),
+                        "note": ("achieved = HBM bytes per launch from the profile / launch time" if traffic is not None else
+                                 "no HBM counter figure for this workload: achieved uses the algorithmic bytes, an "
+                                 "upper bound of what HBM moved") +
+                                "; algorithmic bytes = one node vector per distinct path node of every raw query + "
+                                "hidden rows + ids and outputs (the upper tree levels repeat across queries and are "
+                                "served by L2)"},
            "cpu_baseline": cpu}
     print(json.dumps(out))
     m.close()
@@ -242,6 +288,12 @@ def main() -> int:
                   file=sys.stderr)
             return 2
         cfg = cfg.scaled(unique_frac=args.unique_frac, B=int(round(args.unique_frac * cfg.N)))
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.index_table:
         return bench_index_table(args, cfg, rn, torch, np)
     if args.hs:
@@ -316,28 +368,32 @@ def main() -> int:
         cache_info = {"capacity": args.cache, "trace_steps": args.trace_steps, "carry_frac": args.carry_frac,
                       "uncached_value": round(N * args.trace_steps * 20 / (time.perf_counter() - t0), 1)}
 
-    if args.calibrate_copy:
-        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB read + 256 MiB written
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # exactly --steps steps between two synchronisations (host clock) ...
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_first = time.perf_counter() - t0
+    # ... and the same --steps steps again and again between HIP events on the launch stream: the
+    # reported figure is the median repetition
+    rep_ms = timed_repetitions(step, args.steps, dt_first, torch)
+    dt = median(rep_ms) * 1e-3
     B = int(nu.item())                              # distinct histories actually scored
     assert (B == cfg.B or cfg.unique_frac is not None) and m.last_error() == 0
     ms_per_step = dt / args.steps * 1e3
     value = N * args.steps / dt
+    timing = {"method": "median of %d repetitions of %d steps, each bracketed by HIP events on the launch stream"
+                        % (len(rep_ms), args.steps),
+              "ms_per_step_min": round(rep_ms[0] / args.steps, 4), "ms_per_step_max": round(rep_ms[-1] / args.steps, 4),
+              "ms_per_step_first_pass_host_clock": round(dt_first / args.steps * 1e3, 4)}
     if cache_info is not None:                      # a "step" was a pass over the whole trace
         ms_per_step /= args.trace_steps
         value *= args.trace_steps
+        for k in ("ms_per_step_min", "ms_per_step_max", "ms_per_step_first_pass_host_clock"):
+            timing[k] = round(timing[k] / args.trace_steps, 4)
         st = cache.stats()
         cache_info.update(hit_ratio=round(st["hits"] / max(st["lookups"], 1), 4), entries=st["entries"],
                           note="value = raw queries / s over the trace through the cache; hit_ratio over "
@@ -367,18 +423,18 @@ def main() -> int:
                       "ms_per_step": round(g_dt / (replays * args.graph_steps) * 1e3, 4),
                       "value": round(N * replays * args.graph_steps / g_dt, 1)}
 
-    # dominant kernel: output projection + log-sum-exp, timed alone with HIP events on its stream
-    reps = 50 if args.config == 3 else 10
-    k3_ms = m.time_outproj(B, reps)
-    k3_ms = min(k3_ms, m.time_outproj(B, reps))
-    flops = 2.0 * B * cfg.H * cfg.V
+    # dominant kernel: output projection + log-sum-exp, timed alone with HIP events on its stream, launched
+    # as the timed step launches it (the kernel reads the number of distinct rows from the device)
+    reps = 50 if cfg.V * cfg.H <= 65536 * 512 else 10
+    k3_groups = sorted(m.time_outproj(cfg.N, reps, n_rows_dev=nu) for _ in range(7))
+    k3_ms = median(k3_groups)
+    flops = 2.0 * B * cfg.H * cfg.V                 # the contraction on the distinct rows, each product once
     # fp32 models run the contraction on the bf16 matrix cores (from 64 rows on the tiled kernel,
     # below that the weight-streaming one when H <= 768): six bf16 products per fp32 product
-    # (three-term split of both operands), so the launch does 6x the flops
+    # (three-term split of both operands); `achieved` counts every fp32 product once, the rate at
+    # which bf16 products are issued is reported beside it
     split3 = (not bf16) and args.outproj_kernel in (0, 4, 5) and (B >= 64 or cfg.H <= 768 or args.outproj_kernel == 4)
     on_mfma = bf16 or split3
-    if split3:
-        flops *= 6.0
     achieved = flops / (k3_ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if on_mfma else PEAK_FP32_TFLOPS
     # few rows (one launch of the weight-streaming kernel: up to 64 rows of a bf16 model with
@@ -386,23 +442,39 @@ def main() -> int:
     # weights once, nothing else of size
     streamed = args.outproj_kernel in (0, 5) and ((bf16 and B <= 64 and cfg.H <= 1216) or
                                                   (not bf16 and B <= 32 and cfg.H <= 768))
+    Hp = max(128 if bf16 else 64, -(-cfg.H // 64) * 64)
     if streamed:
-        Hp, Vp = max(128 if bf16 else 64, -(-cfg.H // 64) * 64), -(-cfg.V // 256) * 256
+        kernel_name = "outproj_stream_kernel"
+    elif bf16 and args.outproj_kernel in (0, 2) and Hp in (128, 256, 512) and B >= 128:
+        kernel_name = "outproj_staged_kernel<%d, %s>" % (Hp, "true" if args.lse_mode in (0, 2) else "false")
+    else:
+        kernel_name = "outproj_lse"
+    traffic, traffic_source = TRAFFIC.get((kernel_name, args.config if args.unique_frac is None else -1), (None, None))
+    if args.rows is not None and not streamed:
+        traffic, traffic_source = None, None
+    k3_timing = {"us_per_launch": round(k3_ms * 1e3, 2), "us_per_launch_min": round(k3_groups[0] * 1e3, 2),
+                 "us_per_launch_max": round(k3_groups[-1] * 1e3, 2),
+                 "timing": "median of 7 groups of %d back-to-back launches between HIP events on the launch stream, "
+                           "row count read on the device as in the step" % reps}
+    if streamed:
+        Vp = -(-cfg.V // 256) * 256
         wbytes = float(Hp) * Vp * (2 if bf16 else 4)
         gbs = wbytes / (k3_ms * 1e-3) / 1e9
-        roofline = {"kernel": "outproj_lse (weight streaming, %d rows)" % B, "bound": "hbm",
+        roofline = {"kernel": "%s (weight streaming, %d rows)" % (kernel_name, B), "bound": "hbm",
                     "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": STREAM_TRAFFIC_BYTES.get(args.config),
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE, copy-calibrated)",
-                    "us_per_launch": round(k3_ms * 1e3, 2), "bytes_per_launch": wbytes,
-                    "flop_per_launch": flops}
+                    "bytes_per_launch": wbytes, "flop_per_launch": flops}
     else:
-        roofline = {"kernel": "outproj_lse" + (" (fp32 as 6 bf16 products)" if split3 else ""),
+        roofline = {"kernel": kernel_name + (" (fp32 as 6 bf16 products)" if split3 else ""),
                     "bound": "mfma" if on_mfma else "alu", "achieved": round(achieved, 2), "peak": peak,
                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                    "traffic": OUTPROJ_TRAFFIC_BYTES["staged"] if args.outproj_kernel in (0, 2) and args.config == 3 and args.rows is None else None,
-                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated; algorithmic 68.7e6)",
-                    "us_per_launch": round(k3_ms * 1e3, 2), "flop_per_launch": flops}
+                    "traffic": traffic, "traffic_source": traffic_source,
+                    "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, copy-calibrated)",
+                    "flop_per_launch": flops}
+        if split3:
+            roofline["bf16_products_issued_tflops"] = round(6.0 * achieved, 2)
+    roofline.update(k3_timing)
 
     if roofline["bound"] == "mfma" and not args.no_mfma_probe and not args.no_cpu_baseline:
         # context for `frac`: the rate this device sustains on the same loop shape with nothing else
@@ -459,10 +531,27 @@ def main() -> int:
         raw, ref = oracle_rows(rows)
         cdt = time.perf_counter() - t
         err = float(np.max(np.abs(lp.cpu().numpy()[raw] - ref["logprob"])))
+        # the same oracle on ONE core: a few rows, sized to about 3 s
+        one_rows = min(B, 4)
+        t = time.perf_counter()
+        raw1 = np.flatnonzero(inv_h < one_rows)
+        oracle.step(model, x["prev"][rep_h[:one_rows]], x["h_in"][rep_h[:one_rows]], x["query"][raw1],
+                    row_of_query=inv_h[raw1], num_threads=1)
+        t_one = time.perf_counter() - t
+        more = min(B, max(one_rows, int(one_rows * 3.0 / max(t_one, 1e-3))))
+        if more > one_rows:
+            one_rows = more
+            t = time.perf_counter()
+            raw1 = np.flatnonzero(inv_h < one_rows)
+            oracle.step(model, x["prev"][rep_h[:one_rows]], x["h_in"][rep_h[:one_rows]], x["query"][raw1],
+                        row_of_query=inv_h[raw1], num_threads=1)
+            t_one = time.perf_counter() - t
         cpu = {"value": round(rows / cdt, 2), "unit": "hypothesis-steps/s", "cores": threads, "kind": "oracle",
                "sample": "first %d of %d distinct rows of the same step (hidden update + full-vocabulary "
                          "log-sum-exp + their queries), %.1f s wall" % (rows, B, cdt),
-               "max_abs_dlogprob_vs_gpu": err}
+               "max_abs_dlogprob_vs_gpu": err,
+               "one_core": {"value": round(one_rows / t_one, 2), "unit": "hypothesis-steps/s", "cores": 1,
+                            "sample": "first %d distinct rows of the same step, %.1f s wall" % (one_rows, t_one)}}
 
     out = {
         "metric": "RNNLM hypothesis-steps/sec (V=%d,H=%d,B=%d)" % (cfg.V, cfg.H, cfg.N),
@@ -483,6 +572,7 @@ def main() -> int:
                                   else " cut to %d rows" % args.rows, cfg.V, cfg.H, cfg.N, B, cfg.K,
                                   cfg.dtype, cfg.sigma, cfg.zipf_s or 0),
                    "V": cfg.V, "H": cfg.H, "B": B, "N": cfg.N, "K": cfg.K},
+        "timing": timing,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

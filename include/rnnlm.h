@@ -22,7 +22,9 @@
  *   - float / int32 / uint64 arrays are dense, row-major, naturally aligned; `h_in` and
  *     `h_out` rows must start on 16-byte boundaries when H is a multiple of 4 (any
  *     allocator's base alignment gives this).
- *   - A model may be used from one stream at a time (its scratch buffers are shared).
+ *   - A model handle may be used from one stream at a time (its scratch buffers are shared);
+ *     rnnlm_model_share gives further handles on the same weights, each with scratch of its own,
+ *     for further streams.
  *   - Host-checkable mistakes (NULL, negative sizes, B > max_B, short workspace) return
  *     before anything is launched.  Mistakes only visible on the device (a word id outside
  *     [0,V), a row index outside [0,B)) never cause an out-of-bounds access: the affected
@@ -100,8 +102,19 @@ const char *rnnlm_strerror(int status);
 int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void *O,
                const float *bias_or_null, int max_B, rnnlm_model **out);
 
-/* Release a model and its device memory.  NULL is a no-op.  Synchronises the device. */
+/* Release a model handle and the device memory that belongs to it alone.  The weights go when the
+ * last handle that shares them is released (any order).  NULL is a no-op.  Synchronises the device. */
 int rnnlm_free(rnnlm_model *model);
+
+/*
+ * A further handle on the weights of `model` (either kind of model), with scratch buffers, sticky
+ * flag and options of its own (options start as a copy): one loaded model can then serve several
+ * streams at once, one handle per stream -- several decoders on one RNNLM (the paper's Section 3.1
+ * has one search; a server has many).  Costs max_B * (6 H + 2 KB) bytes of device memory, not
+ * another copy of the weights.  max_B: as in rnnlm_load, for calls through the new handle.
+ * Release it with rnnlm_free.  Synchronous.
+ */
+int rnnlm_model_share(const rnnlm_model *model, int max_B, rnnlm_model **out);
 
 /* Set a tunable (see rnnlm_option).  Host-side only; affects later calls. */
 int rnnlm_set_option(rnnlm_model *model, int option, int value);
@@ -155,7 +168,7 @@ int rnnlm_dedup_static(const uint64_t *history_ids, int N, int32_t *rep, int32_t
  *   h_in          dev f32[B][H]   any finite values; all-zero rows are the utterance start
  *   query_word    dev i32[N][K]
  *   row_of_query  dev i32[N] with values in [0,B), or NULL meaning N == B and row n
- *   h_out         dev f32[B][H]   out; must not overlap h_in
+ *   h_out         dev f32[B][H]   out; its B*H floats must not overlap those of h_in (RNNLM_EINVAL)
  *   logprob       dev f32[N][K]   out
  * The B x V logits never leave the chip; only N x K floats are written besides h_out.
  * B = 0 or N = 0 or K = 0 is a valid no-op for the corresponding outputs.
@@ -275,13 +288,6 @@ int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_wo
                   const int32_t *query_word, const int32_t *row_of_query_or_null, int N,
                   const float *base_score_or_null, float *h_out, float *logprob, void *hip_stream);
 
-/* Measurement aid: only the path-evaluation kernel of rnnlm_hs_step (no hidden update) on
- * h_out as a step left it, `repeats` times back to back on `hip_stream` between HIP events on
- * that stream; mean time of one launch in milliseconds.  Synchronises the stream. */
-int rnnlm_hs_time_query(const rnnlm_model *model, int B, int K, const int32_t *query_word,
-                        const int32_t *row_of_query_or_null, int N, const float *h_out, float *logprob,
-                        int repeats, void *hip_stream, float *ms_per_launch);
-
 /*
  * ---- IndexTable and its inverse on the device (Section 3.2; Table 1 steps 5 and 7-12) -------
  *
@@ -341,32 +347,6 @@ int rnnlm_index_stats(rnnlm_index_table *table, void *hip_stream, int64_t out[6]
  */
 int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N, uint64_t *ids,
                    void *hip_stream);
-
-/*
- * Measurement aid: run only the output-projection + log-sum-exp kernel on the hidden
- * block left in the model by the latest rnnlm_step/rnnlm_step_dedup (B rows), `repeats`
- * times back to back on `hip_stream`, bracketed by HIP events on that stream, and return
- * the mean time of one launch in milliseconds in *ms_per_launch.  Synchronises the stream.
- */
-int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream,
-                       float *ms_per_launch);
-
-/*
- * Measurement aid, no part of the method: the rate the bf16 matrix cores of the current device
- * sustain on a loop shaped like the output projection's inner loop (the whole-vocabulary
- * normalisation of Section 2 is where the time goes), so that the kernel's rate can be set against
- * what this device gives under load and not only against the data-sheet peak.  One workgroup of
- * eight waves per compute unit, chains of 32 dependent 32x32x16 bf16 MFMAs, no memory traffic.
- *   feed 0: both operands in registers; feed 1: one operand read from LDS four steps ahead and
- *           one exp2-and-add per produced logit in between (the output projection's steady state);
- *   data 0: all-zero operands; data 1: random bf16 of the size of weights and centred activations
- *           (the clock under matrix load depends on the data).
- * Runs `launches` (1..1000) launches back to back on the null stream between two HIP events,
- * synchronises, allocates and frees 0.6 MB of device memory of its own.  *tflops: dense bf16
- * TFLOP/s; *core_ghz (may be NULL): core clock during the last launch, from the kernel's own cycle
- * counter against the constant 100 MHz one.  RNNLM_EINVAL for arguments outside these ranges.
- */
-int rnnlm_probe_mfma_rate(int feed, int data, int launches, double *tflops, double *core_ghz);
 
 #ifdef __cplusplus
 }

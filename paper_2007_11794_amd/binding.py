@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librnnlm.so")
 _lib = None
 
-EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_set_option", "rnnlm_last_error",
+EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_model_share", "rnnlm_set_option", "rnnlm_last_error",
            "rnnlm_dedup_workspace_bytes", "rnnlm_dedup", "rnnlm_dedup_static", "rnnlm_step", "rnnlm_step_dedup",
            "rnnlm_time_outproj", "rnnlm_cache_create", "rnnlm_cache_free", "rnnlm_cache_reset",
            "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
@@ -69,7 +69,9 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_step.restype = I
         L.rnnlm_step_dedup.argtypes = [P, I, I, P, P, P, P, P, P, P, P, P, P, Z, P]
         L.rnnlm_step_dedup.restype = I
-        L.rnnlm_time_outproj.argtypes = [P, I, I, P, ctypes.POINTER(ctypes.c_float)]
+        L.rnnlm_model_share.argtypes = [P, I, ctypes.POINTER(P)]
+        L.rnnlm_model_share.restype = I
+        L.rnnlm_time_outproj.argtypes = [P, I, P, I, P, ctypes.POINTER(ctypes.c_float)]
         L.rnnlm_time_outproj.restype = I
         L.rnnlm_probe_mfma_rate.argtypes = [I, I, I, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.rnnlm_probe_mfma_rate.restype = I
@@ -161,9 +163,17 @@ class RnnlmModel:
         _check(lib().rnnlm_last_error(self.handle, _stream(stream), ctypes.byref(f)), "rnnlm_last_error")
         return f.value
 
-    def time_outproj(self, B: int, repeats: int, stream=None) -> float:
+    def share(self, max_B: int) -> "RnnlmModel":
+        """A further handle on the same weights with scratch of its own, for use on another stream."""
+        out = ctypes.c_void_p()
+        _check(lib().rnnlm_model_share(self.handle, int(max_B), ctypes.byref(out)), "rnnlm_model_share")
+        return RnnlmModel(out.value, self.V, self.H, self.dtype, int(max_B))
+
+    def time_outproj(self, B: int, repeats: int, stream=None, n_rows_dev=None) -> float:
         ms = ctypes.c_float(0)
-        _check(lib().rnnlm_time_outproj(self.handle, int(B), int(repeats), _stream(stream),
+        import torch
+        _check(lib().rnnlm_time_outproj(self.handle, int(B), _dev(n_rows_dev, torch.int32, "n_rows_dev"),
+                                        int(repeats), _stream(stream),
                                         ctypes.byref(ms)), "rnnlm_time_outproj")
         return ms.value
 

@@ -19,7 +19,7 @@ SOURCES = ["api.hip", "dedup.hip", "recur.hip", "outproj.hip", "outproj_staged.h
            "load_kernels.hip", "cache.hip", "index_table.hip", "hs.hip", "diag.hip"]
 HEADERS = [os.path.join(CSRC, "rnnlm_internal.h"), os.path.join(CSRC, "device_utils.h"),
            os.path.join(CSRC, "outproj_stream_body.h"), os.path.join(CSRC, "dedup_small_body.h"),
-           os.path.join(ROOT, "include", "rnnlm.h")]
+           os.path.join(ROOT, "include", "rnnlm.h"), os.path.join(ROOT, "include", "rnnlm_diag.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed-fp32 instructions stay off: the compiler must not form them on its own
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

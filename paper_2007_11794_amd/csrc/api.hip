@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -31,7 +32,22 @@ bool use_fixed_offset(const rnnlm_model *m) {
     return m->fixed_ok != 0;
 }
 
-void free_dev(rnnlm_model *m) {
+// What belongs to one handle alone: its scratch blocks, its flag, its events.
+void free_scratch(rnnlm_model *m) {
+    ModelDev &d = m->dev;
+    (void)hipFree(d.d);
+    (void)hipFree(d.dfrag);
+    (void)hipFree(d.part);
+    (void)hipFree(d.flag);
+    (void)hipFree(d.d3);
+    d.d = d.dfrag = d.d3 = nullptr; d.part = nullptr; d.flag = nullptr;
+    if (m->ev0) (void)hipEventDestroy(m->ev0);
+    if (m->ev1) (void)hipEventDestroy(m->ev1);
+    m->ev0 = m->ev1 = nullptr;
+}
+
+// The weights and what rnnlm_load derived from them: shared by every handle on the model.
+void free_weights(rnnlm_model *m) {
     ModelDev &d = m->dev;
     (void)hipFree(const_cast<void *>(d.U));
     (void)hipFree(const_cast<void *>(d.W));
@@ -41,18 +57,55 @@ void free_dev(rnnlm_model *m) {
     (void)hipFree(const_cast<float *>(d.half_colsum_O));
     (void)hipFree(const_cast<float *>(d.cvec2));
     (void)hipFree(const_cast<float *>(d.cvec2_fixed));
-    (void)hipFree(d.d);
-    (void)hipFree(d.dfrag);
-    (void)hipFree(d.part);
-    (void)hipFree(d.flag);
     (void)hipFree(const_cast<void *>(d.Ot3));
     (void)hipFree(const_cast<void *>(d.Ofrag));
-    (void)hipFree(d.d3);
     (void)hipFree(const_cast<void *>(d.Theta));
     (void)hipFree(const_cast<int32_t *>(d.path_off));
     (void)hipFree(const_cast<int32_t *>(d.path_entry));
-    if (m->ev0) (void)hipEventDestroy(m->ev0);
-    if (m->ev1) (void)hipEventDestroy(m->ev1);
+}
+
+void free_dev(rnnlm_model *m) {
+    free_scratch(m);
+    free_weights(m);
+}
+
+std::mutex g_handles_mutex;        // guards rnnlm_model::owner / handles / released of every model
+
+// Scratch of one handle for batches of up to max_Bp rows (a multiple of 256): hidden block in row and
+// fragment order, log-sum-exp partials, three-term block (fp32 full-softmax models), flag, events.
+// On failure the caller releases with free_scratch.
+int alloc_scratch(rnnlm_model *m, int max_Bp, bool with_partials, bool with_split3) {
+    int status = RNNLM_OK;
+    ModelDev &d = m->dev;
+    const size_t es = elem_size(d.dtype), block = (size_t)max_Bp * d.Hp * es;
+    void *p;
+    HIP_TRY(hipMalloc(&p, block)); d.d = p;
+    HIP_TRY(hipMemset(d.d, 0, block));
+    HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
+    HIP_TRY(hipMemset(d.flag, 0, 4));
+    if (d.dtype == RNNLM_BF16) {
+        HIP_TRY(hipMalloc(&p, block)); d.dfrag = p;
+        HIP_TRY(hipMemset(d.dfrag, 0, block));
+    }
+    if (with_partials) {
+        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * kMaxSplits * sizeof(float2))); d.part = static_cast<float2 *>(p);
+        HIP_TRY(hipMemset(d.part, 0, (size_t)max_Bp * kMaxSplits * sizeof(float2)));
+    }
+    if (with_split3) {
+        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * 3 * d.Hp * 2)); d.d3 = p;
+        HIP_TRY(hipMemset(d.d3, 0, (size_t)max_Bp * 3 * d.Hp * 2));
+    }
+    HIP_TRY(hipEventCreate(&m->ev0));
+    HIP_TRY(hipEventCreate(&m->ev1));
+    return RNNLM_OK;
+fail:
+    return status;
+}
+
+// Do [a, a + n) and [b, b + n) floats share an element?
+bool ranges_overlap(const float *a, const float *b, size_t n) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b), bytes = n * sizeof(float);
+    return x < y + bytes && y < x + bytes;
 }
 
 double widen_host(const void *p, size_t i, int dtype) {
@@ -65,9 +118,10 @@ double widen_host(const void *p, size_t i, int dtype) {
     return (double)static_cast<const float *>(p)[i];
 }
 
-// Device copies of what the hidden update needs (U, W zero-padded to Hp, half row sums of W,
-// the scratch blocks, the flag, the events).  On failure the caller releases with free_dev.
-int upload_recurrent(rnnlm_model *m, int V, int H, int Hp, int dtype, const void *U, const void *W, int max_Bp) {
+// Device copies of what the hidden update needs (U, W zero-padded to Hp, half row sums of W) and
+// the handle's scratch.  On failure the caller releases with free_dev.
+int upload_recurrent(rnnlm_model *m, int V, int H, int Hp, int dtype, const void *U, const void *W, int max_Bp,
+                     bool with_partials, bool with_split3) {
     int status = RNNLM_OK;
     const size_t es = elem_size(dtype);
     ModelDev &d = m->dev;
@@ -76,16 +130,8 @@ int upload_recurrent(rnnlm_model *m, int V, int H, int Hp, int dtype, const void
     HIP_TRY(hipMalloc(&p, (size_t)V * Hp * es)); d.U = p;
     HIP_TRY(hipMalloc(&p, (size_t)Hp * Hp * es)); d.W = p;
     HIP_TRY(hipMalloc(&p, (size_t)Hp * 4)); d.half_rowsum_W = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.d = p;
-    HIP_TRY(hipMalloc(&p, 4)); d.flag = static_cast<int *>(p);
-    HIP_TRY(hipMemset(d.d, 0, (size_t)max_Bp * Hp * es));
-    if (dtype == RNNLM_BF16) {
-        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * Hp * es)); d.dfrag = p;
-        HIP_TRY(hipMemset(d.dfrag, 0, (size_t)max_Bp * Hp * es));
-    }
-    HIP_TRY(hipMemset(d.flag, 0, 4));
-    HIP_TRY(hipEventCreate(&m->ev0));
-    HIP_TRY(hipEventCreate(&m->ev1));
+    status = alloc_scratch(m, max_Bp, with_partials, with_split3);
+    if (status != RNNLM_OK) return status;
     HIP_TRY(hipMemset(const_cast<void *>(d.U), 0, (size_t)V * Hp * es));
     HIP_TRY(hipMemset(const_cast<void *>(d.W), 0, (size_t)Hp * Hp * es));
     HIP_TRY(hipMemcpy2D(const_cast<void *>(d.U), Hp * es, U, H * es, H * es, V, hipMemcpyHostToDevice));
@@ -190,15 +236,13 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     float max_upper = -INFINITY, min_lower = INFINITY;
 
     void *p;
-    status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp);
+    status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp, true, dtype == RNNLM_F32);
     if (status != RNNLM_OK) goto fail;
     HIP_TRY(hipMalloc(&p, (size_t)Vp * Hp * es)); d.Ot = p;
     HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.bias = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)V * 4)); d.half_colsum_O = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec2 = static_cast<float *>(p);
     HIP_TRY(hipMalloc(&p, (size_t)Vp * 4)); d.cvec2_fixed = static_cast<float *>(p);
-    HIP_TRY(hipMalloc(&p, (size_t)max_Bp * kMaxSplits * sizeof(float2))); d.part = static_cast<float2 *>(p);
-    HIP_TRY(hipMemset(d.part, 0, (size_t)max_Bp * kMaxSplits * sizeof(float2)));
 
     // O: upload as given, transpose + pad on the device, column statistics
     HIP_TRY(hipMalloc(&O_stage, (size_t)H * V * es));
@@ -235,13 +279,12 @@ int rnnlm_load(int V, int H, int dtype, const void *U, const void *W, const void
     HIP_TRY(launch_frag_weights(d.Ot, dtype, Vp, Hp, const_cast<void *>(d.Ofrag), nullptr));
     if (dtype == RNNLM_F32) {       // three-term bf16 split of the weights, scratch for that of the hidden block
         HIP_TRY(hipMalloc(&p, (size_t)Vp * 3 * Hp * 2)); d.Ot3 = p;
-        HIP_TRY(hipMalloc(&p, (size_t)max_Bp * 3 * Hp * 2)); d.d3 = p;
-        HIP_TRY(hipMemset(d.d3, 0, (size_t)max_Bp * 3 * Hp * 2));
         HIP_TRY(launch_split3_weights(static_cast<const float *>(d.Ot), Vp, Hp, const_cast<void *>(d.Ot3), nullptr));
     }
     HIP_TRY(hipDeviceSynchronize());
     (void)hipFree(O_stage); (void)hipFree(bias_stage); (void)hipFree(upper); (void)hipFree(lower);
     (void)dedup_static_prepare();
+    m->handles = 1;
     *out = m;
     return RNNLM_OK;
 
@@ -256,9 +299,48 @@ fail:
 int rnnlm_free(rnnlm_model *model) {
     if (!model) return RNNLM_OK;
     hipError_t e = hipDeviceSynchronize();
-    free_dev(model);
-    delete model;
+    std::lock_guard<std::mutex> lock(g_handles_mutex);
+    free_scratch(model);
+    rnnlm_model *owner = model->owner ? model->owner : model;
+    if (model == owner) owner->released = 1;
+    --owner->handles;
+    if (model != owner) delete model;
+    if (owner->handles == 0) {             // the last handle on these weights is gone
+        free_weights(owner);
+        delete owner;
+    }
     return e == hipSuccess ? RNNLM_OK : RNNLM_EDEVICE;
+}
+
+int rnnlm_model_share(const rnnlm_model *model, int max_B, rnnlm_model **out) {
+    if (!out) return RNNLM_EINVAL;
+    *out = nullptr;
+    if (!model || max_B <= 0 || max_B > (1 << 24)) return RNNLM_EINVAL;
+    rnnlm_model *m = new (std::nothrow) rnnlm_model();
+    if (!m) return RNNLM_ENOMEM;
+    *m = *model;                           // weights' pointers, shapes, options
+    ModelDev &d = m->dev;
+    d.d = d.dfrag = d.d3 = nullptr; d.part = nullptr; d.flag = nullptr;
+    m->ev0 = m->ev1 = nullptr;
+    m->max_B = max_B;
+    m->max_Bp = round_up(max_B, 256);
+    m->handles = 0; m->released = 0;
+    int status = alloc_scratch(m, m->max_Bp, !d.hs, !d.hs && d.dtype == RNNLM_F32);
+    if (status == RNNLM_OK && hipDeviceSynchronize() != hipSuccess) status = RNNLM_EDEVICE;
+    if (status != RNNLM_OK) {
+        free_scratch(m);
+        delete m;
+        (void)hipGetLastError();
+        return status;
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_handles_mutex);
+        rnnlm_model *owner = model->owner ? model->owner : const_cast<rnnlm_model *>(model);
+        m->owner = owner;
+        ++owner->handles;
+    }
+    *out = m;
+    return RNNLM_OK;
 }
 
 int rnnlm_set_option(rnnlm_model *model, int option, int value) {
@@ -317,7 +399,7 @@ int rnnlm_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word,
     if (B > 0 && (!prev_word || !h_in || !h_out)) return RNNLM_EINVAL;
     if (N > 0 && K > 0 && (!query_word || !logprob)) return RNNLM_EINVAL;
     if (!row_of_query_or_null && N != B) return RNNLM_EINVAL;
-    if (B > 0 && h_out == h_in) return RNNLM_EINVAL;
+    if (B > 0 && ranges_overlap(h_in, h_out, (size_t)B * model->dev.H)) return RNNLM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
     SplitInfo splits = fixed_split_info(1);
@@ -348,7 +430,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
     if (!n_unique) return RNNLM_EINVAL;
     if (N > 0 && (!history_ids || !prev_word || !h_in || !rep || !inverse || !h_out)) return RNNLM_EINVAL;
     if (N > 0 && K > 0 && (!query_word || !score)) return RNNLM_EINVAL;
-    if (N > 0 && h_out == h_in) return RNNLM_EINVAL;
+    if (N > 0 && ranges_overlap(h_in, h_out, (size_t)N * model->dev.H)) return RNNLM_EINVAL;
     if (cache && (cache->dev.H != model->dev.H || N > cache->max_B)) return RNNLM_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     // through a cache, few enough raw queries: grouping and lookup are one launch
@@ -483,7 +565,7 @@ int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const v
     d.V = V; d.H = H; d.Hp = Hp; d.Vp = round_up(V, 256); d.dtype = dtype; d.hs = 1; d.hs_max_len = longest;
     m->max_B = max_B; m->max_Bp = max_Bp;
     void *p;
-    status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp);
+    status = upload_recurrent(m, V, H, Hp, dtype, U, W, max_Bp, false, false);
     if (status != RNNLM_OK) goto fail;
     HIP_TRY(hipMalloc(&p, (size_t)(V - 1) * Hp * es)); d.Theta = p;
     HIP_TRY(hipMemset(p, 0, (size_t)(V - 1) * Hp * es));
@@ -494,6 +576,7 @@ int rnnlm_hs_load(int V, int H, int dtype, const void *U, const void *W, const v
     HIP_TRY(hipMemcpy(p, path_entry, entries * 4, hipMemcpyHostToDevice));
     HIP_TRY(hipDeviceSynchronize());
     (void)dedup_static_prepare();
+    m->handles = 1;
     *out = m;
     return RNNLM_OK;
 fail:
@@ -511,7 +594,7 @@ int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_wo
     if (B > 0 && (!prev_word || !h_in || !h_out)) return RNNLM_EINVAL;
     if (N > 0 && K > 0 && (!query_word || !logprob)) return RNNLM_EINVAL;
     if (!row_of_query_or_null && N != B) return RNNLM_EINVAL;
-    if (B > 0 && h_out == h_in) return RNNLM_EINVAL;
+    if (B > 0 && ranges_overlap(h_in, h_out, (size_t)B * model->dev.H)) return RNNLM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
     if (launch_recur(d, B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
@@ -641,7 +724,8 @@ int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N,
                : RNNLM_EDEVICE;
 }
 
-int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_stream, float *ms_per_launch) {
+int rnnlm_time_outproj(const rnnlm_model *model, int B, const int32_t *n_rows_dev, int repeats, void *hip_stream,
+                       float *ms_per_launch) {
     if (!model || !ms_per_launch || repeats <= 0 || B <= 0 || model->dev.hs) return RNNLM_EINVAL;
     if (B > model->max_B) return RNNLM_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -649,7 +733,7 @@ int rnnlm_time_outproj(const rnnlm_model *model, int B, int repeats, void *hip_s
     const bool fixed = use_fixed_offset(model);
     if (hipEventRecord(model->ev0, s) != hipSuccess) return RNNLM_EDEVICE;
     for (int i = 0; i < repeats; ++i)
-        if (launch_outproj(model->dev, B, nullptr, fixed, model->outproj_kernel, &splits, s) != hipSuccess)
+        if (launch_outproj(model->dev, B, n_rows_dev, fixed, model->outproj_kernel, &splits, s) != hipSuccess)
             return RNNLM_EDEVICE;
     if (hipEventRecord(model->ev1, s) != hipSuccess) return RNNLM_EDEVICE;
     if (hipEventSynchronize(model->ev1) != hipSuccess) return RNNLM_EDEVICE;

@@ -20,7 +20,7 @@
 #include <vector>
 
 #include "device_utils.h"
-#include "rnnlm.h"
+#include "rnnlm_diag.h"
 
 namespace rnnlm {
 

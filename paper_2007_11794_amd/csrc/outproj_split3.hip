@@ -219,15 +219,10 @@ template <int WN>
 hipError_t launch_split3_shape(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset, SplitInfo *splits,
                                hipStream_t stream) {
     using C = Split3Cfg<WN>;
-    static bool attr_set[2] = {false, false};
-    const int which = fixed_offset ? 1 : 0;
+    static LdsLimit limit[2];
     const void *fn = fixed_offset ? reinterpret_cast<const void *>(outproj_split3_kernel<true, WN>)
                                   : reinterpret_cast<const void *>(outproj_split3_kernel<false, WN>);
-    if (!attr_set[which]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set[which] = true;
-    }
+    if (hipError_t e = limit[fixed_offset ? 1 : 0].ensure(fn, C::kLdsBytes); e != hipSuccess) return e;
     // one workgroup per compute unit (a stage pair takes most of its LDS); at most one split per
     // tile of words, rounded UP to a multiple of 8 so that no split gets two tiles while the others
     // have one

@@ -486,15 +486,10 @@ template <int HP>
 hipError_t launch_hp(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset, int wg_per_xcd,
                      hipStream_t stream) {
     using C = StagedCfg<HP>;
-    static bool attr_set[2] = {false, false};
-    const int which = fixed_offset ? 1 : 0;
+    static LdsLimit limit[2];
     const void *fn = fixed_offset ? reinterpret_cast<const void *>(outproj_staged_kernel<HP, true>)
                                   : reinterpret_cast<const void *>(outproj_staged_kernel<HP, false>);
-    if (!attr_set[which]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set[which] = true;
-    }
+    if (hipError_t e = limit[fixed_offset ? 1 : 0].ensure(fn, C::kLdsBytes); e != hipSuccess) return e;
     dim3 grid(kXcds * wg_per_xcd), block(kThreads);
     if (fixed_offset)
         hipLaunchKernelGGL((outproj_staged_kernel<HP, true>), grid, block, C::kLdsBytes, stream, m, rows, B_dev,

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kThreads) void outproj_stream_f32_kernel(ModelDev m
 template <int RB>
 hipError_t launch_rb(const ModelDev &m, int rows, const int *B_dev, int row0, bool fixed_offset, int S,
                      hipStream_t stream) {
-    static size_t attr_bytes[4] = {0, 0, 0, 0};
+    static LdsLimit limit[4];
     const bool f32 = m.dtype == RNNLM_F32;
     const int which = (fixed_offset ? 1 : 0) + (f32 ? 2 : 0);
     const size_t lds_bytes = stream_lds_bytes(f32 ? 3 : 1, RB, m.Hp >> 4);
@@ -62,11 +62,7 @@ hipError_t launch_rb(const ModelDev &m, int rows, const int *B_dev, int row0, bo
                                          : reinterpret_cast<const void *>(outproj_stream_f32_kernel<RB, false>))
                          : (fixed_offset ? reinterpret_cast<const void *>(outproj_stream_kernel<RB, true>)
                                          : reinterpret_cast<const void *>(outproj_stream_kernel<RB, false>));
-    if (attr_bytes[which] < lds_bytes) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_bytes[which] = lds_bytes;
-    }
+    if (hipError_t e = limit[which].ensure(fn, lds_bytes); e != hipSuccess) return e;
     if (f32) {
         if (fixed_offset)
             hipLaunchKernelGGL((outproj_stream_f32_kernel<RB, true>), dim3(S), dim3(kThreads), lds_bytes, stream, m, rows, B_dev, row0);

@@ -345,15 +345,10 @@ template <typename T, int MB, int WN, int NS, bool OVL>
 hipError_t launch_tiled_shape(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset, int wg_target,
                               SplitInfo *splits, hipStream_t stream) {
     using C = TiledCfg<MB, WN, NS>;
-    static bool attr_set[2] = {false, false};
-    const int which = fixed_offset ? 1 : 0;
+    static LdsLimit limit[2];
     const void *fn = fixed_offset ? reinterpret_cast<const void *>(outproj_tiled_kernel<T, true, MB, WN, NS, OVL>)
                                   : reinterpret_cast<const void *>(outproj_tiled_kernel<T, false, MB, WN, NS, OVL>);
-    if (!attr_set[which]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set[which] = true;
-    }
+    if (hipError_t e = limit[fixed_offset ? 1 : 0].ensure(fn, C::kLdsBytes); e != hipSuccess) return e;
     // wg_target workgroups; at most one split per tile of words, rounded UP to a multiple of 8 (a few
     // splits stay empty) so that no split gets two tiles while the others have one
     const int wg_per_xcd = wg_target / kXcds, ntiles = m.Vp / C::kWords, sx_cap = (ntiles + kXcds - 1) / kXcds;

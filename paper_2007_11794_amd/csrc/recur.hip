@@ -468,16 +468,15 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
     if (m.dtype == RNNLM_BF16 && m.H % 4 == 0 && (reinterpret_cast<uintptr_t>(h_in) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(h_out) & 15) == 0) {
         const int units = m.Hp / kRtTile;
-        static bool attr_set = false;                   // the small shape takes more than the default 64 KB of dynamic LDS
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 1>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 4 * RtCfg<32>::kStageBytes);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 2>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 8 * RtCfg<32>::kStageBytes);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
+        static LdsLimit limit[2];                       // the small shape takes more than the default 64 KB of dynamic LDS
+        if (hipError_t e = limit[0].ensure(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 1>),
+                                           4 * RtCfg<32>::kStageBytes);
+            e != hipSuccess)
+            return e;
+        if (hipError_t e = limit[1].ensure(reinterpret_cast<const void *>(recur_bf16_tiled_kernel<4, 32, 2>),
+                                           8 * RtCfg<32>::kStageBytes);
+            e != hipSuccess)
+            return e;
         // The small shape (32 rows per workgroup) while its workgroups fit the compute units in one
         // round, the large one (64 rows, three workgroups per unit) beyond: the crossover measured
         // at H = 512, 768, 1024 and 2048 lies there.

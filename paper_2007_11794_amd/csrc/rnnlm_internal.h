@@ -5,7 +5,11 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "rnnlm.h"
+#include "rnnlm_diag.h"
 
 namespace rnnlm {
 
@@ -109,15 +113,44 @@ struct rnnlm_cache {
 };
 
 struct rnnlm_model {
-    rnnlm::ModelDev dev;
+    rnnlm::ModelDev dev;   // the weights' pointers may be another handle's (see owner); the scratch is this handle's
     int max_B, max_Bp;
     int fixed_ok;          // the fixed-offset log-sum-exp is usable for this model
     int lse_mode;          // RNNLM_OPT_LSE_MODE
     int outproj_kernel;    // RNNLM_OPT_OUTPROJ_KERNEL
     hipEvent_t ev0, ev1;
+    // Handles made by rnnlm_model_share point at the handle that loaded the weights; that one counts
+    // the handles alive on its weights (itself included until it is released) and frees the weights
+    // with the last of them.  Both fields are guarded by one library-wide lock.
+    rnnlm_model *owner;    // null: this handle loaded the weights
+    int handles;           // owner only: handles alive on these weights
+    int released;          // owner only: rnnlm_free was called on it, the struct lives on for the others
 };
 
 namespace rnnlm {
+
+// A kernel's dynamic-LDS limit, raised once per device to the largest size asked for so far.  Safe
+// when two host threads make the first launch at the same time (one static object per kernel).
+class LdsLimit {
+  public:
+    hipError_t ensure(const void *kernel, size_t bytes) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+        if (granted_[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+        std::lock_guard<std::mutex> lock(mutex_);
+        if (granted_[dev].load(std::memory_order_relaxed) >= bytes) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e == hipSuccess) granted_[dev].store(bytes, std::memory_order_release);
+        return e;
+    }
+
+  private:
+    static constexpr int kDevices = 64;
+    std::mutex mutex_;
+    std::atomic<size_t> granted_[kDevices] = {};
+};
 
 // ---- launchers (each enqueues on `stream` and returns the hipGetLastError of the launch)
 

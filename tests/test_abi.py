@@ -1,4 +1,4 @@
-"""The C-ABI library without a GPU: it loads, exports what include/rnnlm.h declares, and
+"""The C-ABI library without a GPU: it loads, exports what include/rnnlm.h and include/rnnlm_diag.h declare, and
 rejects host-checkable mistakes before touching the device."""
 import ctypes
 import os
@@ -13,9 +13,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "rnnlm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rnnlm_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("rnnlm.h", "rnnlm_diag.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(rnnlm_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -68,7 +71,13 @@ def test_host_checked_errors_return_before_any_device_work():
     assert L.rnnlm_dedup(p, 4, p, p, p, ctypes.c_void_p(p.value + 4), 1 << 20, None) == EWORKSPACE
     assert L.rnnlm_dedup(p, (1 << 28) + 1, p, p, p, p, 1 << 20, None) == ERANGE
     ms = ctypes.c_float()
-    assert L.rnnlm_time_outproj(None, 1, 1, None, ctypes.byref(ms)) == EINVAL
+    assert L.rnnlm_time_outproj(None, 1, None, 1, None, ctypes.byref(ms)) == EINVAL
+    assert L.rnnlm_model_share(None, 4, ctypes.byref(out)) == EINVAL
+    assert L.rnnlm_model_share(None, 4, None) == EINVAL
+    assert L.rnnlm_dedup_static(p, -1, p, p, p, None) == EINVAL
+    assert L.rnnlm_dedup_static(None, 4, p, p, p, None) == EINVAL
+    assert L.rnnlm_dedup_static(p, 4, p, p, None, None) == EINVAL
+    assert L.rnnlm_dedup_static(p, 65537, p, p, p, None) == ERANGE
     tf = ctypes.c_double()
     assert L.rnnlm_probe_mfma_rate(2, 0, 1, ctypes.byref(tf), None) == EINVAL
     assert L.rnnlm_probe_mfma_rate(0, -1, 1, ctypes.byref(tf), None) == EINVAL

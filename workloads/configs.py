@@ -48,6 +48,12 @@ CONFIGS: Dict[int, Workload] = {
                 zipf_s=1.1, h_in="sigmoid_normal", steps=50, unique_frac=0.3, seed=1004),
     5: Workload("stress", V=200000, H=1024, B=2048, K=64, N=2048, dtype="bf16", sigma=0.02,
                 zipf_s=1.0, h_in="sigmoid_normal", steps=1, seed=1005),
+    # Not one of the five given workloads: the regime the paper itself runs in (Section 5.1: about a
+    # million words, a hidden layer of 100 units -- 128 here, the next size the matrix cores like) with the
+    # few distinct histories per step that its cache leaves (Section 5.2).  Used to set the hierarchical
+    # output layer of Section 2.1 beside the full softmax where the former is meant to win.
+    6: Workload("paper_regime", V=1000000, H=128, B=64, K=32, N=64, dtype="bf16", sigma=0.05,
+                zipf_s=1.1, h_in="sigmoid_normal", steps=1, seed=1006),
 }
 
 
