@@ -41,6 +41,8 @@
 // Work split (staged_plan): workgroup id modulo 8 is the XCD; vocabulary split s runs on
 // XCD s % 8, with all row groups of that split next to each other, so the row groups that
 // stream the same weights hit in the same 4 MB L2 and HBM is read once.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "outproj_stream_body.h"
 #include "rnnlm_internal.h"
@@ -200,9 +202,85 @@ __device__ __forceinline__ void load_d_operand(bf16x8 &dst, const bf16_t *lane_p
 }
 // Wait until at most `younger` of this wave's vector-memory operations are outstanding; the
 // operand goes in and out so that its first use cannot move in front of the wait.
-__device__ __forceinline__ void await_d_operand(bf16x8 &op, int younger) {
-    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(op) : "n"(younger));
+template <int YOUNGER>
+__device__ __forceinline__ void await_d_operand(bf16x8 &op) {
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(op) : "n"(YOUNGER));
 }
+// fn(std::integral_constant<int, I>) for I = BEGIN .. END - 1, in order.
+template <int BEGIN, int END, typename Fn>
+__device__ __forceinline__ void static_for(Fn &&fn) {
+    if constexpr (BEGIN < END) {
+        fn(std::integral_constant<int, BEGIN>{});
+        static_for<BEGIN + 1, END>(fn);
+    }
+}
+
+// Dispatch of load_d_operand on a compile-time operand index: operand j of a wave lies 1 KB behind
+// operand j - 1; one pointer every 4 KB, immediate offsets in between.
+template <int J>
+__device__ __forceinline__ void load_d_operand_at(bf16x8 &dst, const bf16_t *dfr) {
+    load_d_operand<(J % 4) * 1024>(dst, dfr + (size_t)(J / 4) * 2048);
+}
+
+// What block 0 of an item issues besides its own work (staged_block_fixed<HP, true>): the part of
+// d that the prologue has not requested, and blocks 1 and 2.  All loads of a wave are issued in
+// one fixed program order, so the number of loads younger than any given one is a compile-time
+// figure: that is what the vmcnt immediates of block 0 are computed from.
+template <int HP>
+struct FirstBlockSchedule {
+    using C = StagedCfg<HP>;
+    static constexpr int KS = C::KS, HALF = KS / 2, L = C::kLoadsPerBlock, NW = C::kLoadsPerThread;
+    static constexpr int kLoadStep = (HALF - 2) / NW;
+    static constexpr int D0 = KS < 8 ? KS : 8;                 // operands of d requested by the prologue
+    static_assert(2 * L <= HALF, "blocks 1 and 2 are requested in the first half of block 0");
+    // loads issued in k-step k: before its MFMA an operand of d (e1) and a load of block 1 or 2 (e2),
+    // after its MFMA the regular loads of block 3 (e3)
+    static constexpr int e1(int k) { return k + D0 < KS ? 1 : 0; }
+    static constexpr int e2(int k) { return k < 2 * L ? 1 : 0; }
+    static constexpr int e3(int k) {
+        int n = (k == KS - 2) ? 1 : 0;
+        for (int q = 0; q < NW; ++q)
+            if (k == HALF + 1 + q * kLoadStep) ++n;
+        return n;
+    }
+    // loads younger than operand ks of d when the MFMA of k-step ks is about to be issued
+    static constexpr int younger_than_d(int ks) {
+        int n = 0;
+        if (ks < D0) {
+            n = D0 - 1 - ks;
+            for (int k = 0; k <= ks; ++k) n += e1(k) + e2(k);
+            for (int k = 0; k < ks; ++k) n += e3(k);
+        } else {
+            const int j0 = ks - D0;                             // the k-step that requested it
+            n = e2(j0);
+            for (int k = j0 + 1; k <= ks; ++k) n += e1(k) + e2(k);
+            for (int k = j0; k < ks; ++k) n += e3(k);
+        }
+        return n;
+    }
+    // loads younger than the last load of block 1 (k-step L - 1) at the barrier on top of k-step HALF
+    static constexpr int younger_than_block1() {
+        int n = 0;
+        for (int k = L; k < HALF; ++k) n += e1(k) + e2(k);
+        for (int k = L - 1; k < HALF; ++k) n += e3(k);
+        return n;
+    }
+    static constexpr int worst() {
+        int w = younger_than_block1();
+        for (int ks = 0; ks < KS; ++ks)
+            if (younger_than_d(ks) > w) w = younger_than_d(ks);
+        return w;
+    }
+    static_assert(worst() < 64, "vmcnt is a 6-bit counter");
+};
+struct FirstBlockLoads {
+    const bf16_t *dfr;          // this lane's 16 bytes of operand 0 of its wave's rows
+    const bf16_t *blk[2];       // weights of blocks 1 and 2 (or the dummy source)
+    const float *cst[2];        // their constants
+    bool real[2];
+    uint32_t stage[2], cslot[2];
+};
 
 // Fixed offset: one 32-word block for this wave's 32 rows, as ONE basic block.
 //   acc     on entry the block's constants (the base-2 logits start from them), on return the
@@ -217,19 +295,20 @@ __device__ __forceinline__ void await_d_operand(bf16x8 &op, int younger) {
 // number of loads in flight and the vmcnt immediates hold).  On return a[] holds the first
 // kPrefetch A operands of block bi+1.
 //
-// FIRST (block 0 of an item): the rows of d were requested by load_d_operand just before and are
-// still arriving; every MFMA waits for ITS operand only (await_d_operand with the number of
-// younger loads of this wave: the rest of d, block 2, and what this block has issued of block 3),
-// so the chain starts when the first kilobytes are there, not the last.  No wait is needed at its
-// barrier: block 1 was requested before d, so it has landed when the first operand has.
+// FIRST (block 0 of an item): the prologue has requested block 0 and the first operands of d only,
+// so that the chain starts early; the rest of d is requested here, one operand per k-step eight
+// k-steps ahead of its use, and blocks 1 and 2 load by load in the first half.  Every MFMA waits
+// for ITS operand of d alone, and the barrier for block 1 alone (FirstBlockSchedule has the
+// counts): the chain runs at the pace at which d arrives instead of starting after all of it.
 template <int HP, bool FIRST>
 __device__ __forceinline__ void staged_block_fixed(const char *lds, const char *cring, uint32_t lds0,
                                                    uint32_t cring0, const Loader<HP> &loader, const bf16_t *Ot,
                                                    const float *cvec, int blk0, int nblk, int bi,
                                                    const int (&aoff)[8], bf16x8 (&a)[kPrefetch],
                                                    bf16x8 (&dreg)[HP / 16], int g, f32x16 &acc,
-                                                   f32x16 &other, float &srun) {
+                                                   f32x16 &other, float &srun, const FirstBlockLoads &first) {
     using C = StagedCfg<HP>;
+    using F = FirstBlockSchedule<HP>;
     constexpr int KS = C::KS, HALF = KS / 2, NW = C::kLoadsPerThread;
     constexpr int kLoadStep = (HALF - 2) / NW;                 // k-steps between two weight loads
     static_assert(KS >= 2 * kPrefetch && kLoadStep >= 1 && HALF + 1 + (NW - 1) * kLoadStep < KS - 2, "");
@@ -240,26 +319,30 @@ __device__ __forceinline__ void staged_block_fixed(const char *lds, const char *
     const int v3 = real ? (blk0 + bi + 3) * kStagedWords : 0;
     const bf16_t *blk3 = Ot + (size_t)v3 * HP;
     const uint32_t stage3 = lds0 + ((bi + 3) & 3) * C::kStageBytes, cslot3 = cring0 + ((bi + 3) & 7) * kCSlotBytes;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        if (ks == HALF) {
-            if (!FIRST) wait_vmcnt<C::kLoadsPerBlock>();
+    // the k-steps as a compile-time loop: every condition below is a constant, and so are the vmcnt
+    // immediates
+    static_for<0, KS>([&](auto step) __attribute__((always_inline)) {
+        constexpr int ks = decltype(step)::value;
+        if constexpr (ks == HALF) {
+            if constexpr (FIRST) wait_vmcnt<F::younger_than_block1()>();
+            else wait_vmcnt<C::kLoadsPerBlock>();
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
         const bf16x8 cur = a[ks % kPrefetch];
-        if (ks + kPrefetch < KS) a[ks % kPrefetch] = RNNLM_A_FRAG(stage, ks + kPrefetch);
+        if constexpr (ks + kPrefetch < KS) a[ks % kPrefetch] = RNNLM_A_FRAG(stage, ks + kPrefetch);
         else a[ks % kPrefetch] = RNNLM_A_FRAG(next_stage, ks + kPrefetch - KS);
-        if (FIRST) {
-            // loads of this wave younger than d[ks]: the later operands, block 2, and the loads of
-            // block 3 that the k-steps before this one have issued
-            int younger = (KS - 1 - ks) + C::kLoadsPerBlock;
-#pragma unroll
-            for (int q = 0; q < NW; ++q)
-                if (HALF + 1 + q * kLoadStep < ks) ++younger;
-            if (KS - 2 < ks) ++younger;
-            await_d_operand(dreg[ks], younger);
+        if constexpr (FIRST) {
+            if constexpr (ks + F::D0 < KS) load_d_operand_at<ks + F::D0>(dreg[ks + F::D0], first.dfr);
+            if constexpr (ks < F::L) {
+                if constexpr (ks < NW) loader.issue_weights(first.blk[0], ks, first.real[0], first.stage[0]);
+                else loader.issue_consts(first.cst[0], first.cslot[0]);
+            } else if constexpr (ks < 2 * F::L) {
+                if constexpr (ks - F::L < NW) loader.issue_weights(first.blk[1], ks - F::L, first.real[1], first.stage[1]);
+                else loader.issue_consts(first.cst[1], first.cslot[1]);
+            }
+            await_d_operand<F::younger_than_d(ks)>(dreg[ks]);
         }
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[ks], acc, 0, 0, 0);
         // the previous block's sixteen logits, over k-steps 1 .. HALF
@@ -270,7 +353,7 @@ __device__ __forceinline__ void staged_block_fixed(const char *lds, const char *
 #pragma unroll
         for (int q = 0; q < NW; ++q)
             if (ks == HALF + 1 + q * kLoadStep) loader.issue_weights(blk3, q, real, stage3);
-        if (ks == KS - 2) loader.issue_consts(cvec + v3, cslot3);
+        if constexpr (ks == KS - 2) loader.issue_consts(cvec + v3, cslot3);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             if (ks == HALF + 1 + (q * (HALF - 1)) / 4) {
@@ -281,7 +364,7 @@ __device__ __forceinline__ void staged_block_fixed(const char *lds, const char *
         // keep this order: the compiler's scheduler would otherwise sink every LDS read to
         // just before its MFMA and expose the LDS latency on each step
         __builtin_amdgcn_sched_barrier(0);
-    }
+    });
 }
 
 // Fixed offset: all blocks of one (row group, split) item for this wave's rows; returns the sum
@@ -295,33 +378,34 @@ __device__ __forceinline__ float staged_item_fixed(const ModelDev &m, char *lds,
     const bf16_t *Ot = static_cast<const bf16_t *>(m.Ot);
     const float *cvec = m.cvec2_fixed;
     const uint32_t lds0 = lds_address(lds), cring0 = lds_address(cring);
-    // Blocks 0 and 1, then this wave's rows of d (all k, as MFMA B operands; rows beyond B hold
-    // stale scratch: rows are independent and those lanes' results are dropped).
+    // Block 0 and the first operands of this wave's rows of d (all k of 32 rows are MFMA B operands
+    // held in registers; rows beyond B hold stale scratch: rows are independent and those lanes'
+    // results are dropped).  The rest of d and blocks 1 and 2 are requested by block 0 itself.
+    using F = FirstBlockSchedule<HP>;
     loader.issue_all(Ot, cvec, blk0 * kStagedWords, true, lds0, cring0);
-    loader.issue_all(Ot, cvec, (blk0 + 1) * kStagedWords, 1 < nblk, lds0 + C::kStageBytes, cring0 + kCSlotBytes);
     bf16x8 dreg[KS];
-    {
-        // fragment (row block, ks) of the fragment-ordered copy: 64 lanes x 16 bytes in a row
-        const bf16_t *dfr = static_cast<const bf16_t *>(m.dfrag) +
-                            ((size_t)(rg * (kStagedRows / 32) + wave) * KS * 64 + lane) * 8;
+    FirstBlockLoads first;
+    // fragment (row block, ks) of the fragment-ordered copy: 64 lanes x 16 bytes in a row
+    first.dfr = static_cast<const bf16_t *>(m.dfrag) + ((size_t)(rg * (kStagedRows / 32) + wave) * KS * 64 + lane) * 8;
+    static_for<0, F::D0>([&](auto j) __attribute__((always_inline)) {
+        load_d_operand_at<decltype(j)::value>(dreg[decltype(j)::value], first.dfr);
+    });
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16_t *p4 = dfr + (size_t)(ks / 4) * 2048;          // a pointer every 4 KB, offsets in between
-            if (ks % 4 == 0) load_d_operand<0>(dreg[ks], p4);
-            else if (ks % 4 == 1) load_d_operand<1024>(dreg[ks], p4);
-            else if (ks % 4 == 2) load_d_operand<2048>(dreg[ks], p4);
-            else load_d_operand<3072>(dreg[ks], p4);
-        }
+    for (int i = 0; i < 2; ++i) {
+        first.real[i] = i + 1 < nblk;
+        const int v = first.real[i] ? (blk0 + i + 1) * kStagedWords : 0;
+        first.blk[i] = Ot + (size_t)v * HP;
+        first.cst[i] = cvec + v;
+        first.stage[i] = lds0 + (i + 1) * C::kStageBytes;
+        first.cslot[i] = cring0 + (i + 1) * kCSlotBytes;
     }
-    // Block 0 has landed once only the younger loads are outstanding: block 1 and d.
-    static_assert(C::kLoadsPerBlock + KS < 64, "the vmcnt immediates of the first block");
-    wait_vmcnt<C::kLoadsPerBlock + KS>();
+    // Block 0 has landed once only the younger loads are outstanding: the first operands of d.
+    wait_vmcnt<F::D0>();
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();                             // block 0 is published
     asm volatile("" ::: "memory");
-    // Block 2 has until the barrier in the middle of block 1 to land.  From there on every wave has,
-    // at the barrier in the middle of block bi, the loads of blocks bi+1 and bi+2 in flight at most.
-    loader.issue_all(Ot, cvec, (blk0 + 2) * kStagedWords, 2 < nblk, lds0 + 2 * C::kStageBytes, cring0 + 2 * kCSlotBytes);
+    // From block 1 on every wave has, at the barrier in the middle of block bi, the loads of blocks
+    // bi+1 and bi+2 in flight at most.
     bf16x8 a[kPrefetch];
 #pragma unroll
     for (int i = 0; i < kPrefetch; ++i) a[i] = RNNLM_A_FRAG(lds, i);
@@ -339,7 +423,7 @@ __device__ __forceinline__ float staged_item_fixed(const ModelDev &m, char *lds,
     for (int i = 0; i < 16; ++i) acc1[i] = -INFINITY;        // "previous block" of block 0: adds 2^-inf = 0
     float srun = 0.f;
 #define RNNLM_BLOCK(FIRST, BI, ACC, OTHER) \
-    staged_block_fixed<HP, FIRST>(lds, cring, lds0, cring0, loader, Ot, cvec, blk0, nblk, BI, aoff, a, dreg, g, ACC, OTHER, srun)
+    staged_block_fixed<HP, FIRST>(lds, cring, lds0, cring0, loader, Ot, cvec, blk0, nblk, BI, aoff, a, dreg, g, ACC, OTHER, srun, first)
     RNNLM_BLOCK(true, 0, acc0, acc1);
     int bi = 1;
     for (; bi + 1 < nblk; bi += 2) {
@@ -400,8 +484,8 @@ __global__ __launch_bounds__(kThreads) void outproj_staged_kernel(ModelDev m, in
 
     for (int item = local; item < items; item += wg_per_xcd) {
         const int rg = item % plan.RG, split = xcd + kXcds * (item / plan.RG);
-        const int blk0 = (int)(((long long)split * T) / plan.S);
-        const int nblk = (int)(((long long)(split + 1) * T) / plan.S) - blk0;
+        const int blk0 = part_begin(split, T, plan.S);
+        const int nblk = part_begin(split + 1, T, plan.S) - blk0;
         const int b = rg * kStagedRows + wave * 32 + col;     // this lane's row
         if (FIXED) {
             float srun = 0.f;

@@ -30,8 +30,8 @@ __device__ __forceinline__ void outproj_stream_body(const ModelDev &m, int B, in
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KS = m.Hp >> 4, GPB = KS / kStreamGroup;
     const int T = m.Vp / 32;
-    const int blk1 = (int)(((long long)(split + 1) * T) / S);
-    const int blk0 = (int)(((long long)split * T) / S);
+    const int blk1 = part_begin(split + 1, T, S);
+    const int blk0 = part_begin(split, T, S);
     const bf16x8 *Of = static_cast<const bf16x8 *>(m.Ofrag) + lane;
     const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
     bf16x8 *dl = reinterpret_cast<bf16x8 *>(lds);
@@ -166,8 +166,8 @@ __device__ __forceinline__ void outproj_stream_f32_body(const ModelDev &m, int B
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KS = m.Hp >> 4, GPB = KS / kStreamGroup32;
     const int T = m.Vp / 32;
-    const int blk1 = (int)(((long long)(split + 1) * T) / S);
-    const int blk0 = (int)(((long long)split * T) / S);
+    const int blk1 = part_begin(split + 1, T, S);
+    const int blk0 = part_begin(split, T, S);
     const f32x4 *Of = static_cast<const f32x4 *>(m.Ofrag) + lane;           // [blk][ks][2][64] x 16 bytes
     const float *cvec = FIXED ? m.cvec2_fixed : m.cvec2;
     bf16x8 *dl = reinterpret_cast<bf16x8 *>(lds);                           // [3 terms][RB][KS][64]

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(2 * WN * 64) void outproj_tiled_kernel(ModelDev m, 
     for (int item = local; item < items; item += wg_per_xcd) {
     const int rg = part * RGp + item % RGp, split = xcd / P + (kXcds / P) * (item / RGp);
     const int b0 = rg * C::kRows;
-    const int t_begin = (int)(((long long)split * ntiles) / S), t_end = (int)(((long long)(split + 1) * ntiles) / S);
+    const int t_begin = part_begin(split, ntiles, S), t_end = part_begin(split + 1, ntiles, S);
     const int nchunks = (t_end - t_begin) * nk;
     auto issue = [&](int chunk, int stage) {
         const int t = t_begin + chunk / nk, k0 = (chunk % nk) * kTK;

@@ -191,6 +191,15 @@ __host__ __device__ inline RowPlan plan_rows(int B, int group_rows, int wg_per_x
     p.S = kXcds * p.Sx;
     return p;
 }
+// First unit of part `index` when `units` units are cut into `parts` nearly equal parts,
+// floor(index * units / parts), for 0 <= index <= parts <= 256 and units < 2^31.  With q = units / parts
+// and r = units % parts this is index * q + floor(index * r / parts), and index * r stays below 2^16: 32-bit
+// arithmetic throughout (a 64-bit division costs a wave some hundred scalar instructions in front of
+// its first load).
+__host__ __device__ inline int part_begin(int index, int units, int parts) {
+    const unsigned q = (unsigned)units / (unsigned)parts, r = (unsigned)units % (unsigned)parts;
+    return (int)((unsigned)index * q + ((unsigned)index * r) / (unsigned)parts);
+}
 typedef RowPlan StagedPlan;
 __host__ __device__ inline StagedPlan staged_plan(int B, int wg_per_xcd) {
     return plan_rows(B, kStagedRows, wg_per_xcd, kMaxSplits / kXcds);

@@ -48,6 +48,15 @@ int main() {
         const StagedPlan p = staged_plan(B, 32);
         REQUIRE(p.RG == (B + kStagedRows - 1) / kStagedRows && p.S == kXcds * p.Sx, "staged B=%d", B);
     }
+    // cutting `units` blocks into `parts` splits: the 32-bit form equals floor(index * units / parts)
+    const int units_of[] = {1, 7, 63, 64, 255, 256, 257, 2048, 6250, 31251, 1 << 20, (1 << 25) + 3, 0x7FFFFFFF};
+    for (int units : units_of)
+        for (int parts = 1; parts <= kMaxSplits; ++parts)
+            for (int index = 0; index <= parts; ++index) {
+                const long long want = ((long long)index * units) / parts;
+                REQUIRE(part_begin(index, units, parts) == (int)want, "part_begin(%d, %d, %d) = %d, want %lld", index, units,
+                        parts, part_begin(index, units, parts), want);
+            }
     printf("ok\n");
     return 0;
 }
