@@ -79,7 +79,11 @@ enum rnnlm_option {
      * cached step turns out to have that few rows and their LDS holds them).  One launch
      * serves as many rows as fit its LDS (bf16: 128 up to H = 576, 64 up to H = 1216, 32 up to
      * H = 2432; fp32: 128 up to H = 192, 64 up to H = 384, 32 up to H = 768); on request it takes
-     * up to 128 rows in at most four launches, and larger batches go the automatic way.
+     * up to 128 rows in at most four launches, and larger batches go the automatic way,
+     * 6 = (bf16 models) the kernel that sends only the weights through
+     * LDS and takes the hidden rows straight into registers chunk by chunk: the automatic choice for
+     * H > 512 from 256 rows on when batch and vocabulary give every compute unit a 256 x 256 tile (with
+     * the running maximum it falls back to 3).
      * EINVAL if the model does not allow the choice. */
     RNNLM_OPT_OUTPROJ_KERNEL = 2
 };

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librnnlm.so")
-SOURCES = ["api.hip", "dedup.hip", "recur.hip", "outproj.hip", "outproj_staged.hip", "outproj_tiled.hip", "outproj_stream.hip", "outproj_split3.hip", "query.hip",
+SOURCES = ["api.hip", "dedup.hip", "recur.hip", "outproj.hip", "outproj_staged.hip", "outproj_tiled.hip", "outproj_stream.hip", "outproj_rowstream.hip", "outproj_split3.hip", "query.hip",
            "load_kernels.hip", "cache.hip", "index_table.hip", "hs.hip", "diag.hip"]
 HEADERS = [os.path.join(CSRC, "rnnlm_internal.h"), os.path.join(CSRC, "device_utils.h"),
            os.path.join(CSRC, "outproj_stream_body.h"), os.path.join(CSRC, "dedup_small_body.h"),

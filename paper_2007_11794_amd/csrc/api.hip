@@ -352,8 +352,9 @@ int rnnlm_set_option(rnnlm_model *model, int option, int value) {
             model->lse_mode = value;
             return RNNLM_OK;
         case RNNLM_OPT_OUTPROJ_KERNEL:
-            if (value < 0 || value > 5) return RNNLM_EINVAL;
+            if (value < 0 || value > 6) return RNNLM_EINVAL;
             if (model->dev.hs) return RNNLM_EINVAL;
+            if (value == 6 && !outproj_rowstream_supported(model->dev)) return RNNLM_EINVAL;
             if (value == 5 && outproj_stream_max_rows(model->dev) == 0) return RNNLM_EINVAL;
             if (value == 4 && !model->dev.Ot3) return RNNLM_EINVAL;
             if (value == 2 && !outproj_staged_supported(model->dev)) return RNNLM_EINVAL;

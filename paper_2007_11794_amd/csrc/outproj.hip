@@ -200,6 +200,9 @@ hipError_t launch_outproj_tiled(const ModelDev &m, int rows, const int *B_dev, b
 // defined in outproj_split3.hip
 hipError_t launch_outproj_split3(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                  SplitInfo *splits, hipStream_t stream);
+// defined in outproj_rowstream.hip
+hipError_t launch_outproj_rowstream(const ModelDev &m, int rows, const int *B_dev, SplitInfo *splits,
+                                    hipStream_t stream);
 // defined in outproj_stream.hip
 hipError_t launch_outproj_stream(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                                  SplitInfo *splits, hipStream_t stream);
@@ -223,7 +226,12 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
         if (stream_choice(m, rows, kernel_choice)) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
         const bool staged = kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128);
         if (staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
-        const bool tiled = kernel_choice == 3 || (kernel_choice == 0 && rows >= 64);
+        // hidden sizes beyond the staged kernel's, batches and vocabularies that give every compute unit a
+        // 256 x 256 tile, fixed offset: the hidden rows by-pass LDS (on request: any batch the model allows)
+        const bool big = rows >= 256 && (long long)((rows + 255) / 256) * (m.Vp / 256) >= 256;
+        if (fixed_offset && outproj_rowstream_supported(m) && (kernel_choice == 6 || (kernel_choice == 0 && big)))
+            return launch_outproj_rowstream(m, rows, B_dev, splits, stream);
+        const bool tiled = kernel_choice == 3 || kernel_choice == 6 || (kernel_choice == 0 && rows >= 64);
         if (tiled) return launch_outproj_tiled(m, rows, B_dev, fixed_offset, splits, stream);
         const int row_groups = (rows + 127) / 128, col_blocks = m.Vp / 32;
         int S = choose_splits(row_groups, col_blocks, 1024);

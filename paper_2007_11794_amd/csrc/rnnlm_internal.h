@@ -226,6 +226,7 @@ __host__ inline SplitInfo fixed_split_info(int S) { return SplitInfo{S, 0, 1, 1,
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream);
 bool outproj_staged_supported(const ModelDev &m);
+bool outproj_rowstream_supported(const ModelDev &m);   // bf16 models
 int outproj_stream_max_rows(const ModelDev &m);   // 0: the weight-streaming kernel cannot serve this model
 
 // Query gather: logprob[n][k] = z[row(n)][query[n][k]] - lse[row(n)] - base_score[n][k].

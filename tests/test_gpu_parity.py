@@ -82,7 +82,7 @@ def test_config2_chained_steps_full():
     (900, 1024, 50, 2),       # the longest reduction the streaming kernel takes two row blocks of
     (3000, 256, 127, 2),      # four row blocks (on request only)
 ])
-@pytest.mark.parametrize("kernel", [1, 2, 3, 5])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 5, 6])
 @pytest.mark.parametrize("lse_mode", [1, 2])
 def test_bf16_reduced_elementwise(V, H, B, K, kernel, lse_mode):
     cfg = CONFIGS[3].scaled(V=V, H=H, B=B, K=K)

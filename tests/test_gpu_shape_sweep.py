@@ -51,7 +51,8 @@ def test_shape(i, dtype, V, H, B, K):
     ref = oracle.step(model, prev, h_in, query, row_of_query=roq)
     Hp = max(128, -(-H // 64) * 64)                      # the staged kernel exists for padded sizes 128, 256, 512
     # 5: weight streaming where the rows fit (at most 128), else as 0
-    kernels = [0, 1, 3, 5] + ([2] if dtype == "bf16" and Hp in (128, 256, 512) else []) + ([4] if dtype == "f32" else [])
+    kernels = [0, 1, 3, 5] + ([2] if dtype == "bf16" and Hp in (128, 256, 512) else []) + ([4] if dtype == "f32" else []) + \
+              ([6] if dtype == "bf16" else [])
     for kernel in kernels:
         m.set_option(rn.OPT_OUTPROJ_KERNEL, kernel)
         for lse_mode in (0, 1):
