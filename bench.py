@@ -487,6 +487,24 @@ def main() -> int:
         roofline["sustained_probe"] = probe
         roofline["frac_of_sustained"] = round(achieved / probe["lds_feed_exp_random"]["tflops"], 4)
 
+    # what a kernel launch costs on this machine whatever the kernel does: an empty grouping call (N = 0: one
+    # thread writes one integer), back to back between two events; the same launches show up in a
+    # kernel trace as dedup_empty_kernel, the floor under every small kernel of the step
+    e_keys = torch.zeros(0, dtype=torch.int64, device=dev)
+    e_out = torch.zeros(1, dtype=torch.int32, device=dev)
+    for _ in range(10):
+        rn.rnnlm_dedup(e_keys, e_out, e_out, e_out, None)
+    floors = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(100):
+            rn.rnnlm_dedup(e_keys, e_out, e_out, e_out, None)
+        e1.record()
+        torch.cuda.synchronize()
+        floors.append(e0.elapsed_time(e1) / 100 * 1e3)
+    launch_floor_us = round(median(floors), 2)
+
     gemm_ref = None
     if args.gemm_reference and bf16:
         a = (torch.rand((B, H), device=dev) - 0.5).to(torch.bfloat16)
@@ -573,6 +591,7 @@ def main() -> int:
                                   cfg.dtype, cfg.sigma, cfg.zipf_s or 0),
                    "V": cfg.V, "H": cfg.H, "B": B, "N": cfg.N, "K": cfg.K},
         "timing": timing,
+        "launch_floor_us": launch_floor_us,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -32,6 +32,18 @@ bool use_fixed_offset(const rnnlm_model *m) {
     return m->fixed_ok != 0;
 }
 
+// The model as the hidden update sees it: a copy of the hidden block that the following kernel does not
+// read is not written (null pointer).  Full softmax: the row-ordered copy when the output projection
+// takes the fragment-ordered one (launch sized for `rows` rows); hierarchical layer: neither (the path
+// kernel reads h_out itself).
+ModelDev recur_view(const rnnlm_model *m, int rows) {
+    ModelDev v = m->dev;
+    if (v.dtype != RNNLM_BF16) return v;
+    if (v.hs) { v.d = nullptr; v.dfrag = nullptr; return v; }
+    if (!outproj_reads_row_order(v, rows, use_fixed_offset(m), m->outproj_kernel)) v.d = nullptr;
+    return v;
+}
+
 // What belongs to one handle alone: its scratch blocks, its flag, its events.
 void free_scratch(rnnlm_model *m) {
     ModelDev &d = m->dev;
@@ -404,7 +416,7 @@ int rnnlm_step(const rnnlm_model *model, int B, int K, const int32_t *prev_word,
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
     SplitInfo splits = fixed_split_info(1);
-    if (launch_recur(d, B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_recur(recur_view(model, B), B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
     if (launch_outproj(d, B, nullptr, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
         return RNNLM_EDEVICE;
     if (launch_query(d, B, nullptr, N, K, splits, query_word, row_of_query_or_null, h_out, nullptr, nullptr, logprob, s) !=
@@ -450,7 +462,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
     if (!cache) {
         if (N == 0) return RNNLM_OK;
         // Grids cover N rows; the kernels read the true number of rows from *n_unique.
-        if (launch_recur(d, N, n_unique, rep, nullptr, prev_word, h_in, h_out, s) != hipSuccess)
+        if (launch_recur(recur_view(model, N), N, n_unique, rep, nullptr, prev_word, h_in, h_out, s) != hipSuccess)
             return RNNLM_EDEVICE;
         if (launch_outproj(d, N, n_unique, use_fixed_offset(model), model->outproj_kernel, &splits, s) !=
             hipSuccess)
@@ -467,7 +479,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
     if (N == 0) return RNNLM_OK;
     // Only the histories the cache does not hold are computed: *c.n_miss rows, row r taken
     // from raw query c.miss_src[r], its hidden vector written to row c.miss_dst[r] of h_out.
-    if (launch_recur(d, N, c.n_miss, c.miss_src, c.miss_dst, prev_word, h_in, h_out, s) != hipSuccess)
+    if (launch_recur(recur_view(model, N), N, c.n_miss, c.miss_src, c.miss_dst, prev_word, h_in, h_out, s) != hipSuccess)
         return RNNLM_EDEVICE;
     if (launch_outproj(d, N, c.n_miss, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
         return RNNLM_EDEVICE;
@@ -598,7 +610,7 @@ int rnnlm_hs_step(const rnnlm_model *model, int B, int K, const int32_t *prev_wo
     if (B > 0 && ranges_overlap(h_in, h_out, (size_t)B * model->dev.H)) return RNNLM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const ModelDev &d = model->dev;
-    if (launch_recur(d, B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+    if (launch_recur(recur_view(model, B), B, nullptr, nullptr, nullptr, prev_word, h_in, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
     if (launch_hs_query(d, B, nullptr, N, K, query_word, row_of_query_or_null, h_out, base_score_or_null, logprob,
                         s) != hipSuccess)
         return RNNLM_EDEVICE;

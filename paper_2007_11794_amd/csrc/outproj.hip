@@ -218,21 +218,39 @@ static bool stream_choice(const ModelDev &m, int rows, int kernel_choice) {
     return kernel_choice == 0 && rows <= 64 && launches <= 2;
 }
 
+// Which bf16 kernel launch_outproj takes for a launch sized for `rows` rows.
+enum Bf16Kernel { kBf16Stream, kBf16Staged, kBf16RowStream, kBf16Tiled, kBf16Plain };
+static Bf16Kernel choose_bf16(const ModelDev &m, int rows, bool fixed_offset, int kernel_choice) {
+    if (stream_choice(m, rows, kernel_choice)) return kBf16Stream;
+    if (kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128)) return kBf16Staged;
+    // hidden sizes beyond the staged kernel's, batches and vocabularies that give every compute unit a
+    // 256 x 256 tile, fixed offset: the hidden rows by-pass LDS (on request: any batch the model allows)
+    const bool big = rows >= 256 && (long long)((rows + 255) / 256) * (m.Vp / 256) >= 256;
+    if (fixed_offset && outproj_rowstream_supported(m) && (kernel_choice == 6 || (kernel_choice == 0 && big)))
+        return kBf16RowStream;
+    if (kernel_choice == 3 || kernel_choice == 6 || (kernel_choice == 0 && rows >= 64)) return kBf16Tiled;
+    return kBf16Plain;
+}
+
+// Does the kernel launch_outproj will take read the row-ordered copy of the hidden block (m.d)?  The
+// weight-streaming, staged and row-streaming kernels read the fragment-ordered one (m.dfrag) only, also
+// when they fall back to weight streaming on the device; then the hidden update need not write m.d.
+bool outproj_reads_row_order(const ModelDev &m, int rows, bool fixed_offset, int kernel_choice) {
+    if (m.dtype != RNNLM_BF16) return true;
+    const Bf16Kernel k = choose_bf16(m, rows, fixed_offset, kernel_choice);
+    return k == kBf16Tiled || k == kBf16Plain;
+}
+
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream) {
     *splits = fixed_split_info(1);
     if (rows <= 0) return hipSuccess;
     if (m.dtype == RNNLM_BF16) {
-        if (stream_choice(m, rows, kernel_choice)) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
-        const bool staged = kernel_choice == 2 || (kernel_choice == 0 && outproj_staged_supported(m) && rows >= 128);
-        if (staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
-        // hidden sizes beyond the staged kernel's, batches and vocabularies that give every compute unit a
-        // 256 x 256 tile, fixed offset: the hidden rows by-pass LDS (on request: any batch the model allows)
-        const bool big = rows >= 256 && (long long)((rows + 255) / 256) * (m.Vp / 256) >= 256;
-        if (fixed_offset && outproj_rowstream_supported(m) && (kernel_choice == 6 || (kernel_choice == 0 && big)))
-            return launch_outproj_rowstream(m, rows, B_dev, splits, stream);
-        const bool tiled = kernel_choice == 3 || kernel_choice == 6 || (kernel_choice == 0 && rows >= 64);
-        if (tiled) return launch_outproj_tiled(m, rows, B_dev, fixed_offset, splits, stream);
+        const Bf16Kernel which = choose_bf16(m, rows, fixed_offset, kernel_choice);
+        if (which == kBf16Stream) return launch_outproj_stream(m, rows, B_dev, fixed_offset, splits, stream);
+        if (which == kBf16Staged) return launch_outproj_staged(m, rows, B_dev, fixed_offset, splits, stream);
+        if (which == kBf16RowStream) return launch_outproj_rowstream(m, rows, B_dev, splits, stream);
+        if (which == kBf16Tiled) return launch_outproj_tiled(m, rows, B_dev, fixed_offset, splits, stream);
         const int row_groups = (rows + 127) / 128, col_blocks = m.Vp / 32;
         int S = choose_splits(row_groups, col_blocks, 1024);
         int per = (col_blocks + S - 1) / S;

@@ -122,9 +122,10 @@ __global__ __launch_bounds__(256) void recur_bf16_kernel(
     uint2 dpk;
     dpk.x = pack_bf16x2(hp[0] - 0.5f, hp[1] - 0.5f);
     dpk.y = pack_bf16x2(hp[2] - 0.5f, hp[3] - 0.5f);
-    // padded units (zero weights, zero embedding) come out as sigmoid(0) - 1/2 = 0
-    *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
-    {   // the same four values in the fragment order of the staged output projection
+    // padded units (zero weights, zero embedding) come out as sigmoid(0) - 1/2 = 0; either copy of the
+    // block is left out (null pointer) when the kernel that follows does not read it
+    if (m.d) *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
+    if (m.dfrag) {   // the same four values in the fragment order of the staged output projection
         const size_t frag = (size_t)(b >> 5) * (Hp >> 4) + (je >> 4);
         const size_t at = (frag * 64 + ((je >> 3) & 1) * 32 + (b & 31)) * 8 + (je & 7);
         uint2 dsc;                                       // times log2(e): base-2 logits come out of the MFMAs
@@ -340,13 +341,16 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
         uint2 dpk;                                      // padded units come out as sigmoid(0) - 1/2 = 0
         dpk.x = pack_bf16x2(hp[0] - 0.5f, hp[1] - 0.5f);
         dpk.y = pack_bf16x2(hp[2] - 0.5f, hp[3] - 0.5f);
-        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
-        const size_t frag = (size_t)(b >> 5) * (Hp >> 4) + (je >> 4);
-        const size_t at = (frag * 64 + ((je >> 3) & 1) * 32 + (b & 31)) * 8 + (je & 7);
-        uint2 dsc;                                       // times log2(e): base-2 logits come out of the MFMAs
-        dsc.x = pack_bf16x2((hp[0] - 0.5f) * kLog2e, (hp[1] - 0.5f) * kLog2e);
-        dsc.y = pack_bf16x2((hp[2] - 0.5f) * kLog2e, (hp[3] - 0.5f) * kLog2e);
-        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dsc;
+        // either copy of the block is left out (null pointer) when the kernel that follows does not read it
+        if (m.d) *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.d) + (size_t)b * Hp + je) = dpk;
+        if (m.dfrag) {
+            const size_t frag = (size_t)(b >> 5) * (Hp >> 4) + (je >> 4);
+            const size_t at = (frag * 64 + ((je >> 3) & 1) * 32 + (b & 31)) * 8 + (je & 7);
+            uint2 dsc;                                   // times log2(e): base-2 logits come out of the MFMAs
+            dsc.x = pack_bf16x2((hp[0] - 0.5f) * kLog2e, (hp[1] - 0.5f) * kLog2e);
+            dsc.y = pack_bf16x2((hp[2] - 0.5f) * kLog2e, (hp[3] - 0.5f) * kLog2e);
+            *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(m.dfrag) + at) = dsc;
+        }
         if (je + 4 <= H) *reinterpret_cast<f32x4 *>(h_out + (size_t)bo * H + je) = f32x4{hp[0], hp[1], hp[2], hp[3]};
     }
 }
