@@ -30,12 +30,18 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E, published
 # launch that was timed is that kernel on that workload (otherwise "traffic" is null).
 TRAFFIC = {
     ("outproj_staged_kernel<512, true>", 3): (78.0e6, "profiles/step_kernels_cfg3_large_vocab_hbm_traffic.md"),
+    ("outproj_rowstream_kernel", 5): (1238.0e6, "profiles/outproj_rowstream_cfg5_stress_hbm_fetch.md"),
+    ("outproj_stream_kernel", 6): (260.3e6, "profiles/step_kernels_cfg6_paper_regime_kernel_trace.md"),
     ("outproj_stream_kernel", 2): (21.2e6, "profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md"),
     ("outproj_stream_kernel", 3): (67.8e6, "profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md"),
     ("outproj_stream_kernel", 5): (411.5e6, "profiles/outproj_stream_few_rows_kernel_trace_and_fetch.md"),
 }
-# The path kernel of the hierarchical output layer, by workload number (filled from profiles/).
-HS_TRAFFIC = {}
+# The path kernel of the hierarchical output layer, by workload number: HBM bytes per launch
+# (FETCH_SIZE + WRITE_SIZE, copy-calibrated).
+HS_TRAFFIC = {
+    3: (53.8e6, "profiles/hs_step_cfg3_shape_kernel_trace_and_traffic.md"),
+    6: (2.76e6, "profiles/hs_step_cfg6_paper_regime_kernel_trace_and_traffic.md"),
+}
 MIN_TIMED_REGION_S = 0.1         # the event-timed repetitions together last at least this long
 MIN_REPETITIONS = 20
 
@@ -443,12 +449,10 @@ def main() -> int:
     streamed = args.outproj_kernel in (0, 5) and ((bf16 and B <= 64 and cfg.H <= 1216) or
                                                   (not bf16 and B <= 32 and cfg.H <= 768))
     Hp = max(128 if bf16 else 64, -(-cfg.H // 64) * 64)
-    if streamed:
-        kernel_name = "outproj_stream_kernel"
-    elif bf16 and args.outproj_kernel in (0, 2) and Hp in (128, 256, 512) and B >= 128:
-        kernel_name = "outproj_staged_kernel<%d, %s>" % (Hp, "true" if args.lse_mode in (0, 2) else "false")
-    else:
-        kernel_name = "outproj_lse"
+    kernel_name = m.outproj_kernel_name(cfg.N)      # the library names the kernel it launches
+    if kernel_name == "outproj_staged_kernel":
+        kernel_name += "<%d, %s>" % (Hp, "true" if args.lse_mode in (0, 2) else "false")
+    assert streamed == (kernel_name == "outproj_stream_kernel"), (streamed, kernel_name)
     traffic, traffic_source = TRAFFIC.get((kernel_name, args.config if args.unique_frac is None else -1), (None, None))
     if args.rows is not None and not streamed:
         traffic, traffic_source = None, None
@@ -487,23 +491,9 @@ def main() -> int:
         roofline["sustained_probe"] = probe
         roofline["frac_of_sustained"] = round(achieved / probe["lds_feed_exp_random"]["tflops"], 4)
 
-    # what a kernel launch costs on this machine whatever the kernel does: an empty grouping call (N = 0: one
-    # thread writes one integer), back to back between two events; the same launches show up in a
-    # kernel trace as dedup_empty_kernel, the floor under every small kernel of the step
-    e_keys = torch.zeros(0, dtype=torch.int64, device=dev)
-    e_out = torch.zeros(1, dtype=torch.int32, device=dev)
-    for _ in range(10):
-        rn.rnnlm_dedup(e_keys, e_out, e_out, e_out, None)
-    floors = []
-    for _ in range(5):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(100):
-            rn.rnnlm_dedup(e_keys, e_out, e_out, e_out, None)
-        e1.record()
-        torch.cuda.synchronize()
-        floors.append(e0.elapsed_time(e1) / 100 * 1e3)
-    launch_floor_us = round(median(floors), 2)
+    # what a kernel launch costs on this machine whatever the kernel does (empty kernel, back to back between
+    # two events): the floor under every small kernel of the step
+    launch_floor_us = round(median([rn.rnnlm_time_empty_launch(1000) for _ in range(5)]), 2)
 
     gemm_ref = None
     if args.gemm_reference and bf16:

@@ -24,12 +24,25 @@ extern "C" {
 int rnnlm_time_outproj(const rnnlm_model *model, int B, const int32_t *n_rows_dev_or_null, int repeats,
                        void *hip_stream, float *ms_per_launch);
 
+/* Name (as a kernel trace shows it, without template arguments) of the kernel that a launch of the
+ * output projection sized for B rows takes on this model with its current options; a static string,
+ * NULL for a bad argument or a model with the hierarchical output layer. */
+const char *rnnlm_outproj_kernel_name(const rnnlm_model *model, int B);
+
 /* Only the path-evaluation kernel of rnnlm_hs_step (no hidden update) on
  * h_out as a step left it, `repeats` times back to back on `hip_stream` between HIP events on
  * that stream; mean time of one launch in milliseconds.  Synchronises the stream. */
 int rnnlm_hs_time_query(const rnnlm_model *model, int B, int K, const int32_t *query_word,
                         const int32_t *row_of_query_or_null, int N, const float *h_out, float *logprob,
                         int repeats, void *hip_stream, float *ms_per_launch);
+
+/*
+ * What a kernel launch costs on this device whatever the kernel does: `repeats` (1..100000) launches
+ * of an empty one-wave kernel back to back on `hip_stream` between two HIP events; mean time per
+ * launch in MICROseconds.  The floor under every small kernel of a step (the grouping of ids, the
+ * hidden update and the query gather of Table 1's RnnlmProb are such kernels).  Synchronises the stream.
+ */
+int rnnlm_time_empty_launch(int repeats, void *hip_stream, float *us_per_launch);
 
 /*
  * The rate the bf16 matrix cores of the current device

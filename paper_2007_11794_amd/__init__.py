@@ -8,7 +8,7 @@ from .binding import (RNNLM_BF16, RNNLM_F32, FLAG_BAD_PREV_WORD, FLAG_BAD_QUERY_
                       rnnlm_step_cached, rnnlm_pack_ids, RnnlmIndexTable, rnnlm_index_create,
                       rnnlm_index_intern, rnnlm_index_fetch, INDEX_NOT_STORED, INDEX_COLLISION,
                       rnnlm_huffman_build, rnnlm_hs_load, rnnlm_hs_step, rnnlm_hs_time_query,
-                      rnnlm_probe_mfma_rate)
+                      rnnlm_probe_mfma_rate, rnnlm_time_empty_launch)
 
 __all__ = ["RNNLM_BF16", "RNNLM_F32", "FLAG_BAD_PREV_WORD", "FLAG_BAD_QUERY_WORD", "FLAG_BAD_ROW",
            "OPT_LSE_MODE", "OPT_OUTPROJ_KERNEL", "RnnlmError", "RnnlmModel", "lib", "lib_path",
@@ -17,4 +17,4 @@ __all__ = ["RNNLM_BF16", "RNNLM_F32", "FLAG_BAD_PREV_WORD", "FLAG_BAD_QUERY_WORD
            "rnnlm_step_cached", "rnnlm_pack_ids", "RnnlmIndexTable", "rnnlm_index_create",
            "rnnlm_index_intern", "rnnlm_index_fetch", "INDEX_NOT_STORED", "INDEX_COLLISION",
            "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step", "rnnlm_hs_time_query",
-           "rnnlm_probe_mfma_rate"]
+           "rnnlm_probe_mfma_rate", "rnnlm_time_empty_launch"]

@@ -27,7 +27,7 @@ EXPORTS = ["rnnlm_strerror", "rnnlm_load", "rnnlm_free", "rnnlm_model_share", "r
            "rnnlm_cache_stats", "rnnlm_step_cached", "rnnlm_pack_ids", "rnnlm_index_create",
            "rnnlm_index_free", "rnnlm_index_reset", "rnnlm_index_intern", "rnnlm_index_fetch",
            "rnnlm_index_stats", "rnnlm_huffman_build", "rnnlm_hs_load", "rnnlm_hs_step", "rnnlm_hs_time_query",
-           "rnnlm_probe_mfma_rate"]
+           "rnnlm_probe_mfma_rate", "rnnlm_time_empty_launch", "rnnlm_outproj_kernel_name"]
 
 
 class RnnlmError(RuntimeError):
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.rnnlm_model_share.restype = I
         L.rnnlm_time_outproj.argtypes = [P, I, P, I, P, ctypes.POINTER(ctypes.c_float)]
         L.rnnlm_time_outproj.restype = I
+        L.rnnlm_time_empty_launch.argtypes = [I, P, ctypes.POINTER(ctypes.c_float)]
+        L.rnnlm_time_empty_launch.restype = I
+        L.rnnlm_outproj_kernel_name.argtypes = [P, I]
+        L.rnnlm_outproj_kernel_name.restype = ctypes.c_char_p
         L.rnnlm_probe_mfma_rate.argtypes = [I, I, I, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.rnnlm_probe_mfma_rate.restype = I
         L.rnnlm_cache_create.argtypes = [P, I, ctypes.POINTER(P)]
@@ -177,6 +181,13 @@ class RnnlmModel:
                                         ctypes.byref(ms)), "rnnlm_time_outproj")
         return ms.value
 
+    def outproj_kernel_name(self, B: int) -> str:
+        """Name of the kernel a launch of the output projection sized for B rows takes."""
+        name = lib().rnnlm_outproj_kernel_name(self.handle, int(B))
+        if name is None:
+            raise ValueError("rnnlm_outproj_kernel_name: bad argument")
+        return name.decode()
+
     def close(self):
         if self._h:
             h, self._h = self._h, None
@@ -187,6 +198,13 @@ class RnnlmModel:
             self.close()
         except Exception:
             pass
+
+
+def rnnlm_time_empty_launch(repeats: int = 1000, stream=None) -> float:
+    """Mean time of one launch of an empty kernel, back to back on the stream, in microseconds."""
+    us = ctypes.c_float()
+    _check(lib().rnnlm_time_empty_launch(int(repeats), _stream(stream), ctypes.byref(us)), "rnnlm_time_empty_launch")
+    return float(us.value)
 
 
 def rnnlm_probe_mfma_rate(feed: int, data: int, launches: int = 20):

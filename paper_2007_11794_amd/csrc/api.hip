@@ -737,6 +737,11 @@ int rnnlm_pack_ids(const uint32_t *ctx_idx, const uint32_t *small_lm_idx, int N,
                : RNNLM_EDEVICE;
 }
 
+const char *rnnlm_outproj_kernel_name(const rnnlm_model *model, int B) {
+    if (!model || B <= 0 || B > model->max_B || model->dev.hs) return nullptr;
+    return outproj_kernel_name(model->dev, B, use_fixed_offset(model), model->outproj_kernel);
+}
+
 int rnnlm_time_outproj(const rnnlm_model *model, int B, const int32_t *n_rows_dev, int repeats, void *hip_stream,
                        float *ms_per_launch) {
     if (!model || !ms_per_launch || repeats <= 0 || B <= 0 || model->dev.hs) return RNNLM_EINVAL;

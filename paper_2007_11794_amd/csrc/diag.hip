@@ -102,6 +102,32 @@ struct ProbeBuffers {
 
 using namespace rnnlm;
 
+namespace {
+__global__ void empty_kernel(int *sink) {
+    if (sink && threadIdx.x == 12345) *sink = 0;             // never true: the kernel does nothing
+}
+}  // namespace
+
+extern "C" int rnnlm_time_empty_launch(int repeats, void *hip_stream, float *us_per_launch) {
+    if (repeats <= 0 || repeats > 100000 || !us_per_launch) return RNNLM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess) return RNNLM_EDEVICE;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return RNNLM_EDEVICE; }
+    int status = RNNLM_OK;
+    float ms = 0.f;
+    for (int i = 0; i < 10; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, s, nullptr);      // warm-up
+    if (hipEventRecord(e0, s) != hipSuccess) status = RNNLM_EDEVICE;
+    for (int i = 0; i < repeats && status == RNNLM_OK; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, s, nullptr);
+    if (status == RNNLM_OK && (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                               hipGetLastError() != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+        status = RNNLM_EDEVICE;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (status == RNNLM_OK) *us_per_launch = ms * 1e3f / (float)repeats;
+    return status;
+}
+
 extern "C" int rnnlm_probe_mfma_rate(int feed, int data, int launches, double *tflops, double *core_ghz) {
     if ((feed != 0 && feed != 1) || (data != 0 && data != 1) || launches <= 0 || launches > 1000 || !tflops)
         return RNNLM_EINVAL;

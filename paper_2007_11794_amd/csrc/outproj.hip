@@ -241,6 +241,23 @@ bool outproj_reads_row_order(const ModelDev &m, int rows, bool fixed_offset, int
     return k == kBf16Tiled || k == kBf16Plain;
 }
 
+// The kernel launch_outproj takes for these arguments, by the name a kernel trace shows.
+const char *outproj_kernel_name(const ModelDev &m, int rows, bool fixed_offset, int kernel_choice) {
+    if (m.dtype == RNNLM_BF16) {
+        switch (choose_bf16(m, rows, fixed_offset, kernel_choice)) {
+            case kBf16Stream: return "outproj_stream_kernel";
+            case kBf16Staged: return "outproj_staged_kernel";
+            case kBf16RowStream: return "outproj_rowstream_kernel";
+            case kBf16Tiled: return "outproj_tiled_kernel";
+            default: return "outproj_plain_bf16_kernel";
+        }
+    }
+    if (stream_choice(m, rows, kernel_choice)) return "outproj_stream_kernel";
+    if (kernel_choice == 3) return "outproj_tiled_kernel";
+    if (m.Ot3 && (kernel_choice == 4 || (kernel_choice == 0 && rows >= 64))) return "outproj_split3_kernel";
+    return "outproj_plain_f32_kernel";
+}
+
 hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fixed_offset,
                           int kernel_choice, SplitInfo *splits, hipStream_t stream) {
     *splits = fixed_split_info(1);

@@ -228,6 +228,7 @@ hipError_t launch_outproj(const ModelDev &m, int rows, const int *B_dev, bool fi
 // false: the kernel launch_outproj takes for these arguments reads only the fragment-ordered copy of
 // the hidden block, and the hidden update may leave the row-ordered one (m.d) unwritten
 bool outproj_reads_row_order(const ModelDev &m, int rows, bool fixed_offset, int kernel_choice);
+const char *outproj_kernel_name(const ModelDev &m, int rows, bool fixed_offset, int kernel_choice);
 bool outproj_staged_supported(const ModelDev &m);
 bool outproj_rowstream_supported(const ModelDev &m);   // bf16 models
 int outproj_stream_max_rows(const ModelDev &m);   // 0: the weight-streaming kernel cannot serve this model

@@ -78,6 +78,11 @@ def test_host_checked_errors_return_before_any_device_work():
     assert L.rnnlm_dedup_static(None, 4, p, p, p, None) == EINVAL
     assert L.rnnlm_dedup_static(p, 4, p, p, None, None) == EINVAL
     assert L.rnnlm_dedup_static(p, 65537, p, p, p, None) == ERANGE
+    us = ctypes.c_float()
+    assert L.rnnlm_time_empty_launch(0, None, ctypes.byref(us)) == EINVAL
+    assert L.rnnlm_time_empty_launch(10, None, None) == EINVAL
+    L.rnnlm_outproj_kernel_name.restype = ctypes.c_char_p
+    assert L.rnnlm_outproj_kernel_name(None, 4) is None
     tf = ctypes.c_double()
     assert L.rnnlm_probe_mfma_rate(2, 0, 1, ctypes.byref(tf), None) == EINVAL
     assert L.rnnlm_probe_mfma_rate(0, -1, 1, ctypes.byref(tf), None) == EINVAL
