@@ -129,7 +129,11 @@ int oracle_step(int V, int H, int B, int K, int N,
 #pragma omp parallel for schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
         double *z = (double *)malloc((size_t)V * sizeof(double));
-        if (!z) { bad = 1; continue; }
+        if (!z) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
         double *h = h_out + (size_t)b * H;
         hidden_row(H, U + (size_t)prev[b] * H, W, h_in + (size_t)b * H, h);
         logits_row(V, H, O, bias, h, z);
