@@ -100,12 +100,69 @@ constexpr int kHsTable = 2048;                       // slots of the node table 
 constexpr int kHsMaxK = 256;
 constexpr int kHsThreads = 256;
 
+// Dot products of the distinct nodes for a short hidden vector (Hp = 8 * LPR elements, LPR = 16 or
+// 32): a node row takes only LPR lanes of a wave, so the wave works on 64 / LPR rows side by side,
+// eight per lane group in flight: 32 (16) rows per wave and round trip to memory instead of 8.  Lane
+// group g of wave w takes the nodes d = first + g + G * u, u = 0..7; the eight sums of a group are
+// reduced together (a lane passes on the half it will not finish, as in wave_sum8).
+template <typename T, int LPR>
+__device__ __forceinline__ void hs_dots_short_rows(const T *Theta, const float *hrow, int H, int Hp, bool vec_ok,
+                                                   const int *dnode, float *dx, int D, int wave, int lane) {
+    static_assert(LPR == 16 || LPR == 32, "");
+    constexpr int G = 64 / LPR, kPerWave = G * kHsBatch;
+    const int g = lane / LPR, sl = lane % LPR, j0 = sl * 8;
+    float h8[8];
+    load8_row(hrow, j0, H, vec_ok, 0.f, h8);
+    constexpr int top = LPR / 2;                           // 8 or 16
+    const bool upa = (lane & top) != 0, upb = (lane & (top / 2)) != 0, upc = (lane & (top / 4)) != 0;
+    const int u_mine = (upa ? 4 : 0) + (upb ? 2 : 0) + (upc ? 1 : 0);
+    const bool writer = (lane & (top / 4 - 1)) == 0;
+    auto fetch = [&](int first, float (&w8)[kHsBatch][8]) {
+#pragma unroll
+        for (int u = 0; u < kHsBatch; ++u) {
+            const int d = first + g + G * u;
+            const int node = d < D ? dnode[d] : 0;
+            load8_weights(Theta, (size_t)node * Hp + j0, w8[u]);
+        }
+    };
+    auto finish = [&](int first, const float (&w8)[kHsBatch][8]) {
+        float acc[kHsBatch];
+#pragma unroll
+        for (int u = 0; u < kHsBatch; ++u) {
+            acc[u] = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[u] = fmaf(w8[u][i], h8[i], acc[u]);
+        }
+        // three levels that halve the number of values a lane carries, then the rest of the butterfly
+        float v4[4], v2[2];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v4[i] = (upa ? acc[4 + i] : acc[i]) + __shfl_xor(upa ? acc[i] : acc[4 + i], top, 64);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) v2[i] = (upb ? v4[2 + i] : v4[i]) + __shfl_xor(upb ? v4[i] : v4[2 + i], top / 2, 64);
+        float v = (upc ? v2[1] : v2[0]) + __shfl_xor(upc ? v2[0] : v2[1], top / 4, 64);
+#pragma unroll
+        for (int step = top / 8; step >= 1; step >>= 1) v += __shfl_xor(v, step, 64);
+        const int d = first + g + G * u_mine;
+        if (writer && d < D) dx[d] = v;
+    };
+    // two batches on their way at a time (the second may lie past the end: its loads fetch node 0)
+    constexpr int stride = (kHsThreads / 64) * kPerWave;
+    for (int first = wave * kPerWave; first < D; first += 2 * stride) {
+        float wa[kHsBatch][8], wb[kHsBatch][8];
+        fetch(first, wa);
+        fetch(first + stride, wb);
+        finish(first, wa);
+        finish(first + stride, wb);
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K,
     const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
     const float *__restrict__ h_out, const float *__restrict__ base_score, float *__restrict__ logprob) {
     __shared__ int wbase[kHsMaxK + 1];               // start of word k's entries
+    __shared__ int woff[kHsMaxK];                    // where word k's path starts in the model's entries
     __shared__ uint16_t eslot[kHsMaxEntries];        // entry -> table slot of its node | code bit << 15
     __shared__ int tnode[kHsTable];                  // hash table: node (-1 free)
     __shared__ uint16_t tidx[kHsTable];              // slot -> index of its node among the distinct ones
@@ -126,7 +183,9 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     if (tid < K) {
         const int q_raw = query_word[(size_t)n * K + tid];
         const int q = (q_raw >= 0 && q_raw < m.V) ? q_raw : 0;
-        len = m.path_off[q + 1] - m.path_off[q];
+        const int o = m.path_off[q];
+        len = m.path_off[q + 1] - o;
+        woff[tid] = o;
     }
     for (int i = tid; i < kHsTable; i += kHsThreads) tnode[i] = -1;
     if (tid == 0) dcount = 0;
@@ -135,15 +194,29 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     if (tid < K) wbase[tid] = mybase;
     if (tid == 0) wbase[K] = total;
     __syncthreads();
-    // 2. distinct nodes (a wave per word, lanes along the path): the lane whose insertion claims
+    // 2. distinct nodes (a thread per path entry, all entries of a thread requested before the first
+    //    is used: one round trip to memory for the whole query): the thread whose insertion claims
     //    a slot numbers the node; every entry remembers its slot and its code bit
-    for (int k = wave; k < K; k += kHsThreads / 64) {
-        const int qk = query_word[(size_t)n * K + k];
-        const int qs = (qk >= 0 && qk < m.V) ? qk : 0;
-        const int o = m.path_off[qs], b0 = wbase[k], l = wbase[k + 1] - b0;
-        for (int i = lane; i < l; i += 64) {
-            const uint32_t entry = (uint32_t)m.path_entry[o + i];
-            const int node = (int)(entry & 0x7FFFFFFFu);
+    constexpr int kPerThread = kHsMaxEntries / kHsThreads;
+    uint32_t entry[kPerThread];
+#pragma unroll
+    for (int c = 0; c < kPerThread; ++c) {
+        const int e = tid + c * kHsThreads;
+        entry[c] = 0u;
+        if (e < total) {
+            int lo = 0, hi = K;                                      // the word k with wbase[k] <= e < wbase[k + 1]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (wbase[mid] <= e) lo = mid; else hi = mid;
+            }
+            entry[c] = (uint32_t)m.path_entry[woff[lo] + (e - wbase[lo])];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < kPerThread; ++c) {
+        const int e = tid + c * kHsThreads;
+        if (e < total) {
+            const int node = (int)(entry[c] & 0x7FFFFFFFu);
             uint32_t h = (uint32_t)(node * 0x9E3779B1u) >> 21;       // 11 bits
             for (int probe = 0; probe < kHsTable; ++probe) {
                 const int old = atomicCAS(&tnode[h], -1, node);
@@ -156,7 +229,7 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
                 if (old == node) break;
                 h = (h + 1) & (kHsTable - 1);
             }
-            eslot[b0 + i] = (uint16_t)(h | ((entry >> 31) << 15));
+            eslot[e] = (uint16_t)(h | ((entry[c] >> 31) << 15));
         }
     }
     __syncthreads();
@@ -166,6 +239,9 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     const float *hrow = h_out + (size_t)r * H;
     const bool vec_ok = (H % 4) == 0;
     const int umine = batch_slot_of_lane(lane);
+    if (Hp == 128) hs_dots_short_rows<T, 16>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
+    else if (Hp == 256) hs_dots_short_rows<T, 32>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
+    else
     for (int d0 = wave * kHsBatch; d0 < D; d0 += (kHsThreads / 64) * kHsBatch) {
         const int node_mine = (d0 + umine < D) ? dnode[d0 + umine] : 0;
         int node[kHsBatch];
@@ -189,17 +265,28 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
         if ((lane & 7) == 0 && d0 + umine < D) dx[d0 + umine] = x;
     }
     __syncthreads();
-    // 4. log sigmoid along each path (a wave per word, lanes along the path)
-    for (int k = wave; k < K; k += kHsThreads / 64) {
-        const int b0 = wbase[k], l = wbase[k + 1] - b0;
-        float t = 0.f;
-        for (int i = lane; i < l; i += 64) {
-            const uint32_t es = eslot[b0 + i];
+    // 4. log sigmoid of every path entry (a thread per entry; the terms go where the node table was,
+    //    which nobody has probed since step 2), then eight lanes add up the terms of one word
+    float *const eterm = reinterpret_cast<float *>(tnode);
+    static_assert(kHsMaxEntries <= kHsTable, "the terms fit the node table");
+#pragma unroll
+    for (int c = 0; c < kPerThread; ++c) {
+        const int e = tid + c * kHsThreads;
+        if (e < total) {
+            const uint32_t es = eslot[e];
             const float x = dx[tidx[es & 0x7FFFu]];
-            t += log_sigmoid_f32((es >> 15) ? -x : x);
+            eterm[e] = log_sigmoid_f32((es >> 15) ? -x : x);
         }
-        t = wave_sum(t);
-        if (lane == 0) {
+    }
+    __syncthreads();
+    for (int k = tid >> 3; k < K; k += kHsThreads / 8) {
+        const int b0 = wbase[k], b1 = wbase[k + 1];
+        float t = 0.f;
+        for (int e = b0 + (tid & 7); e < b1; e += 8) t += eterm[e];
+        t += __shfl_xor(t, 4, 64);
+        t += __shfl_xor(t, 2, 64);
+        t += __shfl_xor(t, 1, 64);
+        if ((tid & 7) == 0) {
             const int qk = query_word[(size_t)n * K + k];
             const bool ok = qk >= 0 && qk < m.V;
             const size_t at = (size_t)n * K + k;
