@@ -40,7 +40,7 @@ TRAFFIC = {
 # (FETCH_SIZE + WRITE_SIZE, copy-calibrated).
 HS_TRAFFIC = {
     3: (53.8e6, "profiles/hs_step_cfg3_shape_kernel_trace_and_traffic.md"),
-    6: (2.76e6, "profiles/hs_step_cfg6_paper_regime_kernel_trace_and_traffic.md"),
+    6: (2.83e6, "profiles/hs_step_cfg6_paper_regime_kernel_trace_and_traffic.md"),
 }
 MIN_TIMED_REGION_S = 0.1         # the event-timed repetitions together last at least this long
 MIN_REPETITIONS = 20
