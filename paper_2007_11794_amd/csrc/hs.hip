@@ -156,7 +156,9 @@ __device__ __forceinline__ void hs_dots_short_rows(const T *Theta, const float *
     }
 }
 
-template <typename T>
+// LPR: lanes per node row of the short-row form (16: Hp = 128, 32: Hp = 256), 0: any hidden size.
+// Kernels of their own, so that the registers of the short-row form do not cost the general one occupancy.
+template <typename T, int LPR>
 __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K,
     const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
@@ -239,8 +241,7 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     const float *hrow = h_out + (size_t)r * H;
     const bool vec_ok = (H % 4) == 0;
     const int umine = batch_slot_of_lane(lane);
-    if (Hp == 128) hs_dots_short_rows<T, 16>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
-    else if (Hp == 256) hs_dots_short_rows<T, 32>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
+    if constexpr (LPR != 0) hs_dots_short_rows<T, LPR>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
     else
     for (int d0 = wave * kHsBatch; d0 < D; d0 += (kHsThreads / 64) * kHsBatch) {
         const int node_mine = (d0 + umine < D) ? dnode[d0 + umine] : 0;
@@ -308,12 +309,19 @@ hipError_t launch_hs_query(const ModelDev &m, int rows, const int *B_dev, int N,
     if (N <= 0 || K <= 0) return hipSuccess;
     if (K >= 4 && K <= kHsMaxK && (long long)K * m.hs_max_len <= kHsMaxEntries) {
         // several words per query: one workgroup per raw query, shared path nodes computed once
-        if (m.dtype == RNNLM_BF16)
-            hipLaunchKernelGGL(hs_query_shared_kernel<bf16_t>, dim3(N), dim3(kHsThreads), 0, stream, m, rows, B_dev, N, K,
-                               query_word, row_of_query, h_out, base_score, logprob);
-        else
-            hipLaunchKernelGGL(hs_query_shared_kernel<float>, dim3(N), dim3(kHsThreads), 0, stream, m, rows, B_dev, N, K,
-                               query_word, row_of_query, h_out, base_score, logprob);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, dim3(N), dim3(kHsThreads), 0, stream, m, rows, B_dev, N, K, query_word,
+                               row_of_query, h_out, base_score, logprob);
+        };
+        if (m.dtype == RNNLM_BF16) {
+            if (m.Hp == 128) launch(hs_query_shared_kernel<bf16_t, 16>);
+            else if (m.Hp == 256) launch(hs_query_shared_kernel<bf16_t, 32>);
+            else launch(hs_query_shared_kernel<bf16_t, 0>);
+        } else {
+            if (m.Hp == 128) launch(hs_query_shared_kernel<float, 16>);
+            else if (m.Hp == 256) launch(hs_query_shared_kernel<float, 32>);
+            else launch(hs_query_shared_kernel<float, 0>);
+        }
         return hipGetLastError();
     }
     const long long pairs = (long long)N * K;

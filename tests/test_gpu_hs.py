@@ -52,6 +52,9 @@ def gpu_hs_step(mod, prev, h_in, query, row_of_query=None, base=None):
     ("bf16", 2, 64, 5, 2, 5),                # the smallest tree
     ("f32", 3001, 96, 64, 9, 64),
     ("f32", 20000, 256, 256, 16, 256),       # config 2's shape
+    ("bf16", 3000, 250, 40, 12, 90),         # half a wave per node row (hidden size padded to 256)
+    ("bf16", 3001, 128, 33, 32, 33),         # a quarter wave per node row, more than one batch of nodes
+    ("f32", 2999, 128, 20, 40, 50),
 ])
 def test_hs_step_matches_the_oracle(dtype, V, H, B, K, N):
     rng = np.random.default_rng(V + H)
