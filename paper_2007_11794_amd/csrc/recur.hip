@@ -176,17 +176,12 @@ template <int TB> struct RtCfg {
 // between two barriers instead of two, which is what the single wave per SIMD needs to hide
 // the LDS and matrix latencies.
 template <int NS, int TB, int SUB>
-__global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
-    ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
+__device__ __forceinline__ void recur_bf16_tiled_body(
+    const ModelDev &m, int B, const int32_t *__restrict__ row_src,
     const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
-    float *__restrict__ h_out, int b_min, int b_max) {
+    float *__restrict__ h_out) {
     using C = RtCfg<TB>;
     constexpr bool kSplitK = TB == 32;
-    // When only the device knows the row count, both shapes are launched and the count picks one:
-    // the launch whose range the count is not in sees no rows.  (Folded into B, not a branch of
-    // its own: a branch here would put two more dependent scalar loads in front of everything.)
-    const int B_true = B_dev ? *B_dev : rows;
-    const int B = (B_true < b_min || B_true > b_max) ? 0 : B_true;
     // Workgroup id modulo 8 is the XCD (L2 domain).  Row block rb runs on XCD rb % 8 with all
     // its unit blocks, so h_in (the larger operand) is fetched into one L2 only.
     const int JB = m.Hp / kRtTile;
@@ -355,6 +350,30 @@ __global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
     }
 }
 
+template <int NS, int TB, int SUB>
+__global__ __launch_bounds__(256) void recur_bf16_tiled_kernel(
+    ModelDev m, int rows, const int *__restrict__ B_dev, const int32_t *__restrict__ row_src,
+    const int32_t *__restrict__ row_dst, const int32_t *__restrict__ prev_word, const float *__restrict__ h_in,
+    float *__restrict__ h_out, int b_min, int b_max, int small_upto) {
+    // When only the device knows the row count, both shapes are launched and the count picks one:
+    // the launch whose range the count is not in sees no rows.  (Folded into B, not a branch of
+    // its own: a branch here would put two more dependent scalar loads in front of everything.)
+    const int B_true = B_dev ? *B_dev : rows;
+    const int B = (B_true < b_min || B_true > b_max) ? 0 : B_true;
+    if constexpr (TB == 64) {
+        // A launch of the large shape sized for a bound far above the true count (a step most of whose
+        // histories were found in the cache) would leave a handful of workgroups with 192 KB each to pull
+        // in.  Up to small_upto rows the same workgroups take 32 rows each instead (the small shape's
+        // body in this launch's LDS: three stages of 16 KB), twice as many of them at work.
+        static_assert(2 * RtCfg<64>::kStageBytes == 3 * RtCfg<32>::kStageBytes, "the small body's stages fit this launch's LDS");
+        if (B <= small_upto) {                            // uniform
+            recur_bf16_tiled_body<3, 32, 1>(m, B, row_src, row_dst, prev_word, h_in, h_out);
+            return;
+        }
+    }
+    recur_bf16_tiled_body<NS, TB, SUB>(m, B, row_src, row_dst, prev_word, h_in, h_out);
+}
+
 // ----------------------------------------------------------------------------- fp32 / MFMA
 // Same shape as the bf16 kernel (32 x 32 block per workgroup, reduction length split over the
 // four waves, all loads of a wave in flight together), with the full-precision fp32 matrix
@@ -487,19 +506,22 @@ hipError_t launch_recur(const ModelDev &m, int rows, const int *B_dev, const int
         const int small_max = 32 * (256 / units);       // most rows the small shape is chosen for
         auto launch_big = [&](int b_min) {
             const int big_blocks = (rows + 63) / 64;
-            dim3 grid(kXcds * ((big_blocks + kXcds - 1) / kXcds) * units);
+            const int slots = kXcds * ((big_blocks + kXcds - 1) / kXcds);   // row blocks the grid has workgroups for
+            dim3 grid(slots * units);
+            // true counts up to here are served 32 rows per workgroup (see the kernel)
+            const int small_upto = B_dev ? std::min(small_max, 32 * slots) : 0;
             hipLaunchKernelGGL((recur_bf16_tiled_kernel<2, 64, 1>), grid, dim3(256), 2 * RtCfg<64>::kStageBytes, stream,
-                               m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, b_min, INT_MAX);
+                               m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, b_min, INT_MAX, small_upto);
         };
         auto launch_small = [&](int upto) {             // grid for `upto` rows
             const int small_blocks = (upto + 31) / 32;
             dim3 grid(kXcds * ((small_blocks + kXcds - 1) / kXcds) * units);
             if (m.Hp % 128 == 0)
                 hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32, 2>), grid, dim3(256), 8 * RtCfg<32>::kStageBytes,
-                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, 0, upto);
+                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, 0, upto, 0);
             else
                 hipLaunchKernelGGL((recur_bf16_tiled_kernel<4, 32, 1>), grid, dim3(256), 4 * RtCfg<32>::kStageBytes,
-                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, 0, upto);
+                                   stream, m, rows, B_dev, row_src, row_dst, prev_word, h_in, h_out, 0, upto, 0);
         };
         if (rows <= small_max) {
             launch_small(rows);

@@ -178,7 +178,12 @@ def test_config3_model_few_rows_full_vocabulary():
                                             (2000, 640, 500, 10),       # 128 x 256 tiles; more workgroups than 32-word blocks
                                             (2000, 640, 500, 50),       # ... two row blocks streamed
                                             (3000, 1024, 700, 25),      # hidden update: both shapes launched, the small one works
-                                            (3000, 1024, 700, 600)])    # ... the large one works
+                                            (3000, 1024, 700, 600),     # ... the large one works
+                                            (3000, 512, 1500, 40),      # hidden update: large launch, 32 rows per workgroup after all
+                                            (3000, 512, 1500, 700),     # ... up to the row blocks the grid has workgroups for (768)
+                                            (3000, 512, 1500, 800),     # ... beyond: 64 rows per workgroup
+                                            (3000, 768, 900, 500),
+                                            (3000, 768, 900, 600)])
 def test_many_raw_queries_few_distinct_histories(V, H, N, distinct):
     """The search repeats itself (Section 5.2): N raw queries, a handful of distinct histories.  The
     host sizes the launch for N rows; the kernel learns the true count on the device and streams
