@@ -417,8 +417,8 @@ __global__ __launch_bounds__(256) void recur_f32_kernel(
     const int kq = Hp / 4;                           // this wave's share of k (a multiple of 16)
     const int k_begin = wave * kq + 4 * g, k_end = (wave + 1) * kq;
     f32x16 acc = {0};
-    for (int kb = k_begin; kb < k_end; kb += 8 * kRecurGroups) {
-        f32x4 wf[kRecurGroups], hf[kRecurGroups];
+    f32x4 wf[kRecurGroups], hf[kRecurGroups];
+    auto request = [&](int kb) {
 #pragma unroll
         for (int u = 0; u < kRecurGroups; ++u) {
             const int k0 = kb + 8 * u;
@@ -427,6 +427,8 @@ __global__ __launch_bounds__(256) void recur_f32_kernel(
                 hf[u] = row_ok ? load4_row(hrow, k0, H, vec_ok, 0.5f) : f32x4{0.5f, 0.5f, 0.5f, 0.5f};
             }
         }
+    };
+    auto multiply = [&](int kb) {
 #pragma unroll
         for (int u = 0; u < kRecurGroups; ++u) {
             const int k0 = kb + 8 * u;
@@ -436,9 +438,17 @@ __global__ __launch_bounds__(256) void recur_f32_kernel(
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wf[u][e], hf[u][e] - 0.5f, acc, 0, 0, 0);
             }
         }
-    }
+    };
+    // The embedding row hangs on the previous word, one round trip behind the operands of the first
+    // groups: requested right after them, it is on its way while the matrix instructions run.
+    request(k_begin);
     const bool w_ok = (w >= 0 && w < m.V);
     const f32x4 u4 = *reinterpret_cast<const f32x4 *>(U + (size_t)(w_ok ? w : 0) * Hp + je);
+    multiply(k_begin);
+    for (int kb = k_begin + 8 * kRecurGroups; kb < k_end; kb += 8 * kRecurGroups) {
+        request(kb);
+        multiply(kb);
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q)
         red[wave][q][lane] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
