@@ -51,6 +51,8 @@ def _load():
         lib.oracle_cache_stats.restype = None
         lib.oracle_step_cached.argtypes = [P, I, I, I, I] + [P] * 15 + [I]
         lib.oracle_step_cached.restype = I
+        lib.oracle_hs_step_cached.argtypes = [P, I, I, I, I] + [P] * 15
+        lib.oracle_hs_step_cached.restype = I
         lib.oracle_pack_ids.argtypes = [P, P, I, P]
         lib.oracle_pack_ids.restype = None
         lib.oracle_huffman_build.argtypes = [I, P, P, P, ctypes.c_longlong]
@@ -192,6 +194,42 @@ def step_cached(model: dict, cache: Optional[Cache], ids, prev, h_in, query, bas
     return {"n_unique": rc, "rep": rep[:rc].copy(), "inverse": inverse[:N].copy(),
             "h_out": h_out[:rc].copy(), "lse": lse[:rc].copy(), "score": score,
             "stats": tuple(int(x) for x in stats)}
+
+
+def hs_step_cached(model: dict, cache: Optional[Cache], ids, prev, h_in, query, base_score=None) -> dict:
+    """step_cached for a model with the hierarchical output layer (model as in hs_step): returns
+    n_unique, rep, inverse, float64 h_out[n_unique,H], score[N,K] and stats = (distinct, hits,
+    computed, entries)."""
+    U = _c(model["U"], np.float32)
+    W = _c(model["W"], np.float32)
+    theta = _c(model["theta"], np.float32)
+    off = _c(model["path_off"], np.int32)
+    entry = _c(model["path_entry"], np.int32)
+    V, H = U.shape
+    assert W.shape == (H, H) and theta.shape == (V - 1, H) and off.shape == (V + 1,)
+    ids = _c(ids, np.uint64)
+    prev = _c(prev, np.int32)
+    h_in = _c(h_in, np.float32)
+    query = _c(query, np.int32)
+    N, K = query.shape
+    assert ids.shape == (N,) and prev.shape == (N,) and h_in.shape == (N, H)
+    if base_score is not None:
+        base_score = _c(base_score, np.float32)
+        assert base_score.shape == (N, K)
+    n1 = max(N, 1)
+    rep = np.zeros(n1, dtype=np.int32)
+    inverse = np.zeros(n1, dtype=np.int32)
+    h_out = np.zeros((n1, H), dtype=np.float64)
+    score = np.zeros((N, K), dtype=np.float64)
+    stats = np.zeros(4, dtype=np.int32)
+    rc = _load().oracle_hs_step_cached(cache._h if cache is not None else None, V, H, N, K, _ptr(U), _ptr(W),
+                                       _ptr(theta), _ptr(off), _ptr(entry), _ptr(ids), _ptr(prev), _ptr(h_in),
+                                       _ptr(query), _ptr(base_score), _ptr(rep), _ptr(inverse), _ptr(h_out),
+                                       _ptr(score), _ptr(stats))
+    if rc < 0:
+        raise ValueError("oracle_hs_step_cached failed (%d)" % rc)
+    return {"n_unique": rc, "rep": rep[:rc].copy(), "inverse": inverse[:N].copy(), "h_out": h_out[:rc].copy(),
+            "score": score, "stats": tuple(int(x) for x in stats)}
 
 
 def pack_ids(ctx, small_lm) -> np.ndarray:

@@ -587,6 +587,75 @@ int oracle_hs_step(int V, int H, int B, int K, int N,
     return 0;
 }
 
+/*
+ * Table 1 as the paper runs it: RnnlmProb with its cache (Sections 3.2, 4.2) around a ComputeRnnlm
+ * whose output layer is the hierarchical one (Section 2.1).  The walk over the raw queries is that
+ * of oracle_step_cached; what a history's answers are made of is its updated hidden vector alone
+ * (a path needs no normaliser), so that is all the cache keeps.  c == NULL: nothing outlives the
+ * step.  Outputs: rep[U], inverse[N]; h_out[U][H] in group order;
+ *   score[n][k] = log p(query[n][k] | history n) - base_score[n][k];
+ * step_stats = {distinct, found in cache, computed, entries afterwards}.
+ * Returns the number of distinct histories, -1 on a word id outside [0, V), -2 without memory.
+ */
+int oracle_hs_step_cached(oracle_cache *c, int V, int H, int N, int K,
+                          const float *U, const float *W, const float *theta,
+                          const int32_t *path_off, const int32_t *path_entry,
+                          const uint64_t *ids, const int32_t *prev, const float *h_in,
+                          const int32_t *query, const float *base_score,
+                          int32_t *rep, int32_t *inverse, double *h_out, double *score, int32_t step_stats[4])
+{
+    if (c && c->H != H) return -1;
+    for (int n = 0; n < N; ++n) {
+        if (prev[n] < 0 || prev[n] >= V) return -1;
+        for (int k = 0; k < K; ++k)
+            if (query[(size_t)n * K + k] < 0 || query[(size_t)n * K + k] >= V) return -1;
+    }
+    int nu = 0, nhit = 0, nmiss = 0;
+    for (int n = 0; n < N; ++n) {
+        int u = -1;
+        for (int t = 0; t < nu; ++t)                      /* met earlier in this step? */
+            if (ids[rep[t]] == ids[n]) { u = t; break; }
+        if (u < 0) {
+            u = nu++;
+            rep[u] = n;
+            int e = -1;
+            if (c)
+                for (int i = 0; i < c->count; ++i)
+                    if (c->keys[i] == ids[n]) { e = i; break; }
+            double *h = h_out + (size_t)u * H;
+            if (e >= 0) {                                  /* "Cache[I] exists": the stored context, whatever prev / h_in say now */
+                ++nhit;
+                for (int j = 0; j < H; ++j) h[j] = c->h[(size_t)e * H + j];
+            } else {                                       /* ComputeRnnlm, then store while there is room */
+                ++nmiss;
+                hidden_row(H, U + (size_t)prev[n] * H, W, h_in + (size_t)n * H, h);
+                if (c) {
+                    if (c->count < c->capacity) {
+                        int slot = c->count++;
+                        c->keys[slot] = ids[n];
+                        for (int j = 0; j < H; ++j) c->h[(size_t)slot * H + j] = h[j];
+                        c->lse[slot] = 0.0;
+                    } else {
+                        ++c->unstored;
+                    }
+                }
+            }
+        }
+        inverse[n] = u;
+    }
+    if (c) { c->lookups += nu; c->hits += nhit; c->misses += nmiss; }
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k) {
+            double p = hs_logp(H, theta, path_off, path_entry, query[(size_t)n * K + k], h_out + (size_t)inverse[n] * H);
+            if (base_score) p -= (double)base_score[(size_t)n * K + k];
+            score[(size_t)n * K + k] = p;
+        }
+    if (step_stats) {
+        step_stats[0] = nu; step_stats[1] = nhit; step_stats[2] = nmiss; step_stats[3] = c ? c->count : 0;
+    }
+    return nu;
+}
+
 int oracle_max_threads(void)
 {
 #ifdef _OPENMP

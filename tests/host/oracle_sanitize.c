@@ -37,6 +37,11 @@ int oracle_hs_step(int V, int H, int B, int K, int N, const float *U, const floa
                    const int32_t *path_off, const int32_t *path_entry, const int32_t *prev,
                    const float *h_in, const int32_t *query, const int32_t *row_of_query, double *h_out,
                    double *logprob, double *full_logp, int num_threads);
+int oracle_hs_step_cached(oracle_cache *c, int V, int H, int N, int K, const float *U, const float *W,
+                          const float *theta, const int32_t *path_off, const int32_t *path_entry,
+                          const uint64_t *ids, const int32_t *prev, const float *h_in, const int32_t *query,
+                          const float *base_score, int32_t *rep, int32_t *inverse, double *h_out, double *score,
+                          int32_t step_stats[4]);
 int oracle_max_threads(void);
 
 #define CHECK(cond)                                               \
@@ -172,6 +177,22 @@ static void tree_case(int V, int H, int B, int K, int kind)
         double total = 0;
         for (int v = 0; v < V; ++v) total += exp(full[(size_t)b * V + v]);
         CHECK(fabs(total - 1.0) < 1e-9);
+    }
+    /* the same rows as raw queries through a cache that fills up (ids repeat: b / 2) */
+    {
+        oracle_cache *c = oracle_cache_new(H, 1);
+        uint64_t *ids = (uint64_t *)malloc((size_t)B * sizeof(uint64_t));
+        for (int b = 0; b < B; ++b) ids[b] = 77u + (uint64_t)(b / 2);
+        int32_t *rep = (int32_t *)malloc((size_t)B * sizeof(int32_t)), *inv = (int32_t *)malloc((size_t)B * sizeof(int32_t));
+        double *h2 = doubles((size_t)B * H), *score = doubles((size_t)B * K);
+        int32_t stats[4];
+        for (int pass = 0; pass < 2; ++pass) {
+            int nu = oracle_hs_step_cached(pass ? c : NULL, V, H, B, K, U, W, theta, off, entry, ids, prev, h_in, query, NULL,
+                                           rep, inv, h2, score, stats);
+            CHECK(nu == (B + 1) / 2 && stats[0] == nu && stats[3] == (pass ? 1 : 0));
+        }
+        oracle_cache_free(c);
+        free(ids); free(rep); free(inv); free(h2); free(score);
     }
     freq[0] = -1.0;
     CHECK(oracle_huffman_build(V, freq, off, entry, need) == -1);

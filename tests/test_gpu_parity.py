@@ -355,7 +355,7 @@ def test_dedup_bit_exact(N, distinct):
     Uo, repo, invo = oracle.dedup(keys) if N <= 5000 else None_or_numpy(keys)
     assert U == Uo
     assert np.array_equal(rep, repo) and np.array_equal(inv, invo)
-    for _ in range(5):                                    # run-to-run identical
+    for _ in range(100 if N <= 100000 else 20):           # run-to-run identical (the order never comes from a race)
         U2, rep2, inv2 = gpu_dedup(keys)
         assert U2 == U and np.array_equal(rep2, rep) and np.array_equal(inv2, inv)
 

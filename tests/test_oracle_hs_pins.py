@@ -213,3 +213,94 @@ def test_extreme_activations_stay_finite():
     m["theta"] *= 400.0
     out = oracle.hs_step(m, [1], [[0.3, 0.3, 0.3]], np.arange(9, dtype=np.int32)[None, :], want_full=True)
     assert np.all(np.isfinite(out["logprob"])) and np.exp(out["full_logp"]).sum() == pytest.approx(1.0, abs=1e-12)
+
+
+# ------------------------------------------------------------------ through the cache (Table 1 around Section 2.1)
+def numpy_path_logp(model, h, word):
+    """log p(word | h) from numpy: the product of sigmoids along the word's path."""
+    off, entry = model["path_off"], model["path_entry"].view(np.uint32)
+    lp = 0.0
+    for e in entry[off[word]:off[word + 1]]:
+        x = float(model["theta"][int(e & 0x7FFFFFFF)].astype(np.float64) @ h)
+        lp += -np.logaddexp(0.0, x if (e >> 31) else -x)
+    return lp
+
+
+def cached_case(rng, V, H, N, K, pool):
+    freq = rng.zipf(1.3, V).astype(np.float64)
+    off, entry = oracle.huffman_build(freq)
+    model = {"U": rng.normal(0, 0.3, (V, H)).astype(np.float32), "W": rng.normal(0, 0.3, (H, H)).astype(np.float32),
+             "theta": rng.normal(0, 0.6, (V - 1, H)).astype(np.float32), "path_off": off, "path_entry": entry}
+    ids = rng.choice(pool, size=N).astype(np.uint64)
+    by_id, prev, h_in = {}, np.zeros(N, np.int32), np.zeros((N, H), np.float32)
+    for n in range(N):
+        if int(ids[n]) not in by_id:
+            by_id[int(ids[n])] = (rng.integers(0, V), rng.uniform(0, 1, H).astype(np.float32))
+        prev[n], h_in[n] = by_id[int(ids[n])]
+    return model, ids, prev, h_in, rng.integers(0, V, (N, K)).astype(np.int32)
+
+
+@pytest.mark.parametrize("cache_kind", ["none", "capacity0", "empty"])
+def test_cached_step_without_stored_entries_is_grouping_plus_plain_step(cache_kind):
+    rng = np.random.default_rng(5)
+    V, H, N, K = 61, 9, 30, 4
+    model, ids, prev, h_in, query = cached_case(rng, V, H, N, K, np.arange(500, 511, dtype=np.uint64))
+    cache = {"none": None, "capacity0": oracle.Cache(H, 0), "empty": oracle.Cache(H, 64)}[cache_kind]
+    got = oracle.hs_step_cached(model, cache, ids, prev, h_in, query)
+    U_, rep, inverse = oracle.dedup(ids)
+    ref = oracle.hs_step(model, prev[rep], h_in[rep], query, row_of_query=inverse)
+    assert got["n_unique"] == U_ and np.array_equal(got["rep"], rep) and np.array_equal(got["inverse"], inverse)
+    assert np.array_equal(got["h_out"], ref["h_out"]) and np.array_equal(got["score"], ref["logprob"])
+    stored = {"none": 0, "capacity0": 0, "empty": U_}[cache_kind]
+    assert got["stats"] == (U_, 0, U_, stored)
+
+
+def test_cached_step_answers_a_known_history_from_the_store_and_subtracts_the_base_score():
+    """Second step: half of the ids are known and arrive with DIFFERENT prev / h_in (the stored context
+    must win), the others are new; a bounded cache keeps what fits, in order of first appearance."""
+    rng = np.random.default_rng(6)
+    V, H, N, K = 47, 7, 24, 3
+    model, ids1, prev1, h1, q1 = cached_case(rng, V, H, N, K, np.arange(100, 108, dtype=np.uint64))
+    cache = oracle.Cache(H, 10)
+    first = oracle.hs_step_cached(model, cache, ids1, prev1, h1, q1)
+    known = {int(ids1[first["rep"][u]]): first["h_out"][u] for u in range(first["n_unique"])}
+    assert first["stats"] == (len(known), 0, len(known), len(known))
+    _, ids2, prev2, h2, q2 = cached_case(rng, V, H, N, K, np.arange(104, 116, dtype=np.uint64))
+    base = rng.normal(0, 1, (N, K)).astype(np.float32)
+    second = oracle.hs_step_cached(model, cache, ids2, prev2, h2, q2, base_score=base)
+    hits = misses = 0
+    entries = len(known)
+    for u in range(second["n_unique"]):
+        n = int(second["rep"][u])
+        key = int(ids2[n])
+        if key in known:
+            hits += 1
+            assert np.array_equal(second["h_out"][u], known[key])          # the stored bits, not a recomputation
+        else:
+            misses += 1
+            expect = scipy.special.expit(model["U"][prev2[n]].astype(np.float64)
+                                         + model["W"].astype(np.float64) @ h2[n].astype(np.float64))
+            assert np.allclose(second["h_out"][u], expect, rtol=0, atol=1e-14)
+            entries = min(entries + 1, 10)
+    assert hits > 0 and misses > 0
+    assert second["stats"] == (hits + misses, hits, misses, entries)
+    for n in range(N):
+        h = second["h_out"][second["inverse"][n]]
+        for k in range(K):
+            want = numpy_path_logp(model, h, int(q2[n, k])) - float(base[n, k])
+            assert abs(second["score"][n, k] - want) <= 1e-12
+    # every history the cache kept answers a third step without being computed
+    third = oracle.hs_step_cached(model, cache, ids2, prev2, h2, q2)
+    assert third["stats"][1] >= hits and third["stats"][3] == entries
+    assert third["stats"][1] + third["stats"][2] == third["stats"][0]
+
+
+def test_cached_step_still_gives_a_distribution_over_the_words():
+    rng = np.random.default_rng(8)
+    V, H = 23, 5
+    model, ids, prev, h_in, _ = cached_case(rng, V, H, 6, 1, np.arange(3, dtype=np.uint64))
+    query = np.tile(np.arange(V, dtype=np.int32), (6, 1))
+    cache = oracle.Cache(H, 2)
+    for _ in range(2):                                                       # computed, then (partly) from the store
+        got = oracle.hs_step_cached(model, cache, ids, prev, h_in, query)
+        assert np.allclose(np.exp(got["score"]).sum(axis=1), 1.0, rtol=0, atol=1e-12)
