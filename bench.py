@@ -78,7 +78,7 @@ def bench_hs(args, cfg, rn, torch, np) -> int:
     dev = "cuda:0"
     bf16 = cfg.dtype == "bf16"
     model = make_model(cfg)
-    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed))
+    x = make_step_inputs(cfg, np.random.default_rng(cfg.seed)) if cfg.unique_frac is None else None
     V, H, N, K = cfg.V, cfg.H, cfg.N, cfg.K
     freq = np.arange(1, V + 1, dtype=np.float64) ** -(cfg.zipf_s or 0.0)
     off, entry = rn.rnnlm_huffman_build(freq)
@@ -89,6 +89,8 @@ def bench_hs(args, cfg, rn, torch, np) -> int:
                              entry, N)
     else:
         m = rn.rnnlm_hs_load(V, H, rn.RNNLM_F32, model["U"], model["W"], theta, off, entry, N)
+    if args.cache is not None:
+        return bench_hs_cached(args, cfg, m, rn, torch, np)
     prev = torch.from_numpy(x["prev"]).to(dev)
     h_in = torch.from_numpy(x["h_in"]).to(dev)
     query = torch.from_numpy(x["query"]).to(dev)
@@ -158,6 +160,78 @@ def bench_hs(args, cfg, rn, torch, np) -> int:
                                 "served by L2)"},
            "cpu_baseline": cpu}
     print(json.dumps(out))
+    m.close()
+    return 0
+
+
+def bench_hs_cached(args, cfg, m, rn, torch, np) -> int:
+    """The paper's whole RnnlmProb (Table 1): a decode trace of raw queries through the cache kept between
+    steps, scored with the hierarchical output layer (rnnlm_step_cached on a model loaded with
+    rnnlm_hs_load).  A "step" of the timed loop is a pass over the whole trace (one utterance: the cache is
+    reset at its start); reported per step of the trace, beside the same trace without the cache."""
+    from workloads import DecodeTrace
+    if cfg.unique_frac is None:
+        print("bench.py: --cache needs the decode-trace workload (--config 4)", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    N, K, H = cfg.N, cfg.K, cfg.H
+    rep = torch.empty(N, dtype=torch.int32, device=dev)
+    inv = torch.empty(N, dtype=torch.int32, device=dev)
+    nu = torch.zeros(1, dtype=torch.int32, device=dev)
+    h_out = torch.zeros((N, H), device=dev)
+    lp = torch.zeros((N, K), device=dev)
+    ws = torch.empty(rn.rnnlm_dedup_workspace_bytes(N), dtype=torch.uint8, device=dev)
+    tr = DecodeTrace(cfg, carry_frac=args.carry_frac)
+    xt, trace = tr.first(), []
+    for _ in range(args.trace_steps):               # built once, untimed: step t+1 grows from what step t returned
+        dev_in = tuple(torch.from_numpy(a).to(dev) for a in (xt["keys"].view(np.int64), xt["prev"], xt["h_in"], xt["query"]))
+        rn.rnnlm_step_dedup(m, *dev_in, rep, inv, nu, h_out, lp, ws)
+        torch.cuda.synchronize()
+        trace.append(dev_in)
+        xt = tr.next(xt, h_out.cpu().numpy(), inv.cpu().numpy())
+    cache = rn.rnnlm_cache_create(m, args.cache)
+    stats = torch.zeros(4, dtype=torch.int32, device=dev)
+
+    def cached_pass():
+        cache.reset()
+        for dev_in in trace:
+            rn.rnnlm_step_cached(m, cache, *dev_in, rep, inv, nu, h_out, lp, ws, step_stats=stats)
+
+    def uncached_pass():
+        for dev_in in trace:
+            rn.rnnlm_step_dedup(m, *dev_in, rep, inv, nu, h_out, lp, ws)
+
+    results = {}
+    for name, fn in (("uncached", uncached_pass), ("cached", cached_pass)):
+        for _ in range(max(args.warmup, 1)):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        rep_ms = timed_repetitions(fn, args.steps, time.perf_counter() - t0, torch)
+        results[name] = median(rep_ms) * 1e-3 / (args.steps * args.trace_steps)
+    st = cache.stats()
+    assert m.last_error() == 0
+    out = {"metric": "RNNLM hypothesis-steps/sec, hierarchical output layer through the cache (V=%d,H=%d,N=%d)" % (cfg.V, H, N),
+           "value": round(N / results["cached"], 1), "unit": "hypothesis-steps/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(results["cached"] * 1e3, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+           "config": {"workload": "%s with the hierarchical output layer through the cache: V=%d H=%d N=%d raw queries "
+                                  "(%d distinct histories per step, %.0f %% of them kept from step to step) K=%d, trace of "
+                                  "%d steps, cache reset at its start"
+                                  % (cfg.name, cfg.V, H, N, tr.U0, 100 * args.carry_frac, K, args.trace_steps)},
+           "timing": {"method": "median of event-bracketed repetitions of %d passes over the trace" % args.steps},
+           "roofline": None, "cpu_baseline": None,
+           "cache": {"capacity": args.cache, "trace_steps": args.trace_steps, "carry_frac": args.carry_frac,
+                     "uncached_value": round(N / results["uncached"], 1),
+                     "uncached_ms_per_step": round(results["uncached"] * 1e3, 4),
+                     "hit_ratio": round(st["hits"] / max(st["lookups"], 1), 4), "entries": st["entries"],
+                     "note": "value = raw queries / s over the trace through the cache; hit_ratio over distinct "
+                             "histories per step; uncached_value = same trace without the cache"}}
+    print(json.dumps(out))
+    cache.close()
     m.close()
     return 0
 
@@ -303,9 +377,9 @@ def main() -> int:
     if args.index_table:
         return bench_index_table(args, cfg, rn, torch, np)
     if args.hs:
-        if cfg.unique_frac is not None:
-            print("bench.py: --hs times one row per raw query (workloads 1, 2, 3, 5); the decode-trace "
-                  "workload repeats histories and is timed with the full softmax only", file=sys.stderr)
+        if (cfg.unique_frac is not None) != (args.cache is not None):
+            print("bench.py: --hs times one row per raw query (workloads 1, 2, 3, 5, 6), or with --cache the "
+                  "decode-trace workload (--config 4) through the cache", file=sys.stderr)
             return 2
         return bench_hs(args, cfg, rn, torch, np)
     bf16 = cfg.dtype == "bf16"

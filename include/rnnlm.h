@@ -195,7 +195,7 @@ int rnnlm_step(const rnnlm_model *model, int B, int K,
  *   h_out         dev f32[N][H]   out: row u < *n_unique = updated hidden vector of the
  *                                 u-th distinct history; rows beyond are left untouched
  *   logprob       dev f32[N][K]   out
- * Requires N <= max_B.
+ * Requires N <= max_B.  Either kind of model (full softmax or hierarchical output layer).
  */
 int rnnlm_step_dedup(const rnnlm_model *model, int N, int K,
                      const uint64_t *history_ids, const int32_t *prev_word, const float *h_in,
@@ -263,7 +263,12 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache_or_null, int 
  *     log p(w | h') = sum over the path nodes i of log sigmoid(+-theta_i . h'),
  * + for code bit 0, - for code bit 1: about log2 V dot products per queried word, no
  * whole-vocabulary normalisation.  A model loaded with rnnlm_hs_load is stepped with
- * rnnlm_hs_step (and refused by the full-softmax entry points, and the other way round).
+ * rnnlm_hs_step on rows the caller has made distinct (rnnlm_step refuses it, and rnnlm_hs_step a
+ * full-softmax model), or, like any model, with rnnlm_step_dedup / rnnlm_step_cached on raw
+ * queries: grouping of the history ids, the cache of Table 1 -- which for such a model keeps the
+ * hidden vector of a history and nothing else, a path needs no normaliser -- and the paths of
+ * the queried words in one call.  That is the paper's RnnlmProb as a whole: its cache around
+ * its own output layer.
  */
 
 /* Huffman tree over V >= 2 words from their frequencies (HOST arrays, host code): the path of

@@ -438,7 +438,7 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
                       const float *base_score, int32_t *rep, int32_t *inverse, int32_t *n_unique, float *h_out,
                       float *score, int32_t *step_stats, void *workspace, size_t workspace_bytes,
                       void *hip_stream) {
-    int rc = check_step_args(model, N, K, N);
+    int rc = check_step_args(model, N, K, N, model ? model->dev.hs : 0);   // either kind of model
     if (rc != RNNLM_OK) return rc;
     if (!n_unique) return RNNLM_EINVAL;
     if (N > 0 && (!history_ids || !prev_word || !h_in || !rep || !inverse || !h_out)) return RNNLM_EINVAL;
@@ -464,6 +464,11 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
         // Grids cover N rows; the kernels read the true number of rows from *n_unique.
         if (launch_recur(recur_view(model, N), N, n_unique, rep, nullptr, prev_word, h_in, h_out, s) != hipSuccess)
             return RNNLM_EDEVICE;
+        if (d.hs) {                                         // hierarchical output layer: paths instead of the normaliser
+            if (launch_hs_query(d, N, n_unique, N, K, query_word, inverse, h_out, base_score, score, s) != hipSuccess)
+                return RNNLM_EDEVICE;
+            return RNNLM_OK;
+        }
         if (launch_outproj(d, N, n_unique, use_fixed_offset(model), model->outproj_kernel, &splits, s) !=
             hipSuccess)
             return RNNLM_EDEVICE;
@@ -481,6 +486,15 @@ int rnnlm_step_cached(const rnnlm_model *model, rnnlm_cache *cache, int N, int K
     // from raw query c.miss_src[r], its hidden vector written to row c.miss_dst[r] of h_out.
     if (launch_recur(recur_view(model, N), N, c.n_miss, c.miss_src, c.miss_dst, prev_word, h_in, h_out, s) != hipSuccess)
         return RNNLM_EDEVICE;
+    if (d.hs) {
+        // Hierarchical output layer: what the cache keeps of a history is its hidden vector.  The
+        // bookkeeping launch (stored vectors out to h_out, new ones in) leaves every distinct history's
+        // vector in h_out; the path kernel then reads them there.
+        if (launch_cache_commit(c, d, N, n_unique, splits, h_out, s) != hipSuccess) return RNNLM_EDEVICE;
+        if (launch_hs_query(d, N, n_unique, N, K, query_word, inverse, h_out, base_score, score, s) != hipSuccess)
+            return RNNLM_EDEVICE;
+        return RNNLM_OK;
+    }
     if (launch_outproj(d, N, c.n_miss, use_fixed_offset(model), model->outproj_kernel, &splits, s) != hipSuccess)
         return RNNLM_EDEVICE;
     // With words to score, the query kernel also does the cache's bookkeeping after the computation

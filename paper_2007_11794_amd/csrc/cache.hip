@@ -293,7 +293,8 @@ __global__ __launch_bounds__(256) void cache_commit_kernel(CacheDev c, ModelDev 
     float *hrow = h_out + (size_t)u * H;
     if (row >= 0) {
         // computed in this step: its partials are in row `row` of the block of *n_miss rows
-        if (wave == 0) {
+        // (a model with the hierarchical output layer has no normaliser: the hidden vector is all)
+        if (wave == 0 && !m.hs) {
             const int splits = splits_of(si, *c.n_miss);
             const float lse = lse_from_partials(m.part + (size_t)row * kMaxSplits, splits, lane);
             if (lane == 0) {
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(256) void cache_commit_kernel(CacheDev c, ModelDev 
     } else {
         const float *src = c.store_h + (size_t)entry * H;
         for (int j = threadIdx.x; j < H; j += 256) hrow[j] = src[j];
-        if (threadIdx.x == 0) c.lse_rows[u] = c.store_lse[entry];
+        if (threadIdx.x == 0 && !m.hs) c.lse_rows[u] = c.store_lse[entry];
     }
 }
 

@@ -186,3 +186,58 @@ def test_hs_awkward_shapes(i, dtype, V, H, B, K):
     assert dh <= TOL[dtype][1] and dlp <= TOL[dtype][0], (i, dtype, V, H, B, K, dh, dlp, int(np.diff(m["path_off"]).max()))
     assert mod.last_error() == 0
     mod.close()
+
+
+# ------------------------------------------------------------------------ the paper's whole RnnlmProb: cache + hierarchical layer
+@pytest.mark.parametrize("dtype,V,H,K", [("bf16", 8200, 256, 5), ("bf16", 4099, 160, 2), ("f32", 3001, 96, 9),
+                                         ("bf16", 5000, 100, 16)])
+@pytest.mark.parametrize("capacity", [100000, 150, 0, None])
+def test_hs_steps_through_the_cache_match_the_oracle(dtype, V, H, K, capacity):
+    """Table 1 around the output layer of Section 2.1 (rnnlm_step_cached on a model loaded with
+    rnnlm_hs_load; capacity None: rnnlm_step_dedup's case, nothing outlives the step).  Grouping and the
+    hit / computed / stored counts bit-exact, values within the step's tolerances, and a history
+    answered from the cache carries the hidden vector first computed, bit for bit."""
+    from harness import CachedStepper
+    rng = np.random.default_rng(V + H + (capacity or 7))
+    m = hs_model(rng, V, H, dtype, 0.05)
+    mod = load(m, dtype, 700)
+    cache = rn.rnnlm_cache_create(mod, capacity) if capacity is not None else None
+    ocache = oracle.Cache(H, capacity) if capacity is not None else None
+    pool = (np.arange(400, dtype=np.uint64) << np.uint64(32)) | np.uint64(0x1234)
+    pool[3] = np.uint64(0xFFFFFFFFFFFFFFFF)
+    st = CachedStepper(mod, cache, 700, K)
+    seen = {}
+    for step, N in enumerate([300, 700, 64, 1, 513]):
+        ids = rng.choice(pool, size=N).astype(np.uint64)
+        prev = rng.integers(0, V, N).astype(np.int32)
+        h_in = rng.uniform(0, 1, (N, H)).astype(np.float32)
+        first = {}
+        for n in range(N):                       # rows of one id agree within a step
+            f = first.setdefault(int(ids[n]), n)
+            prev[n], h_in[n] = prev[f], h_in[f]
+        query = rng.integers(0, V, (N, K)).astype(np.int32)
+        base = rng.normal(-6, 2, (N, K)).astype(np.float32) if step % 2 == 0 else None
+        out = st.step(ids, prev, h_in, query, base)
+        ref = oracle.hs_step_cached(m, ocache, ids, prev, h_in, query, base_score=base)
+        what = "hs cached %s V=%d H=%d K=%d cap=%s step %d" % (dtype, V, H, K, capacity, step)
+        assert out["n_unique"] == ref["n_unique"], what
+        assert np.array_equal(out["rep"], ref["rep"]) and np.array_equal(out["inverse"], ref["inverse"]), what
+        if capacity is not None:
+            assert out["stats"] == ref["stats"], (what, out["stats"], ref["stats"])
+        assert np.all(np.isnan(out["h_out_rest"])), what
+        dh = np.max(np.abs(out["h_out"].astype(np.float64) - ref["h_out"]))
+        ds = np.max(np.abs(out["score"].astype(np.float64) - ref["score"]))
+        print("%s stats=%s max|dh|=%.3g max|dscore|=%.3g" % (what, out["stats"], dh, ds), flush=True)
+        assert dh <= TOL[dtype][1] and ds <= TOL[dtype][0], (what, dh, ds)
+        if capacity == 100000:                   # everything is kept: a known history returns the same bits
+            for u in range(out["n_unique"]):
+                key = int(ids[out["rep"][u]])
+                if key in seen:
+                    assert np.array_equal(out["h_out"][u], seen[key]), what
+                else:
+                    seen[key] = out["h_out"][u].copy()
+    if cache is not None:
+        assert cache.stats() == ocache.stats()
+        cache.close()
+    assert mod.last_error() == 0
+    mod.close()
