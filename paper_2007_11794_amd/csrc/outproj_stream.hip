@@ -11,7 +11,7 @@
 //     of a wave = 32 words x 16 units = 1 KB contiguous), so every load instruction of a wave
 //     is one fully coalesced kilobyte straight into the registers the MFMA reads: no LDS
 //     round trip, no barrier, no partial cache lines;
-//   - a wave owns whole 32-word blocks and keeps a ring of kRing groups of kGroup operands in
+//   - a wave owns whole 32-word blocks and keeps a ring of kStreamRing groups of kGroup operands in
 //     flight (16 KB per wave, 128 KB per CU with 8 waves, 32 MB over the chip: more than
 //     bandwidth x latency of HBM), waves never synchronise inside the loop;
 //   - the hidden block (<= 32 RB rows, times log2 e, already in operand order) sits in LDS and is
@@ -27,8 +27,6 @@ namespace rnnlm {
 namespace {
 
 constexpr int kThreads = kStreamThreads;
-constexpr int kWaves = kStreamWaves;
-constexpr int kRing = kStreamRing;
 typedef StreamCursor Cursor;
 
 template <int RB, bool FIXED>
