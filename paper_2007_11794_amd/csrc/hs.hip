@@ -95,17 +95,27 @@ __global__ __launch_bounds__(256) void hs_query_kernel(
 // unit -- the kernel is a chain of dependent loads and lives on occupancy), computes one dot product per distinct
 // node, and only then adds up log sigmoid along each path.  At the headline shape (K = 32, Zipf
 // words) that is 163 instead of 304 node vectors per query.
-constexpr int kHsMaxEntries = 1024;                  // path entries of one raw query (all K words)
-constexpr int kHsTable = 2048;                       // slots of the node table (at most half full)
-constexpr int kHsMaxK = 256;
-constexpr int kHsThreads = 256;
+// Two sizes of the workgroup of a raw query: up to 1024 path entries (all K words together) with 256
+// threads, and up to 256 entries with 128 threads -- few words per query (a search step that extends
+// every hypothesis by a handful of words): a third of the LDS, twice the queries in flight per
+// compute unit, and the kernel lives on how many chains of dependent loads are in flight.
+template <int THREADS, int LOG2_TABLE, int MAX_ENTRIES, int MAX_K>
+struct HsShape {
+    static constexpr int kThreads = THREADS;
+    static constexpr int kLog2Table = LOG2_TABLE, kTable = 1 << LOG2_TABLE;   // slots of the node table (at most half full)
+    static constexpr int kMaxEntries = MAX_ENTRIES;                          // path entries of one raw query
+    static constexpr int kMaxK = MAX_K;
+    static_assert(kTable >= 2 * MAX_ENTRIES && kTable <= 32768 && MAX_ENTRIES % THREADS == 0, "");
+};
+typedef HsShape<256, 11, 1024, 256> HsLarge;
+typedef HsShape<128, 9, 256, 64> HsSmall;
 
 // Dot products of the distinct nodes for a short hidden vector (Hp = 8 * LPR elements, LPR = 16 or
 // 32): a node row takes only LPR lanes of a wave, so the wave works on 64 / LPR rows side by side,
 // eight per lane group in flight: 32 (16) rows per wave and round trip to memory instead of 8.  Lane
 // group g of wave w takes the nodes d = first + g + G * u, u = 0..7; the eight sums of a group are
 // reduced together (a lane passes on the half it will not finish, as in wave_sum8).
-template <typename T, int LPR>
+template <typename T, int LPR, int THREADS>
 __device__ __forceinline__ void hs_dots_short_rows(const T *Theta, const float *hrow, int H, int Hp, bool vec_ok,
                                                    const int *dnode, float *dx, int D, int wave, int lane) {
     static_assert(LPR == 16 || LPR == 32, "");
@@ -146,7 +156,7 @@ __device__ __forceinline__ void hs_dots_short_rows(const T *Theta, const float *
         if (writer && d < D) dx[d] = v;
     };
     // two batches on their way at a time (the second may lie past the end: its loads fetch node 0)
-    constexpr int stride = (kHsThreads / 64) * kPerWave;
+    constexpr int stride = (THREADS / 64) * kPerWave;
     for (int first = wave * kPerWave; first < D; first += 2 * stride) {
         float wa[kHsBatch][8], wb[kHsBatch][8];
         fetch(first, wa);
@@ -158,21 +168,22 @@ __device__ __forceinline__ void hs_dots_short_rows(const T *Theta, const float *
 
 // LPR: lanes per node row of the short-row form (16: Hp = 128, 32: Hp = 256), 0: any hidden size.
 // Kernels of their own, so that the registers of the short-row form do not cost the general one occupancy.
-template <typename T, int LPR>
-__global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
+template <typename T, int LPR, class S>
+__global__ __launch_bounds__(S::kThreads) void hs_query_shared_kernel(
     ModelDev m, int rows, const int *__restrict__ B_dev, int N, int K,
     const int32_t *__restrict__ query_word, const int32_t *__restrict__ row_of_query,
     const float *__restrict__ h_out, const float *__restrict__ base_score, float *__restrict__ logprob) {
-    __shared__ int wbase[kHsMaxK + 1];               // start of word k's entries
-    __shared__ int woff[kHsMaxK];                    // where word k's path starts in the model's entries
-    __shared__ uint16_t eslot[kHsMaxEntries];        // entry -> table slot of its node | code bit << 15
-    __shared__ int tnode[kHsTable];                  // hash table: node (-1 free)
-    __shared__ uint16_t tidx[kHsTable];              // slot -> index of its node among the distinct ones
-    __shared__ int dnode[kHsMaxEntries];             // the distinct nodes
-    __shared__ float dx[kHsMaxEntries];              // their dot products
+    __shared__ int wbase[S::kMaxK + 1];               // start of word k's entries
+    __shared__ int woff[S::kMaxK];                    // where word k's path starts in the model's entries
+    __shared__ uint16_t eslot[S::kMaxEntries];        // entry -> table slot of its node | code bit << 15
+    __shared__ int tnode[S::kTable];                  // hash table: node (-1 free)
+    __shared__ uint16_t tidx[S::kTable];              // slot -> index of its node among the distinct ones
+    __shared__ int dnode[S::kMaxEntries];             // the distinct nodes
+    __shared__ float dx[S::kMaxEntries];              // their dot products
     __shared__ int dcount;
-    __shared__ int wsum[kHsThreads / 64 + 1];
-    static_assert(kHsTable <= 32768, "slot index and code bit share sixteen bits");
+    __shared__ int wsum[S::kThreads / 64 + 1];
+    static_assert(S::kTable <= 32768, "slot index and code bit share sixteen bits");
+    static_assert(S::kMaxK <= S::kThreads, "one word per thread in step 1");
     const int B = B_dev ? *B_dev : rows;
     const int n = blockIdx.x;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -189,7 +200,7 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
         len = m.path_off[q + 1] - o;
         woff[tid] = o;
     }
-    for (int i = tid; i < kHsTable; i += kHsThreads) tnode[i] = -1;
+    for (int i = tid; i < S::kTable; i += S::kThreads) tnode[i] = -1;
     if (tid == 0) dcount = 0;
     int total;
     const int mybase = block_exclusive_scan(len, wsum, total);      // barriers inside
@@ -199,11 +210,11 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     // 2. distinct nodes (a thread per path entry, all entries of a thread requested before the first
     //    is used: one round trip to memory for the whole query): the thread whose insertion claims
     //    a slot numbers the node; every entry remembers its slot and its code bit
-    constexpr int kPerThread = kHsMaxEntries / kHsThreads;
+    constexpr int kPerThread = S::kMaxEntries / S::kThreads;
     uint32_t entry[kPerThread];
 #pragma unroll
     for (int c = 0; c < kPerThread; ++c) {
-        const int e = tid + c * kHsThreads;
+        const int e = tid + c * S::kThreads;
         entry[c] = 0u;
         if (e < total) {
             int lo = 0, hi = K;                                      // the word k with wbase[k] <= e < wbase[k + 1]
@@ -216,11 +227,11 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     }
 #pragma unroll
     for (int c = 0; c < kPerThread; ++c) {
-        const int e = tid + c * kHsThreads;
+        const int e = tid + c * S::kThreads;
         if (e < total) {
             const int node = (int)(entry[c] & 0x7FFFFFFFu);
-            uint32_t h = (uint32_t)(node * 0x9E3779B1u) >> 21;       // 11 bits
-            for (int probe = 0; probe < kHsTable; ++probe) {
+            uint32_t h = (uint32_t)(node * 0x9E3779B1u) >> (32 - S::kLog2Table);
+            for (int probe = 0; probe < S::kTable; ++probe) {
                 const int old = atomicCAS(&tnode[h], -1, node);
                 if (old == -1) {
                     const int d = atomicAdd(&dcount, 1);
@@ -229,7 +240,7 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
                     break;
                 }
                 if (old == node) break;
-                h = (h + 1) & (kHsTable - 1);
+                h = (h + 1) & (S::kTable - 1);
             }
             eslot[e] = (uint16_t)(h | ((entry[c] >> 31) << 15));
         }
@@ -241,9 +252,9 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     const float *hrow = h_out + (size_t)r * H;
     const bool vec_ok = (H % 4) == 0;
     const int umine = batch_slot_of_lane(lane);
-    if constexpr (LPR != 0) hs_dots_short_rows<T, LPR>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
+    if constexpr (LPR != 0) hs_dots_short_rows<T, LPR, S::kThreads>(Theta, hrow, H, Hp, vec_ok, dnode, dx, D, wave, lane);
     else
-    for (int d0 = wave * kHsBatch; d0 < D; d0 += (kHsThreads / 64) * kHsBatch) {
+    for (int d0 = wave * kHsBatch; d0 < D; d0 += (S::kThreads / 64) * kHsBatch) {
         const int node_mine = (d0 + umine < D) ? dnode[d0 + umine] : 0;
         int node[kHsBatch];
 #pragma unroll
@@ -269,10 +280,10 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
     // 4. log sigmoid of every path entry (a thread per entry; the terms go where the node table was,
     //    which nobody has probed since step 2), then eight lanes add up the terms of one word
     float *const eterm = reinterpret_cast<float *>(tnode);
-    static_assert(kHsMaxEntries <= kHsTable, "the terms fit the node table");
+    static_assert(S::kMaxEntries <= S::kTable, "the terms fit the node table");
 #pragma unroll
     for (int c = 0; c < kPerThread; ++c) {
-        const int e = tid + c * kHsThreads;
+        const int e = tid + c * S::kThreads;
         if (e < total) {
             const uint32_t es = eslot[e];
             const float x = dx[tidx[es & 0x7FFFu]];
@@ -280,7 +291,7 @@ __global__ __launch_bounds__(kHsThreads) void hs_query_shared_kernel(
         }
     }
     __syncthreads();
-    for (int k = tid >> 3; k < K; k += kHsThreads / 8) {
+    for (int k = tid >> 3; k < K; k += S::kThreads / 8) {
         const int b0 = wbase[k], b1 = wbase[k + 1];
         float t = 0.f;
         for (int e = b0 + (tid & 7); e < b1; e += 8) t += eterm[e];
@@ -307,21 +318,27 @@ hipError_t launch_hs_query(const ModelDev &m, int rows, const int *B_dev, int N,
                            const int32_t *query_word, const int32_t *row_of_query, const float *h_out,
                            const float *base_score, float *logprob, hipStream_t stream) {
     if (N <= 0 || K <= 0) return hipSuccess;
-    if (K >= 4 && K <= kHsMaxK && (long long)K * m.hs_max_len <= kHsMaxEntries) {
+    if (K >= 4 && K <= HsLarge::kMaxK && (long long)K * m.hs_max_len <= HsLarge::kMaxEntries) {
         // several words per query: one workgroup per raw query, shared path nodes computed once
-        auto launch = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, dim3(N), dim3(kHsThreads), 0, stream, m, rows, B_dev, N, K, query_word,
+        const bool small = K <= HsSmall::kMaxK && (long long)K * m.hs_max_len <= HsSmall::kMaxEntries;
+        auto launch = [&](auto kernel, int threads) {
+            hipLaunchKernelGGL(kernel, dim3(N), dim3(threads), 0, stream, m, rows, B_dev, N, K, query_word,
                                row_of_query, h_out, base_score, logprob);
         };
-        if (m.dtype == RNNLM_BF16) {
-            if (m.Hp == 128) launch(hs_query_shared_kernel<bf16_t, 16>);
-            else if (m.Hp == 256) launch(hs_query_shared_kernel<bf16_t, 32>);
-            else launch(hs_query_shared_kernel<bf16_t, 0>);
-        } else {
-            if (m.Hp == 128) launch(hs_query_shared_kernel<float, 16>);
-            else if (m.Hp == 256) launch(hs_query_shared_kernel<float, 32>);
-            else launch(hs_query_shared_kernel<float, 0>);
-        }
+        auto pick = [&](auto tag) {
+            using T = decltype(tag);
+            if (small) {
+                if (m.Hp == 128) launch(hs_query_shared_kernel<T, 16, HsSmall>, HsSmall::kThreads);
+                else if (m.Hp == 256) launch(hs_query_shared_kernel<T, 32, HsSmall>, HsSmall::kThreads);
+                else launch(hs_query_shared_kernel<T, 0, HsSmall>, HsSmall::kThreads);
+            } else {
+                if (m.Hp == 128) launch(hs_query_shared_kernel<T, 16, HsLarge>, HsLarge::kThreads);
+                else if (m.Hp == 256) launch(hs_query_shared_kernel<T, 32, HsLarge>, HsLarge::kThreads);
+                else launch(hs_query_shared_kernel<T, 0, HsLarge>, HsLarge::kThreads);
+            }
+        };
+        if (m.dtype == RNNLM_BF16) pick(bf16_t{});
+        else pick(float{});
         return hipGetLastError();
     }
     const long long pairs = (long long)N * K;
