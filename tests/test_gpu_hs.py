@@ -241,3 +241,35 @@ def test_hs_steps_through_the_cache_match_the_oracle(dtype, V, H, K, capacity):
         cache.close()
     assert mod.last_error() == 0
     mod.close()
+
+
+def test_hs_many_raw_queries_through_the_cache():
+    """More raw queries than one workgroup groups (grid-wide grouping and lookup), a cache that fills up."""
+    from harness import CachedStepper
+    rng = np.random.default_rng(99)
+    V, H, K = 2000, 64, 4
+    m = hs_model(rng, V, H, "bf16", 0.1)
+    mod = load(m, "bf16", 9000)
+    pool = rng.integers(0, 2 ** 64, 7000, dtype=np.uint64)
+    cache, ocache = rn.rnnlm_cache_create(mod, 3000), oracle.Cache(H, 3000)
+    st = CachedStepper(mod, cache, 9000, K)
+    for step, N in enumerate([6000, 9000, 4097]):
+        ids = rng.choice(pool, size=N).astype(np.uint64)
+        prev = rng.integers(0, V, N).astype(np.int32)
+        h_in = rng.uniform(0, 1, (N, H)).astype(np.float32)
+        first = {}
+        for n in range(N):
+            f = first.setdefault(int(ids[n]), n)
+            prev[n], h_in[n] = prev[f], h_in[f]
+        query = rng.integers(0, V, (N, K)).astype(np.int32)
+        out = st.step(ids, prev, h_in, query, None)
+        ref = oracle.hs_step_cached(m, ocache, ids, prev, h_in, query)
+        assert out["n_unique"] == ref["n_unique"] and out["stats"] == ref["stats"], (step, out["stats"], ref["stats"])
+        assert np.array_equal(out["rep"], ref["rep"]) and np.array_equal(out["inverse"], ref["inverse"])
+        dh = np.max(np.abs(out["h_out"].astype(np.float64) - ref["h_out"]))
+        ds = np.max(np.abs(out["score"].astype(np.float64) - ref["score"]))
+        print("hs cached N=%d stats=%s max|dh|=%.3g max|dscore|=%.3g" % (N, out["stats"], dh, ds), flush=True)
+        assert dh <= TOL["bf16"][1] and ds <= TOL["bf16"][0]
+    assert cache.stats() == ocache.stats() and mod.last_error() == 0
+    cache.close()
+    mod.close()
